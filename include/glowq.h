@@ -1,0 +1,153 @@
+/* glowq.h -- C ABI of the GlowQ group forward for AMD MI355X (gfx950).
+ *
+ * The library computes, for one input-sharing group of a decoder block (q/k/v;
+ * gate/up) or one solo module (o_proj, down_proj), the cache-and-reuse forward
+ * of GlowQ (paper Sec. 3.3):
+ *
+ *     R    = X B^T                          once per group          (Eq. 8)
+ *     Y_i  = X dequant(W_q,i)^T + R A_i^T   every module i          (Eq. 9)
+ *     Y_i  = X dequant(W_q,i)^T             unit not restored (GlowQ-S gating)
+ *
+ * Memory is token-major and dense: X[T][d_in], B[r][d_in], A_i[d_out][r],
+ * R[T][r], Y_i[T][ldy].  W_q,i is W4A16 storage (paper Sec. 4.1: INT4 weights,
+ * group size G along d_in, 16-bit activations): q in [0,15], one binary16 scale
+ * s and one integer-valued binary16 zero-point z per (row, group), and
+ * dequant = round_to_act((q - z) * s) with a single rounding.
+ *
+ * Conventions for every entry point
+ *  - Pointers marked DEVICE are HIP device pointers owned by the caller and
+ *    must stay valid until the stream has executed the call; pointers marked
+ *    HOST are read during the call only.  The library allocates nothing and
+ *    keeps no state between calls.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue work and return; they never synchronise the device.
+ *  - Every function returns a glowq_status; on any error nothing is enqueued.
+ *    Argument checking is host-side and touches no GPU.
+ *  - All DEVICE pointers must be 16-byte aligned.
+ */
+#ifndef GLOWQ_H
+#define GLOWQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GLOWQ_MAX_MODULES 8   /* modules per unit                               */
+#define GLOWQ_MAX_RANK 128    /* r in {0} u {8k : k >= 1, 8k <= 128}           */
+
+typedef enum {
+  GLOWQ_OK = 0,
+  GLOWQ_ERR_NULL = -1,        /* a required pointer is NULL                     */
+  GLOWQ_ERR_SHAPE = -2,       /* a size is out of range or inconsistent         */
+  GLOWQ_ERR_ALIGN = -3,       /* a device pointer or stride is misaligned       */
+  GLOWQ_ERR_DTYPE = -4,       /* unsupported activation / output type           */
+  GLOWQ_ERR_UNSUPPORTED = -5, /* valid request this build cannot serve          */
+  GLOWQ_ERR_WORKSPACE = -6,   /* workspace missing or too small                 */
+  GLOWQ_ERR_HIP = -7          /* a HIP runtime call failed                      */
+} glowq_status;
+
+typedef enum { GLOWQ_F16 = 0, GLOWQ_BF16 = 1, GLOWQ_F32 = 2 } glowq_dtype;
+
+/* One module (one linear map W_i of a unit). */
+typedef struct {
+  const void* w_prepared; /* DEVICE: output of glowq_prepare_weights for this module      */
+  const void* A;          /* DEVICE: act dtype [d_out][r]; may be NULL iff r == 0          */
+  void* Y;                /* DEVICE: out dtype [T][ldy]                                    */
+  int32_t d_out;          /* rows of W_i; multiple of 8                                    */
+  int32_t ldy;            /* row stride of Y in elements; >= d_out, multiple of 8          */
+} glowq_module;
+
+/* One unit of the restore policy (Sec. 3.3): an input-sharing group
+ * (n_modules > 1) or a solo module (n_modules == 1). */
+typedef struct {
+  const void* X;               /* DEVICE: act dtype [T][d_in]                              */
+  const void* B;               /* DEVICE: act dtype [r][d_in], shared by all modules;
+                                  may be NULL iff r == 0                                    */
+  const glowq_module* modules; /* HOST: n_modules descriptors                               */
+  int32_t n_modules;           /* 1 .. GLOWQ_MAX_MODULES                                    */
+  int32_t T;                   /* tokens (batch x time flattened), >= 1                     */
+  int32_t d_in;                /* shared input width; multiple of group_size                */
+  int32_t r;                   /* rank of the correction; 0 or a multiple of 8, <= 128      */
+  int32_t group_size;          /* G: 64 or 128                                              */
+  int32_t act_dtype;           /* GLOWQ_F16 or GLOWQ_BF16: type of X, B, A and of the
+                                  dequantised weight                                        */
+  int32_t out_dtype;           /* act_dtype or GLOWQ_F32: type of Y                         */
+} glowq_unit;
+
+/* Human-readable name of a status code (static string). */
+const char* glowq_status_string(glowq_status s);
+
+/* Argument check of one unit exactly as the forward calls perform it (HOST
+ * only, no GPU access).  check_pointers == 0 skips the NULL / alignment tests so
+ * that shapes can be validated before buffers exist. */
+glowq_status glowq_validate_unit(const glowq_unit* u, int32_t check_pointers);
+
+/* ---- weight preparation (one-off, at load time) --------------------------
+ * The kernels read weights from a tiled layout in which one 64-lane wavefront
+ * fetches 32 rows x 64 input channels with a single contiguous 1 KiB load and
+ * every lane's four words are already in matrix-core operand order; scales and
+ * zero-points are stored as (s, z) pairs, transposed so that the 32 rows of a
+ * tile are contiguous.  glowq_prepared_bytes gives the size of that buffer,
+ * glowq_prepare_weights fills it from the canonical W4A16 arrays:
+ *   wq      DEVICE uint32 [d_out][d_in/8], element 8j+e of a row in bits 4e..4e+3 of word j
+ *   scales  DEVICE binary16 [d_out][d_in/G]
+ *   zeros   DEVICE binary16 [d_out][d_in/G], integers in [0, 15]
+ * Zero-points outside that set give unspecified values (never a fault). */
+glowq_status glowq_prepared_bytes(int32_t d_out, int32_t d_in, int32_t group_size,
+                                  size_t* bytes);
+glowq_status glowq_prepare_weights(const uint32_t* wq, const uint16_t* scales,
+                                   const uint16_t* zeros, int32_t d_out, int32_t d_in,
+                                   int32_t group_size, void* w_prepared, void* stream);
+
+/* ---- workspace ------------------------------------------------------------
+ * Scratch for a call over `n_units` units (R in 16-bit and fp32 partial sums of
+ * the projection, plus a few control words).  The control words must be zero
+ * before the first call that uses the buffer: glowq_workspace_init enqueues
+ * that clear.  Every call leaves them zero again, so one buffer can serve any
+ * number of consecutive calls on one stream; calls that may overlap in time
+ * need separate workspaces. */
+glowq_status glowq_workspace_bytes(const glowq_unit* units, int32_t n_units, size_t* bytes);
+glowq_status glowq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- the forward (Sec. 3.3) ------------------------------------------------
+ * glowq_shared_proj: Eq. 8 alone.  R_out DEVICE fp32 [T][r] receives X B^T
+ * (fp32 accumulation).  Exists so that the cached projection can be inspected;
+ * the group forward does not need it to be called first.  r must be > 0. */
+glowq_status glowq_shared_proj(const glowq_unit* u, float* R_out, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/* glowq_group_forward: Eqs. 8-9 for one unit.  restore != 0: R is computed once
+ * and every module adds R A_i^T.  restore == 0 (unit not selected by GlowQ-S) or
+ * r == 0: Y_i = X dequant(W_q,i)^T and neither B nor any A_i is read. */
+glowq_status glowq_group_forward(const glowq_unit* u, int32_t restore, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/* glowq_block_forward: the same for `n_units` independent units (for example
+ * the four units of one decoder block, or a whole stack), unit i restored iff
+ * restore_mask[i] != 0 (HOST, one byte per unit; NULL = restore every unit).
+ * No unit's Y may alias another unit's X within one call.  The glue between
+ * the units of a real decoder block (attention, activation, norms, residual)
+ * is not part of GlowQ and not part of this library. */
+glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,
+                                 const uint8_t* restore_mask, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/* ---- inspection hooks (bit-exactness checks of the storage format) ---------
+ * Both read the prepared layout of one module, the very words the forward
+ * kernels multiply with.
+ * glowq_debug_unpack:  q_out DEVICE uint8 [d_out][d_in], values 0..15.
+ * glowq_debug_dequant: w_out DEVICE act dtype [d_out][d_in],
+ *                      round_to_act((q - z) * s), one rounding. */
+glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d_in,
+                                int32_t group_size, uint8_t* q_out, void* stream);
+glowq_status glowq_debug_dequant(const void* w_prepared, int32_t d_out, int32_t d_in,
+                                 int32_t group_size, int32_t act_dtype, void* w_out,
+                                 void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLOWQ_H */

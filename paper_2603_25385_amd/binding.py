@@ -1,0 +1,167 @@
+"""ctypes binding of libglowq.so: the same names and arguments as include/glowq.h.
+
+Argument marshalling only -- every step of the forward runs in the HIP kernels
+behind the C ABI.  Device buffers are passed as integer addresses (for a torch
+tensor: `t.data_ptr()`), the stream as the integer value of a hipStream_t (for
+torch: `torch.cuda.current_stream().cuda_stream`).  There is no CPU fallback: if
+the shared library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+GLOWQ_F16, GLOWQ_BF16, GLOWQ_F32 = 0, 1, 2
+GLOWQ_MAX_MODULES = 8
+GLOWQ_MAX_RANK = 128
+GLOWQ_OK = 0
+GLOWQ_ERR_NULL, GLOWQ_ERR_SHAPE, GLOWQ_ERR_ALIGN, GLOWQ_ERR_DTYPE = -1, -2, -3, -4
+GLOWQ_ERR_UNSUPPORTED, GLOWQ_ERR_WORKSPACE, GLOWQ_ERR_HIP = -5, -6, -7
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libglowq.so")
+
+
+class glowq_module(ctypes.Structure):
+    _fields_ = [("w_prepared", ctypes.c_void_p), ("A", ctypes.c_void_p), ("Y", ctypes.c_void_p),
+                ("d_out", ctypes.c_int32), ("ldy", ctypes.c_int32)]
+
+
+class glowq_unit(ctypes.Structure):
+    _fields_ = [("X", ctypes.c_void_p), ("B", ctypes.c_void_p),
+                ("modules", ctypes.POINTER(glowq_module)), ("n_modules", ctypes.c_int32),
+                ("T", ctypes.c_int32), ("d_in", ctypes.c_int32), ("r", ctypes.c_int32),
+                ("group_size", ctypes.c_int32), ("act_dtype", ctypes.c_int32),
+                ("out_dtype", ctypes.c_int32)]
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2603_25385_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    up = ctypes.POINTER(glowq_unit)
+    sigs = {
+        "glowq_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+        "glowq_validate_unit": (ctypes.c_int, [up, i32]),
+        "glowq_prepared_bytes": (ctypes.c_int, [i32, i32, i32, ctypes.POINTER(sz)]),
+        "glowq_prepare_weights": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, vp, vp]),
+        "glowq_workspace_bytes": (ctypes.c_int, [up, i32, ctypes.POINTER(sz)]),
+        "glowq_workspace_init": (ctypes.c_int, [vp, sz, vp]),
+        "glowq_shared_proj": (ctypes.c_int, [up, vp, vp, sz, vp]),
+        "glowq_group_forward": (ctypes.c_int, [up, i32, vp, sz, vp]),
+        "glowq_block_forward": (ctypes.c_int, [up, i32, vp, vp, sz, vp]),
+        "glowq_debug_unpack": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
+        "glowq_debug_dequant": (ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)          # AttributeError if a declared symbol is not exported
+        fn.restype, fn.argtypes = res, args
+    return lib, tuple(sigs)
+
+
+_lib, EXPORTED = _load()
+
+
+class GlowqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {glowq_status_string(status)} ({status})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != GLOWQ_OK:
+        raise GlowqError(status, where)
+
+
+def make_module(w_prepared: int, A: int, Y: int, d_out: int, ldy: int) -> glowq_module:
+    return glowq_module(w_prepared or None, A or None, Y or None, d_out, ldy)
+
+
+def make_unit(X: int, B: int, modules: Sequence[glowq_module], T: int, d_in: int, r: int,
+              group_size: int, act_dtype: int, out_dtype: int) -> glowq_unit:
+    arr = (glowq_module * len(modules))(*modules) if modules else None
+    u = glowq_unit(X or None, B or None, arr, len(modules), T, d_in, r, group_size, act_dtype,
+                   out_dtype)
+    u._keepalive = arr       # the descriptor array lives as long as the unit object
+    return u
+
+
+def _units_array(units: Sequence[glowq_unit]):
+    arr = (glowq_unit * len(units))()
+    for i, u in enumerate(units):
+        ctypes.memmove(ctypes.byref(arr[i]), ctypes.byref(u), ctypes.sizeof(glowq_unit))
+    arr._keepalive = list(units)
+    return arr
+
+
+def glowq_status_string(status: int) -> str:
+    return _lib.glowq_status_string(status).decode()
+
+
+def glowq_validate_unit(unit: glowq_unit, check_pointers: bool = True) -> int:
+    """Returns the status code (does not raise)."""
+    return _lib.glowq_validate_unit(ctypes.byref(unit) if unit is not None else None,
+                                    1 if check_pointers else 0)
+
+
+def glowq_prepared_bytes(d_out: int, d_in: int, group_size: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.glowq_prepared_bytes(d_out, d_in, group_size, ctypes.byref(n)),
+           "glowq_prepared_bytes")
+    return n.value
+
+
+def glowq_prepare_weights(wq: int, scales: int, zeros: int, d_out: int, d_in: int,
+                          group_size: int, w_prepared: int, stream: int = 0) -> None:
+    _check(_lib.glowq_prepare_weights(wq or None, scales or None, zeros or None, d_out, d_in,
+                                      group_size, w_prepared or None, stream or None),
+           "glowq_prepare_weights")
+
+
+def glowq_workspace_bytes(units: Sequence[glowq_unit]) -> int:
+    n = ctypes.c_size_t(0)
+    arr = _units_array(units)
+    _check(_lib.glowq_workspace_bytes(arr, len(units), ctypes.byref(n)), "glowq_workspace_bytes")
+    return n.value
+
+
+def glowq_workspace_init(workspace: int, workspace_bytes: int, stream: int = 0) -> None:
+    _check(_lib.glowq_workspace_init(workspace or None, workspace_bytes, stream or None),
+           "glowq_workspace_init")
+
+
+def glowq_shared_proj(unit: glowq_unit, R_out: int, workspace: int, workspace_bytes: int,
+                      stream: int = 0) -> None:
+    _check(_lib.glowq_shared_proj(ctypes.byref(unit), R_out or None, workspace or None,
+                                  workspace_bytes, stream or None), "glowq_shared_proj")
+
+
+def glowq_group_forward(unit: glowq_unit, restore: bool, workspace: int, workspace_bytes: int,
+                        stream: int = 0) -> None:
+    _check(_lib.glowq_group_forward(ctypes.byref(unit), 1 if restore else 0, workspace or None,
+                                    workspace_bytes, stream or None), "glowq_group_forward")
+
+
+def glowq_block_forward(units: Sequence[glowq_unit], restore_mask: Optional[bytes],
+                        workspace: int, workspace_bytes: int, stream: int = 0) -> None:
+    arr = _units_array(units)
+    mask = None
+    if restore_mask is not None:
+        mask = (ctypes.c_uint8 * len(units))(*[1 if b else 0 for b in restore_mask])
+    _check(_lib.glowq_block_forward(arr, len(units), mask, workspace or None, workspace_bytes,
+                                    stream or None), "glowq_block_forward")
+
+
+def glowq_debug_unpack(w_prepared: int, d_out: int, d_in: int, group_size: int, q_out: int,
+                       stream: int = 0) -> None:
+    _check(_lib.glowq_debug_unpack(w_prepared or None, d_out, d_in, group_size, q_out or None,
+                                   stream or None), "glowq_debug_unpack")
+
+
+def glowq_debug_dequant(w_prepared: int, d_out: int, d_in: int, group_size: int, act_dtype: int,
+                        w_out: int, stream: int = 0) -> None:
+    _check(_lib.glowq_debug_dequant(w_prepared or None, d_out, d_in, group_size, act_dtype,
+                                    w_out or None, stream or None), "glowq_debug_dequant")

@@ -1,0 +1,222 @@
+// C ABI of the GlowQ group forward (declared in include/glowq.h): host-side
+// argument checks, workspace planning and dispatch to the HIP kernels.  Nothing in
+// this file allocates, synchronises or keeps state.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace glowq {
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
+  UnitWorkspace w;
+  w.base = base;
+  const int mblocks = (u.T + 31) / 32;
+  w.off_counters = sizeof(Control);
+  w.ctl_bytes = align_up(w.off_counters + (size_t)mblocks * 4, 256);
+  // K slices of the projection: decode spreads B over many compute units; prefill
+  // already has T / 32 token blocks and only needs enough slices to fill the chip
+  int ksplit;
+  if (is_decode(u.T)) ksplit = 32;
+  else ksplit = (512 + mblocks - 1) / mblocks;
+  if (ksplit > 32) ksplit = 32;
+  if (ksplit < 1) ksplit = 1;
+  int steps = u.d_in / 16;
+  int per = (steps + ksplit - 1) / ksplit;
+  w.kslice = per * 16;
+  w.ksplit = (u.d_in + w.kslice - 1) / w.kslice;
+  w.off_rpart = w.ctl_bytes;
+  size_t rpart = (u.r > 0) ? (size_t)w.ksplit * u.T * u.r * sizeof(float) : 0;
+  w.off_r16 = align_up(w.off_rpart + rpart, 256);
+  size_t r16 = (u.r > 0) ? (size_t)u.T * u.r * 2 : 0;
+  w.bytes = align_up(w.off_r16 + r16, 256);
+  return w;
+}
+
+static glowq_status validate(const glowq_unit* u, bool ptrs) {
+  if (!u) return GLOWQ_ERR_NULL;
+  if (u->n_modules < 1 || u->n_modules > GLOWQ_MAX_MODULES) return GLOWQ_ERR_SHAPE;
+  if (ptrs && !u->modules) return GLOWQ_ERR_NULL;
+  if (u->T < 1 || u->T > (1 << 20)) return GLOWQ_ERR_SHAPE;
+  if (u->group_size != 64 && u->group_size != 128) return GLOWQ_ERR_SHAPE;
+  if (u->d_in < u->group_size || u->d_in > (1 << 16) || u->d_in % u->group_size)
+    return GLOWQ_ERR_SHAPE;
+  if (u->r < 0 || u->r > GLOWQ_MAX_RANK || u->r % 8) return GLOWQ_ERR_SHAPE;
+  if (u->act_dtype != GLOWQ_F16 && u->act_dtype != GLOWQ_BF16) return GLOWQ_ERR_DTYPE;
+  if (u->out_dtype != u->act_dtype && u->out_dtype != GLOWQ_F32) return GLOWQ_ERR_DTYPE;
+  if (!u->modules) return GLOWQ_OK;   // shapes only
+  for (int i = 0; i < u->n_modules; ++i) {
+    const glowq_module& m = u->modules[i];
+    if (m.d_out < 8 || m.d_out > (1 << 20) || m.d_out % 8) return GLOWQ_ERR_SHAPE;
+    if (m.ldy < m.d_out || m.ldy % 8) return GLOWQ_ERR_SHAPE;
+  }
+  if (!ptrs) return GLOWQ_OK;
+  if (!u->X || (u->r > 0 && !u->B)) return GLOWQ_ERR_NULL;
+  for (int i = 0; i < u->n_modules; ++i) {
+    const glowq_module& m = u->modules[i];
+    if (!m.w_prepared || !m.Y || (u->r > 0 && !m.A)) return GLOWQ_ERR_NULL;
+  }
+  if (misaligned(u->X) || misaligned(u->B)) return GLOWQ_ERR_ALIGN;
+  for (int i = 0; i < u->n_modules; ++i) {
+    const glowq_module& m = u->modules[i];
+    if (misaligned(m.w_prepared) || misaligned(m.Y) || misaligned(m.A)) return GLOWQ_ERR_ALIGN;
+  }
+  return GLOWQ_OK;
+}
+
+static glowq_status check_weights_shape(int d_out, int d_in, int G) {
+  if (G != 64 && G != 128) return GLOWQ_ERR_SHAPE;
+  if (d_in < G || d_in > (1 << 16) || d_in % G) return GLOWQ_ERR_SHAPE;
+  if (d_out < 8 || d_out > (1 << 20) || d_out % 8) return GLOWQ_ERR_SHAPE;
+  return GLOWQ_OK;
+}
+
+static inline glowq_status hip_status(hipError_t e) { return e == hipSuccess ? GLOWQ_OK : GLOWQ_ERR_HIP; }
+
+static glowq_status forward_one(const glowq_unit& u, bool restore, char* ws_base, hipStream_t st) {
+  UnitWorkspace ws = plan_unit_workspace(u, ws_base);
+  const bool corr = restore && u.r > 0;
+  if (corr) {
+    hipError_t e = launch_proj(u, ws, nullptr, true, st);
+    if (e != hipSuccess) return GLOWQ_ERR_HIP;
+  }
+  hipError_t e = is_decode(u.T) ? launch_decode(u, ws, corr, st) : launch_prefill(u, ws, corr, st);
+  return hip_status(e);
+}
+
+}  // namespace glowq
+
+using namespace glowq;
+
+extern "C" {
+
+const char* glowq_status_string(glowq_status s) {
+  switch (s) {
+    case GLOWQ_OK: return "ok";
+    case GLOWQ_ERR_NULL: return "required pointer is NULL";
+    case GLOWQ_ERR_SHAPE: return "size out of range or inconsistent";
+    case GLOWQ_ERR_ALIGN: return "device pointer or stride misaligned";
+    case GLOWQ_ERR_DTYPE: return "unsupported data type";
+    case GLOWQ_ERR_UNSUPPORTED: return "unsupported request";
+    case GLOWQ_ERR_WORKSPACE: return "workspace missing or too small";
+    case GLOWQ_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+glowq_status glowq_validate_unit(const glowq_unit* u, int32_t check_pointers) {
+  return validate(u, check_pointers != 0);
+}
+
+glowq_status glowq_prepared_bytes(int32_t d_out, int32_t d_in, int32_t group_size, size_t* bytes) {
+  if (!bytes) return GLOWQ_ERR_NULL;
+  glowq_status s = check_weights_shape(d_out, d_in, group_size);
+  if (s != GLOWQ_OK) return s;
+  *bytes = prepared_total_bytes(d_out, d_in, group_size);
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_prepare_weights(const uint32_t* wq, const uint16_t* scales,
+                                   const uint16_t* zeros, int32_t d_out, int32_t d_in,
+                                   int32_t group_size, void* w_prepared, void* stream) {
+  if (!wq || !scales || !zeros || !w_prepared) return GLOWQ_ERR_NULL;
+  glowq_status s = check_weights_shape(d_out, d_in, group_size);
+  if (s != GLOWQ_OK) return s;
+  if (misaligned(wq) || misaligned(scales) || misaligned(zeros) || misaligned(w_prepared))
+    return GLOWQ_ERR_ALIGN;
+  return hip_status(launch_prepare(wq, scales, zeros, d_out, d_in, group_size, w_prepared,
+                                   (hipStream_t)stream));
+}
+
+glowq_status glowq_workspace_bytes(const glowq_unit* units, int32_t n_units, size_t* bytes) {
+  if (!units || !bytes) return GLOWQ_ERR_NULL;
+  if (n_units < 1) return GLOWQ_ERR_SHAPE;
+  size_t total = 0;
+  for (int i = 0; i < n_units; ++i) {
+    glowq_status s = validate(&units[i], false);
+    if (s != GLOWQ_OK) return s;
+    total += plan_unit_workspace(units[i], nullptr).bytes;
+  }
+  *bytes = total;
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace) return GLOWQ_ERR_NULL;
+  if (misaligned(workspace)) return GLOWQ_ERR_ALIGN;
+  if (workspace_bytes % 4) return GLOWQ_ERR_SHAPE;
+  return hip_status(launch_fill_zero(workspace, workspace_bytes, (hipStream_t)stream));
+}
+
+glowq_status glowq_shared_proj(const glowq_unit* u, float* R_out, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  glowq_status s = validate(u, true);
+  if (s != GLOWQ_OK) return s;
+  if (u->r == 0) return GLOWQ_ERR_SHAPE;
+  if (!R_out) return GLOWQ_ERR_NULL;
+  if (misaligned(R_out)) return GLOWQ_ERR_ALIGN;
+  if (!workspace) return GLOWQ_ERR_WORKSPACE;
+  if (misaligned(workspace)) return GLOWQ_ERR_ALIGN;
+  UnitWorkspace ws = plan_unit_workspace(*u, (char*)workspace);
+  if (workspace_bytes < ws.bytes) return GLOWQ_ERR_WORKSPACE;
+  return hip_status(launch_proj(*u, ws, R_out, false, (hipStream_t)stream));
+}
+
+glowq_status glowq_group_forward(const glowq_unit* u, int32_t restore, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  uint8_t mask = restore ? 1 : 0;
+  return glowq_block_forward(u, 1, &mask, workspace, workspace_bytes, stream);
+}
+
+glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,
+                                 const uint8_t* restore_mask, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!units) return GLOWQ_ERR_NULL;
+  if (n_units < 1) return GLOWQ_ERR_SHAPE;
+  // check everything before anything is enqueued
+  size_t need = 0;
+  bool any_corr = false;
+  for (int i = 0; i < n_units; ++i) {
+    glowq_status s = validate(&units[i], true);
+    if (s != GLOWQ_OK) return s;
+    need += plan_unit_workspace(units[i], nullptr).bytes;
+    if (units[i].r > 0 && (!restore_mask || restore_mask[i])) any_corr = true;
+  }
+  if (any_corr) {
+    if (!workspace) return GLOWQ_ERR_WORKSPACE;
+    if (misaligned(workspace)) return GLOWQ_ERR_ALIGN;
+    if (workspace_bytes < need) return GLOWQ_ERR_WORKSPACE;
+  }
+  size_t off = 0;
+  for (int i = 0; i < n_units; ++i) {
+    const bool restore = !restore_mask || restore_mask[i];
+    glowq_status s = forward_one(units[i], restore, (char*)workspace + off, (hipStream_t)stream);
+    if (s != GLOWQ_OK) return s;
+    off += plan_unit_workspace(units[i], nullptr).bytes;
+  }
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d_in,
+                                int32_t group_size, uint8_t* q_out, void* stream) {
+  if (!w_prepared || !q_out) return GLOWQ_ERR_NULL;
+  glowq_status s = check_weights_shape(d_out, d_in, group_size);
+  if (s != GLOWQ_OK) return s;
+  if (misaligned(w_prepared) || misaligned(q_out)) return GLOWQ_ERR_ALIGN;
+  return hip_status(launch_debug_unpack(w_prepared, d_out, d_in, q_out, (hipStream_t)stream));
+}
+
+glowq_status glowq_debug_dequant(const void* w_prepared, int32_t d_out, int32_t d_in,
+                                 int32_t group_size, int32_t act_dtype, void* w_out,
+                                 void* stream) {
+  if (!w_prepared || !w_out) return GLOWQ_ERR_NULL;
+  glowq_status s = check_weights_shape(d_out, d_in, group_size);
+  if (s != GLOWQ_OK) return s;
+  if (act_dtype != GLOWQ_F16 && act_dtype != GLOWQ_BF16) return GLOWQ_ERR_DTYPE;
+  if (misaligned(w_prepared) || misaligned(w_out)) return GLOWQ_ERR_ALIGN;
+  return hip_status(launch_debug_dequant(w_prepared, d_out, d_in, group_size, act_dtype, w_out,
+                                         (hipStream_t)stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,154 @@
+// Device-side building blocks shared by every GlowQ kernel: the prepared weight
+// layout, the single-rounding dequantiser (W4A16 storage, paper Sec. 4.1), and
+// thin wrappers over the gfx950 matrix-core instructions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace glowq {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+enum Act { ACT_F16 = 0, ACT_BF16 = 1 };
+
+// ---------------------------------------------------------------------------
+// Prepared layout of one module's weights (built by prepare.hip):
+//   tiles : [rows32][d_in/64][64 lanes][4 words]   one tile = 32 rows x 64 channels = 1 KiB
+//           lane l holds row 32*rb + (l & 31), channels 64*kb + 32*(l >> 5) + 8*j + e
+//           in word j; inside a word, nibble i holds e = 2i and nibble i + 4 holds
+//           e = 2i + 1, so that ((w >> 4i) & 0x000F000F) is the pair (e = 2i, e = 2i + 1)
+//   sz    : [d_in/G][rows32 * 32] words, low half = scale bits, high half = zero-point bits
+// rows32 = ceil(d_out / 32); rows past d_out hold q = 0, s = 1, z = 0 (dequantise to 0).
+// ---------------------------------------------------------------------------
+struct PreparedView {
+  const u32x4_t* tiles;
+  const uint32_t* sz;
+  int rows32;   // 32-row blocks
+  int ktiles;   // d_in / 64
+};
+
+__host__ __device__ inline size_t prepared_tile_bytes(int d_out, int d_in) {
+  return (size_t)((d_out + 31) / 32) * 32 * (size_t)d_in / 2;
+}
+__host__ __device__ inline size_t prepared_total_bytes(int d_out, int d_in, int G) {
+  return prepared_tile_bytes(d_out, d_in) + (size_t)(d_in / G) * ((d_out + 31) / 32) * 32 * 4;
+}
+__host__ __device__ inline PreparedView prepared_view(const void* p, int d_out, int d_in) {
+  PreparedView v;
+  v.tiles = (const u32x4_t*)p;
+  v.sz = (const uint32_t*)((const char*)p + prepared_tile_bytes(d_out, d_in));
+  v.rows32 = (d_out + 31) / 32;
+  v.ktiles = d_in / 64;
+  return v;
+}
+
+// Per (row, group) constants of the dequantiser, derived once from an sz word.
+template <int ACT> struct GroupConst;
+template <> struct GroupConst<ACT_F16> {
+  half2_t s2;    // (s, s)
+  half2_t nb2;   // (-(1024 + z), -(1024 + z)), exact in binary16 for integer z <= 1023
+  __device__ inline void set(uint32_t szw) {
+    _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(szw & 0xffffu));
+    _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)(szw >> 16));
+    _Float16 nb = -((_Float16)1024.0f + z);
+    s2 = half2_t{s, s};
+    nb2 = half2_t{nb, nb};
+  }
+};
+template <> struct GroupConst<ACT_BF16> {
+  float s;     // scale widened
+  float nzs;   // -z * s, exact in fp32 (<= 4 + 11 significant bits)
+  __device__ inline void set(uint32_t szw) {
+    s = (float)__builtin_bit_cast(_Float16, (uint16_t)(szw & 0xffffu));
+    float z = (float)__builtin_bit_cast(_Float16, (uint16_t)(szw >> 16));
+    nzs = -z * s;
+  }
+};
+
+// Eight dequantised weights of one prepared word, in channel order e = 0..7,
+// as four 32-bit registers of packed 16-bit values (a matrix-core operand).
+//
+// binary16: the pair (1024 + q_a, 1024 + q_b) is made by OR-ing the nibbles into
+// the fraction of 0x6400; adding -(1024 + z) is exact, and the packed multiply by
+// s rounds once, to nearest even -- the definition of the stored weight.
+// bfloat16: q widens to fp32 exactly, fma(q, s, -z s) is exact in fp32, and the
+// packed fp32 -> bf16 conversion rounds once, to nearest even.
+template <int ACT>
+__device__ inline u32x4_t dequant_word(uint32_t w, const GroupConst<ACT>& g);
+
+template <>
+__device__ inline u32x4_t dequant_word<ACT_F16>(uint32_t w, const GroupConst<ACT_F16>& g) {
+  u32x4_t out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t t = ((w >> (4 * i)) & 0x000F000Fu) | 0x64006400u;
+    half2_t v = __builtin_bit_cast(half2_t, t);
+    v = (v + g.nb2) * g.s2;
+    out[i] = __builtin_bit_cast(uint32_t, v);
+  }
+  return out;
+}
+
+template <>
+__device__ inline u32x4_t dequant_word<ACT_BF16>(uint32_t w, const GroupConst<ACT_BF16>& g) {
+  // nibble positions 0,2,4,6 (channels e = 0,4,1,5) and 1,3,5,7 (e = 2,6,3,7), one per byte,
+  // so that each widening is a single byte-to-float conversion
+  const uint32_t m0 = w & 0x0F0F0F0Fu;
+  const uint32_t m1 = (w >> 4) & 0x0F0F0F0Fu;
+  const float q0 = (float)(m0 & 0xFFu), q4 = (float)((m0 >> 8) & 0xFFu);
+  const float q1 = (float)((m0 >> 16) & 0xFFu), q5 = (float)(m0 >> 24);
+  const float q2 = (float)(m1 & 0xFFu), q6 = (float)((m1 >> 8) & 0xFFu);
+  const float q3 = (float)((m1 >> 16) & 0xFFu), q7 = (float)(m1 >> 24);
+  const float qs[8] = {q0, q1, q2, q3, q4, q5, q6, q7};
+  u32x4_t out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    bf16x2_t v;
+    v[0] = (__bf16)__builtin_fmaf(qs[2 * i], g.s, g.nzs);
+    v[1] = (__bf16)__builtin_fmaf(qs[2 * i + 1], g.s, g.nzs);
+    out[i] = __builtin_bit_cast(uint32_t, v);
+  }
+  return out;
+}
+
+// Nibble e (channel order) of a prepared word.
+__device__ inline uint32_t prepared_nibble(uint32_t w, int e) {
+  return (w >> (4 * (e >> 1) + 16 * (e & 1))) & 0xFu;
+}
+
+// D(32x32, fp32) += A(32x16) * B(16x32).  Lane l supplies row (l & 31) of A and
+// column (l & 31) of B, eight consecutive k each, k-half (l >> 5); any k order is
+// fine as long as both operands use the same one.  D: lane l holds column (l & 31),
+// rows 8*(i/4) + 4*(l >> 5) + (i & 3) in element i.
+template <int ACT>
+__device__ inline float16_t mfma32(u32x4_t a, u32x4_t b, float16_t c) {
+  if constexpr (ACT == ACT_F16) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
+                                                  __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  }
+}
+
+template <int ACT> __device__ inline uint16_t to_act16(float v) {
+  if constexpr (ACT == ACT_F16) return __builtin_bit_cast(uint16_t, (_Float16)v);
+  else return __builtin_bit_cast(uint16_t, (__bf16)v);
+}
+
+// Control words at the head of a unit's workspace slice (all zero between calls).
+struct Control {
+  uint32_t proj_arrivals;   // projection workgroups that have stored their partial sums
+  uint32_t r_ready;         // 1 once R is complete (single-launch decode path only)
+  uint32_t consumers_done;  // workgroups that have consumed R in this launch
+  uint32_t status;          // nonzero: a bounded wait expired (cannot happen in order dispatch)
+  uint32_t pad[12];
+};
+
+}  // namespace glowq

@@ -1,0 +1,125 @@
+// Weight preparation and the two inspection hooks.
+//
+// prepare:       canonical W4A16 arrays -> tiled layout the forward kernels read
+// debug_unpack:  tiled layout -> q[d_out][d_in] bytes
+// debug_dequant: tiled layout -> round_to_act((q - z) * s), through the very
+//                dequant_word() the forward kernels feed the matrix cores with
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace glowq {
+
+// one thread per prepared word
+__global__ void k_prepare_tiles(const uint32_t* __restrict__ wq, uint32_t* __restrict__ tiles,
+                                int d_out, int d_in, long long n_words) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_words) return;
+  const int ktiles = d_in / 64;
+  int j = (int)(idx & 3);
+  int lane = (int)((idx >> 2) & 63);
+  long long tile = idx >> 8;
+  int kb = (int)(tile % ktiles);
+  int rb = (int)(tile / ktiles);
+  int row = rb * 32 + (lane & 31);
+  int k0 = kb * 64 + 32 * (lane >> 5) + 8 * j;
+  uint32_t c = 0;
+  if (row < d_out) c = wq[(long long)row * (d_in / 8) + k0 / 8];
+  uint32_t w = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    w |= ((c >> (8 * i)) & 0xFu) << (4 * i);            // e = 2i     -> nibble i
+    w |= ((c >> (8 * i + 4)) & 0xFu) << (4 * i + 16);   // e = 2i + 1 -> nibble i + 4
+  }
+  tiles[idx] = w;
+}
+
+// one thread per (group, padded row)
+__global__ void k_prepare_sz(const uint16_t* __restrict__ scales,
+                             const uint16_t* __restrict__ zeros, uint32_t* __restrict__ sz,
+                             int d_out, int rows_pad, int n_groups) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)rows_pad * n_groups) return;
+  int row = (int)(idx % rows_pad);
+  int g = (int)(idx / rows_pad);
+  uint32_t v = 0x3C00u;   // s = 1, z = 0 for padding rows
+  if (row < d_out)
+    v = (uint32_t)scales[(long long)row * n_groups + g] |
+        ((uint32_t)zeros[(long long)row * n_groups + g] << 16);
+  sz[idx] = v;
+}
+
+__device__ inline uint32_t load_prepared_word(const PreparedView& v, int row, int k) {
+  int rb = row >> 5, kb = k >> 6;
+  int lane = (row & 31) + 32 * ((k >> 5) & 1);
+  int j = (k >> 3) & 3;
+  const uint32_t* t = (const uint32_t*)v.tiles;
+  return t[(((long long)rb * v.ktiles + kb) * 64 + lane) * 4 + j];
+}
+
+// one thread per (row, 8 channels)
+__global__ void k_debug_unpack(const void* prepared, int d_out, int d_in,
+                               uint8_t* __restrict__ q_out) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  int words = d_in / 8;
+  if (idx >= (long long)d_out * words) return;
+  int row = (int)(idx / words), k = (int)(idx % words) * 8;
+  PreparedView v = prepared_view(prepared, d_out, d_in);
+  uint32_t w = load_prepared_word(v, row, k);
+  uint32_t lo = 0, hi = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    lo |= prepared_nibble(w, e) << (8 * e);
+    hi |= prepared_nibble(w, e + 4) << (8 * e);
+  }
+  uint2* dst = (uint2*)(q_out + (long long)row * d_in + k);
+  *dst = make_uint2(lo, hi);
+}
+
+template <int ACT>
+__global__ void k_debug_dequant(const void* prepared, int d_out, int d_in, int G,
+                                uint16_t* __restrict__ w_out) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  int words = d_in / 8;
+  if (idx >= (long long)d_out * words) return;
+  int row = (int)(idx / words), k = (int)(idx % words) * 8;
+  PreparedView v = prepared_view(prepared, d_out, d_in);
+  uint32_t w = load_prepared_word(v, row, k);
+  GroupConst<ACT> g;
+  g.set(v.sz[(long long)(k / G) * (v.rows32 * 32) + row]);
+  u32x4_t d = dequant_word<ACT>(w, g);
+  *(u32x4_t*)(w_out + (long long)row * d_in + k) = d;
+}
+
+hipError_t launch_prepare(const uint32_t* wq, const uint16_t* scales, const uint16_t* zeros,
+                          int d_out, int d_in, int G, void* prepared, hipStream_t st) {
+  PreparedView v = prepared_view(prepared, d_out, d_in);
+  long long n_words = (long long)prepared_tile_bytes(d_out, d_in) / 4;
+  int rows_pad = v.rows32 * 32, n_groups = d_in / G;
+  k_prepare_tiles<<<dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st>>>(
+      wq, (uint32_t*)v.tiles, d_out, d_in, n_words);
+  long long n_sz = (long long)rows_pad * n_groups;
+  k_prepare_sz<<<dim3((unsigned)((n_sz + 255) / 256)), dim3(256), 0, st>>>(
+      scales, zeros, (uint32_t*)v.sz, d_out, rows_pad, n_groups);
+  return hipGetLastError();
+}
+
+hipError_t launch_debug_unpack(const void* prepared, int d_out, int d_in, uint8_t* q_out,
+                               hipStream_t st) {
+  long long n = (long long)d_out * (d_in / 8);
+  k_debug_unpack<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(prepared, d_out, d_in,
+                                                                          q_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_debug_dequant(const void* prepared, int d_out, int d_in, int G, int act,
+                                void* w_out, hipStream_t st) {
+  long long n = (long long)d_out * (d_in / 8);
+  dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (act == ACT_F16)
+    k_debug_dequant<ACT_F16><<<grid, block, 0, st>>>(prepared, d_out, d_in, G, (uint16_t*)w_out);
+  else
+    k_debug_dequant<ACT_BF16><<<grid, block, 0, st>>>(prepared, d_out, d_in, G, (uint16_t*)w_out);
+  return hipGetLastError();
+}
+
+}  // namespace glowq

@@ -1,0 +1,98 @@
+"""Glue for the GPU parity tests: moves an oracle-style unit (numpy bit patterns)
+into device memory with torch, prepares the weights, and calls the C ABI through
+the Python binding.  Torch is used for memory and streams only."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2603_25385_amd as G
+
+ACT_CODE = {"f16": G.GLOWQ_F16, "bf16": G.GLOWQ_BF16, "f32": G.GLOWQ_F32}
+TORCH_ACT = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}
+
+
+def dev_bits(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bit patterns -> int16 device tensor (same bytes)."""
+    return torch.from_numpy(np.ascontiguousarray(bits, np.uint16).view(np.int16)).cuda()
+
+
+def dev_words(words: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(words, np.uint32).view(np.int32)).cuda()
+
+
+def stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class DeviceModule:
+    def __init__(self, module: dict, d_in: int, Gs: int):
+        self.d_out = int(module["wq"].shape[0])
+        self.wq = dev_words(module["wq"]) if not torch.is_tensor(module["wq"]) else module["wq"]
+        self.scales = _as_dev16(module["scales"])
+        self.zeros = _as_dev16(module["zeros"])
+        nbytes = G.glowq_prepared_bytes(self.d_out, d_in, Gs)
+        self.prepared = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        G.glowq_prepare_weights(self.wq.data_ptr(), self.scales.data_ptr(), self.zeros.data_ptr(),
+                                self.d_out, d_in, Gs, self.prepared.data_ptr(), stream())
+        A = module.get("A")
+        self.A = None if A is None or A.shape[1] == 0 else _as_dev16(A)
+
+
+def _as_dev16(x):
+    if torch.is_tensor(x):
+        return x.cuda().contiguous()
+    return dev_bits(x)
+
+
+class DeviceUnit:
+    """Device copy of one unit plus its output buffers."""
+
+    def __init__(self, unit: dict, out: str = "f32", ldy_pad: int = 0):
+        self.act, self.Gs, self.r = unit["act"], unit["G"], unit["r"]
+        self.d_in = int(unit["d_in"])
+        self.X = _as_dev16(unit["X"])
+        self.T = int(self.X.shape[0])
+        self.B = None if self.r == 0 else _as_dev16(unit["B"])
+        self.modules = [DeviceModule(m, self.d_in, self.Gs) for m in unit["modules"]]
+        self.out = self.act if out == "act" else out
+        self.Y = [torch.full((self.T, m.d_out + ldy_pad), float("nan"), dtype=TORCH_ACT[self.out],
+                             device="cuda") for m in self.modules]
+        self.desc = self.describe()
+
+    def describe(self, T=None, r=None, X=None):
+        mods = [G.make_module(m.prepared.data_ptr(), 0 if m.A is None else m.A.data_ptr(),
+                              y.data_ptr(), m.d_out, y.shape[1])
+                for m, y in zip(self.modules, self.Y)]
+        return G.make_unit((X if X is not None else self.X).data_ptr(),
+                           0 if self.B is None else self.B.data_ptr(), mods,
+                           self.T if T is None else T, self.d_in, self.r if r is None else r,
+                           self.Gs, ACT_CODE[self.act], ACT_CODE[self.out])
+
+    def outputs(self):
+        torch.cuda.synchronize()
+        return [y[:, :m.d_out].to(torch.float64).cpu().numpy()
+                for y, m in zip(self.Y, self.modules)]
+
+    def clear(self):
+        for y in self.Y:
+            y.fill_(float("nan"))
+
+
+class Workspace:
+    def __init__(self, descs):
+        self.bytes = G.glowq_workspace_bytes(descs)
+        self.buf = torch.empty(max(self.bytes, 256), dtype=torch.uint8, device="cuda")
+        G.glowq_workspace_init(self.buf.data_ptr(), self.buf.numel(), stream())
+
+    @property
+    def ptr(self):
+        return self.buf.data_ptr()
+
+
+def run_group(unit: dict, restore: bool = True, out: str = "f32", ldy_pad: int = 0):
+    du = DeviceUnit(unit, out, ldy_pad)
+    ws = Workspace([du.desc])
+    G.glowq_group_forward(du.desc, restore, ws.ptr, ws.bytes, stream())
+    ys = du.outputs()
+    return ys, du, ws

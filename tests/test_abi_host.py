@@ -1,0 +1,79 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/glowq.h declares, and rejects bad arguments with the
+documented status codes before touching any device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2603_25385_amd as G
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "glowq.h")).read()
+    declared = set(re.findall(r"\b(glowq_[a-z_0-9]+)\s*\(", text))
+    assert declared, "no declarations found"
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2603_25385_amd", "lib", "libglowq.so"))
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(G.EXPORTED)
+
+
+def _unit(**kw):
+    base = dict(X=0x1000, B=0x2000, T=4, d_in=256, r=16, group_size=64, act=G.GLOWQ_F16,
+                out=G.GLOWQ_F32, d_out=64, ldy=64, wp=0x3000, A=0x4000, Y=0x5000, n=1)
+    base.update(kw)
+    mods = [G.make_module(base["wp"], base["A"], base["Y"], base["d_out"], base["ldy"])
+            for _ in range(base["n"])]
+    return G.make_unit(base["X"], base["B"], mods, base["T"], base["d_in"], base["r"],
+                       base["group_size"], base["act"], base["out"])
+
+
+def test_valid_unit_passes():
+    assert G.glowq_validate_unit(_unit()) == G.GLOWQ_OK
+    assert G.glowq_validate_unit(_unit(r=0, B=0, A=0)) == G.GLOWQ_OK
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(X=0), G.GLOWQ_ERR_NULL), (dict(B=0), G.GLOWQ_ERR_NULL), (dict(A=0), G.GLOWQ_ERR_NULL),
+    (dict(wp=0), G.GLOWQ_ERR_NULL), (dict(Y=0), G.GLOWQ_ERR_NULL),
+    (dict(X=0x1008), G.GLOWQ_ERR_ALIGN), (dict(Y=0x5004), G.GLOWQ_ERR_ALIGN),
+    (dict(T=0), G.GLOWQ_ERR_SHAPE), (dict(d_in=200), G.GLOWQ_ERR_SHAPE),
+    (dict(group_size=32), G.GLOWQ_ERR_SHAPE), (dict(r=12), G.GLOWQ_ERR_SHAPE),
+    (dict(r=136), G.GLOWQ_ERR_SHAPE), (dict(d_out=60), G.GLOWQ_ERR_SHAPE),
+    (dict(ldy=56), G.GLOWQ_ERR_SHAPE), (dict(ldy=68), G.GLOWQ_ERR_SHAPE),
+    (dict(n=0), G.GLOWQ_ERR_SHAPE), (dict(n=9), G.GLOWQ_ERR_SHAPE),
+    (dict(act=G.GLOWQ_F32), G.GLOWQ_ERR_DTYPE), (dict(act=G.GLOWQ_F16, out=G.GLOWQ_BF16), G.GLOWQ_ERR_DTYPE),
+])
+def test_bad_units_are_rejected(kw, status):
+    assert G.glowq_validate_unit(_unit(**kw)) == status
+    # the forward entry points apply the same check and enqueue nothing
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_group_forward(_unit(**kw), True, 0x9000, 1 << 20, 0)
+    assert e.value.status == status
+
+
+def test_workspace_and_misc_errors():
+    u = _unit()
+    need = G.glowq_workspace_bytes([u])
+    assert need > 0 and need % 256 == 0
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_group_forward(u, True, 0, 0, 0)
+    assert e.value.status == G.GLOWQ_ERR_WORKSPACE
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_group_forward(u, True, 0x9000, need - 1, 0)
+    assert e.value.status == G.GLOWQ_ERR_WORKSPACE
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_shared_proj(_unit(r=0, B=0, A=0), 0x8000, 0x9000, 1 << 20, 0)
+    assert e.value.status == G.GLOWQ_ERR_SHAPE
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_prepare_weights(0, 0x10, 0x20, 64, 256, 64, 0x30, 0)
+    assert e.value.status == G.GLOWQ_ERR_NULL
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_prepared_bytes(64, 250, 64)
+    assert e.value.status == G.GLOWQ_ERR_SHAPE
+    assert G.glowq_prepared_bytes(40, 128, 128) == 64 * 128 // 2 + 1 * 64 * 4
+    assert "NULL" in G.glowq_status_string(G.GLOWQ_ERR_NULL)
