@@ -146,19 +146,24 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
 
   // correction: r more channels, operand [A_i] against [R]
   if (a.restore) {
-    for (int j0 = 8 * h; j0 < a.r; j0 += 16) {
+    // the trip count is the same for every lane (matrix-core instructions must not sit
+    // under a divergent branch); a half-wave past the rank contributes zeros
+    for (int jj = 0; jj * 16 < a.r; ++jj) {
+      const int j0 = jj * 16 + 8 * h;
+      const bool j_ok = j0 < a.r;
       u32x4_t af[2];
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
         af[b] = u32x4_t{0u, 0u, 0u, 0u};
         const int row = (nb0 + b) * 32 + m;
-        if (valid[b] && row < M.d_out) af[b] = *(const u32x4_t*)(M.A + (size_t)row * a.r + j0);
+        if (j_ok && valid[b] && row < M.d_out)
+          af[b] = *(const u32x4_t*)(M.A + (size_t)row * a.r + j0);
       }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         const int tok = tok0 + mb * 32 + m;
         u32x4_t rf = {0u, 0u, 0u, 0u};
-        if (tok < a.T) rf = *(const u32x4_t*)(a.R16 + (size_t)tok * a.r + j0);
+        if (j_ok && tok < a.T) rf = *(const u32x4_t*)(a.R16 + (size_t)tok * a.r + j0);
         if (valid[0]) acc[0][mb] = mfma32<ACT>(af[0], rf, acc[0][mb]);
         if (valid[1]) acc[1][mb] = mfma32<ACT>(af[1], rf, acc[1][mb]);
       }
