@@ -69,7 +69,7 @@ typedef struct {
   const glowq_module* modules; /* HOST: n_modules descriptors                               */
   int32_t n_modules;           /* 1 .. GLOWQ_MAX_MODULES                                    */
   int32_t T;                   /* tokens (batch x time flattened), >= 1                     */
-  int32_t d_in;                /* shared input width; multiple of group_size                */
+  int32_t d_in;                /* shared input width; multiple of 128                       */
   int32_t r;                   /* rank of the correction; 0 or a multiple of 8, <= 128      */
   int32_t group_size;          /* G: 64 or 128                                              */
   int32_t act_dtype;           /* GLOWQ_F16 or GLOWQ_BF16: type of X, B, A and of the
@@ -80,6 +80,10 @@ typedef struct {
 /* Human-readable name of a status code (static string). */
 const char* glowq_status_string(glowq_status s);
 
+/* Text of the HIP error behind the calling thread's most recent GLOWQ_ERR_HIP
+ * ("no error" if there was none).  Static string owned by the HIP runtime. */
+const char* glowq_last_hip_error(void);
+
 /* Argument check of one unit exactly as the forward calls perform it (HOST
  * only, no GPU access).  check_pointers == 0 skips the NULL / alignment tests so
  * that shapes can be validated before buffers exist. */
@@ -87,10 +91,11 @@ glowq_status glowq_validate_unit(const glowq_unit* u, int32_t check_pointers);
 
 /* ---- weight preparation (one-off, at load time) --------------------------
  * The kernels read weights from a tiled layout in which one 64-lane wavefront
- * fetches 32 rows x 64 input channels with a single contiguous 1 KiB load and
+ * fetches 16 rows x 128 input channels with a single contiguous 1 KiB load and
  * every lane's four words are already in matrix-core operand order; scales and
- * zero-points are stored as (s, z) pairs, transposed so that the 32 rows of a
- * tile are contiguous.  glowq_prepared_bytes gives the size of that buffer,
+ * zero-points are stored as (s, z) pairs, transposed so that the 16 rows of a
+ * tile are contiguous.  d_in must be a multiple of 128, d_out a multiple of 8.
+ * glowq_prepared_bytes gives the size of that buffer,
  * glowq_prepare_weights fills it from the canonical W4A16 arrays:
  *   wq      DEVICE uint32 [d_out][d_in/8], element 8j+e of a row in bits 4e..4e+3 of word j
  *   scales  DEVICE binary16 [d_out][d_in/G]

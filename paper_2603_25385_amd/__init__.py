@@ -7,4 +7,4 @@ The work is done by hand-written HIP kernels behind `include/glowq.h`; this
 package only marshals arguments.  Importing it without a built library raises.
 """
 from .binding import *  # noqa: F401,F403
-from .binding import EXPORTED, GlowqError, glowq_module, glowq_unit, make_module, make_unit  # noqa: F401
+from .binding import EXPORTED, GlowqError, glowq_module, glowq_unit, make_module, make_unit, pack_mask, pack_units  # noqa: F401

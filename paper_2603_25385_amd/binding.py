@@ -35,16 +35,34 @@ class glowq_unit(ctypes.Structure):
                 ("out_dtype", ctypes.c_int32)]
 
 
+def _share_hip_runtime_with_torch() -> None:
+    """One process must hold ONE HIP runtime.  A PyTorch-ROCm wheel bundles its own
+    libamdhip64; if this library pulled in the system copy first, torch would then be
+    bound to a runtime that does not match its bundled HSA layer and no device would
+    be found.  So when torch is installed, its copy is loaded first (without importing
+    torch) and libglowq.so resolves its HIP symbols against it."""
+    import importlib.util
+
+    spec = importlib.util.find_spec("torch")
+    if spec is None or not spec.submodule_search_locations:
+        return
+    path = os.path.join(list(spec.submodule_search_locations)[0], "lib", "libamdhip64.so")
+    if os.path.exists(path):
+        ctypes.CDLL(path, mode=ctypes.RTLD_GLOBAL)
+
+
 def _load():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(
-            f"{_LIB_PATH} is missing: build it with `python -m paper_2603_25385_amd.build` "
+            f"{_LIB_PATH} is missing: build it with `python paper_2603_25385_amd/csrc/build.py` "
             "(there is no fallback path)")
+    _share_hip_runtime_with_torch()
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     up = ctypes.POINTER(glowq_unit)
     sigs = {
         "glowq_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+        "glowq_last_hip_error": (ctypes.c_char_p, []),
         "glowq_validate_unit": (ctypes.c_int, [up, i32]),
         "glowq_prepared_bytes": (ctypes.c_int, [i32, i32, i32, ctypes.POINTER(sz)]),
         "glowq_prepare_weights": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, vp, vp]),
@@ -68,7 +86,8 @@ _lib, EXPORTED = _load()
 class GlowqError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {glowq_status_string(status)} ({status})")
+        detail = f" [{glowq_last_hip_error()}]" if status == GLOWQ_ERR_HIP else ""
+        super().__init__(f"{where}: {glowq_status_string(status)} ({status}){detail}")
 
 
 def _check(status: int, where: str) -> None:
@@ -89,7 +108,9 @@ def make_unit(X: int, B: int, modules: Sequence[glowq_module], T: int, d_in: int
     return u
 
 
-def _units_array(units: Sequence[glowq_unit]):
+def _units_array(units):
+    if isinstance(units, ctypes.Array):      # already packed by pack_units()
+        return units
     arr = (glowq_unit * len(units))()
     for i, u in enumerate(units):
         ctypes.memmove(ctypes.byref(arr[i]), ctypes.byref(u), ctypes.sizeof(glowq_unit))
@@ -97,8 +118,22 @@ def _units_array(units: Sequence[glowq_unit]):
     return arr
 
 
+def pack_units(units: Sequence[glowq_unit]):
+    """Pack unit descriptors into one C array once, for callers that issue the same
+    glowq_block_forward / glowq_workspace_bytes call many times."""
+    return _units_array(list(units))
+
+
+def pack_mask(restore_mask) -> "ctypes.Array":
+    return (ctypes.c_uint8 * len(restore_mask))(*[1 if b else 0 for b in restore_mask])
+
+
 def glowq_status_string(status: int) -> str:
     return _lib.glowq_status_string(status).decode()
+
+
+def glowq_last_hip_error() -> str:
+    return _lib.glowq_last_hip_error().decode()
 
 
 def glowq_validate_unit(unit: glowq_unit, check_pointers: bool = True) -> int:
@@ -149,8 +184,10 @@ def glowq_block_forward(units: Sequence[glowq_unit], restore_mask: Optional[byte
                         workspace: int, workspace_bytes: int, stream: int = 0) -> None:
     arr = _units_array(units)
     mask = None
-    if restore_mask is not None:
-        mask = (ctypes.c_uint8 * len(units))(*[1 if b else 0 for b in restore_mask])
+    if isinstance(restore_mask, ctypes.Array):
+        mask = restore_mask
+    elif restore_mask is not None:
+        mask = pack_mask(restore_mask)
     _check(_lib.glowq_block_forward(arr, len(units), mask, workspace or None, workspace_bytes,
                                     stream or None), "glowq_block_forward")
 

@@ -12,19 +12,17 @@ static inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0;
 UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   UnitWorkspace w;
   w.base = base;
-  const int mblocks = (u.T + 31) / 32;
+  const int tblocks = (u.T + 15) / 16;
   w.off_counters = sizeof(Control);
-  w.ctl_bytes = align_up(w.off_counters + (size_t)mblocks * 4, 256);
+  w.ctl_bytes = align_up(w.off_counters + (size_t)tblocks * 4, 256);
   // K slices of the projection: decode spreads B over many compute units; prefill
-  // already has T / 32 token blocks and only needs enough slices to fill the chip
-  int ksplit;
-  if (is_decode(u.T)) ksplit = 32;
-  else ksplit = (512 + mblocks - 1) / mblocks;
+  // already has T / 16 token blocks and only needs enough slices to fill the chip
+  int ksplit = is_decode(u.T) ? 32 : (256 + tblocks - 1) / tblocks;
   if (ksplit > 32) ksplit = 32;
   if (ksplit < 1) ksplit = 1;
-  int steps = u.d_in / 16;
+  int steps = u.d_in / 32;
   int per = (steps + ksplit - 1) / ksplit;
-  w.kslice = per * 16;
+  w.kslice = per * 32;
   w.ksplit = (u.d_in + w.kslice - 1) / w.kslice;
   w.off_rpart = w.ctl_bytes;
   size_t rpart = (u.r > 0) ? (size_t)w.ksplit * u.T * u.r * sizeof(float) : 0;
@@ -40,8 +38,7 @@ static glowq_status validate(const glowq_unit* u, bool ptrs) {
   if (ptrs && !u->modules) return GLOWQ_ERR_NULL;
   if (u->T < 1 || u->T > (1 << 20)) return GLOWQ_ERR_SHAPE;
   if (u->group_size != 64 && u->group_size != 128) return GLOWQ_ERR_SHAPE;
-  if (u->d_in < u->group_size || u->d_in > (1 << 16) || u->d_in % u->group_size)
-    return GLOWQ_ERR_SHAPE;
+  if (u->d_in < 128 || u->d_in > (1 << 16) || u->d_in % 128) return GLOWQ_ERR_SHAPE;
   if (u->r < 0 || u->r > GLOWQ_MAX_RANK || u->r % 8) return GLOWQ_ERR_SHAPE;
   if (u->act_dtype != GLOWQ_F16 && u->act_dtype != GLOWQ_BF16) return GLOWQ_ERR_DTYPE;
   if (u->out_dtype != u->act_dtype && u->out_dtype != GLOWQ_F32) return GLOWQ_ERR_DTYPE;
@@ -67,19 +64,24 @@ static glowq_status validate(const glowq_unit* u, bool ptrs) {
 
 static glowq_status check_weights_shape(int d_out, int d_in, int G) {
   if (G != 64 && G != 128) return GLOWQ_ERR_SHAPE;
-  if (d_in < G || d_in > (1 << 16) || d_in % G) return GLOWQ_ERR_SHAPE;
+  if (d_in < 128 || d_in > (1 << 16) || d_in % 128) return GLOWQ_ERR_SHAPE;
   if (d_out < 8 || d_out > (1 << 20) || d_out % 8) return GLOWQ_ERR_SHAPE;
   return GLOWQ_OK;
 }
 
-static inline glowq_status hip_status(hipError_t e) { return e == hipSuccess ? GLOWQ_OK : GLOWQ_ERR_HIP; }
+static thread_local hipError_t g_last_hip_error = hipSuccess;
+static inline glowq_status hip_status(hipError_t e) {
+  if (e == hipSuccess) return GLOWQ_OK;
+  g_last_hip_error = e;
+  return GLOWQ_ERR_HIP;
+}
 
 static glowq_status forward_one(const glowq_unit& u, bool restore, char* ws_base, hipStream_t st) {
   UnitWorkspace ws = plan_unit_workspace(u, ws_base);
   const bool corr = restore && u.r > 0;
   if (corr) {
     hipError_t e = launch_proj(u, ws, nullptr, true, st);
-    if (e != hipSuccess) return GLOWQ_ERR_HIP;
+    if (e != hipSuccess) return hip_status(e);
   }
   hipError_t e = is_decode(u.T) ? launch_decode(u, ws, corr, st) : launch_prefill(u, ws, corr, st);
   return hip_status(e);
@@ -104,6 +106,8 @@ const char* glowq_status_string(glowq_status s) {
   }
   return "unknown status";
 }
+
+const char* glowq_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 glowq_status glowq_validate_unit(const glowq_unit* u, int32_t check_pointers) {
   return validate(u, check_pointers != 0);

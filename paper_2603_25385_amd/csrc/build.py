@@ -1,9 +1,11 @@
 """Build libglowq.so (the C-ABI library) for gfx950 with hipcc.
 
-    python -m paper_2603_25385_amd.build
+    python paper_2603_25385_amd/csrc/build.py
 
 The library lands in paper_2603_25385_amd/lib/ (git-ignored, in-tree so that a
-snapshot of the tree carries it to the GPU machine).
+snapshot of the tree carries it to the GPU machine).  This file is a plain script on
+purpose: it must run when the library does not exist yet, so it cannot live
+behind the package import, which loads the library.
 """
 from __future__ import annotations
 
@@ -11,9 +13,8 @@ import os
 import subprocess
 import sys
 
-HERE = os.path.dirname(os.path.abspath(__file__))
-CSRC = os.path.join(HERE, "csrc")
-LIB_DIR = os.path.join(HERE, "lib")
+CSRC = os.path.dirname(os.path.abspath(__file__))
+LIB_DIR = os.path.join(os.path.dirname(CSRC), "lib")
 LIB = os.path.join(LIB_DIR, "libglowq.so")
 SOURCES = ["api.hip", "prepare.hip", "proj.hip", "decode.hip", "prefill.hip"]
 # packed-fp32 instructions are switched off for device code on purpose

@@ -19,32 +19,34 @@ enum Act { ACT_F16 = 0, ACT_BF16 = 1 };
 
 // ---------------------------------------------------------------------------
 // Prepared layout of one module's weights (built by prepare.hip):
-//   tiles : [rows32][d_in/64][64 lanes][4 words]   one tile = 32 rows x 64 channels = 1 KiB
-//           lane l holds row 32*rb + (l & 31), channels 64*kb + 32*(l >> 5) + 8*j + e
-//           in word j; inside a word, nibble i holds e = 2i and nibble i + 4 holds
-//           e = 2i + 1, so that ((w >> 4i) & 0x000F000F) is the pair (e = 2i, e = 2i + 1)
-//   sz    : [d_in/G][rows32 * 32] words, low half = scale bits, high half = zero-point bits
-// rows32 = ceil(d_out / 32); rows past d_out hold q = 0, s = 1, z = 0 (dequantise to 0).
+//   tiles : [rows16][d_in/128][64 lanes][4 words]  one tile = 16 rows x 128 channels = 1 KiB
+//           lane l holds row 16*rb + (l & 15); word j of lane l holds channels
+//           128*kb + 32*j + 8*(l >> 4) + e, e = 0..7 -- exactly the B operand of one
+//           16x16x32 matrix-core instruction per word; inside a word, nibble i holds
+//           e = 2i and nibble i + 4 holds e = 2i + 1, so that ((w >> 4i) & 0x000F000F)
+//           is the pair (e = 2i, e = 2i + 1)
+//   sz    : [d_in/G][rows16 * 16] words, low half = scale bits, high half = zero-point bits
+// rows16 = ceil(d_out / 16); rows past d_out hold q = 0, s = 1, z = 0 (dequantise to 0).
 // ---------------------------------------------------------------------------
 struct PreparedView {
   const u32x4_t* tiles;
   const uint32_t* sz;
-  int rows32;   // 32-row blocks
-  int ktiles;   // d_in / 64
+  int rows16;   // 16-row blocks
+  int ktiles;   // d_in / 128
 };
 
 __host__ __device__ inline size_t prepared_tile_bytes(int d_out, int d_in) {
-  return (size_t)((d_out + 31) / 32) * 32 * (size_t)d_in / 2;
+  return (size_t)((d_out + 15) / 16) * 16 * (size_t)d_in / 2;
 }
 __host__ __device__ inline size_t prepared_total_bytes(int d_out, int d_in, int G) {
-  return prepared_tile_bytes(d_out, d_in) + (size_t)(d_in / G) * ((d_out + 31) / 32) * 32 * 4;
+  return prepared_tile_bytes(d_out, d_in) + (size_t)(d_in / G) * ((d_out + 15) / 16) * 16 * 4;
 }
 __host__ __device__ inline PreparedView prepared_view(const void* p, int d_out, int d_in) {
   PreparedView v;
   v.tiles = (const u32x4_t*)p;
   v.sz = (const uint32_t*)((const char*)p + prepared_tile_bytes(d_out, d_in));
-  v.rows32 = (d_out + 31) / 32;
-  v.ktiles = d_in / 64;
+  v.rows16 = (d_out + 15) / 16;
+  v.ktiles = d_in / 128;
   return v;
 }
 
@@ -74,22 +76,44 @@ template <> struct GroupConst<ACT_BF16> {
 // Eight dequantised weights of one prepared word, in channel order e = 0..7,
 // as four 32-bit registers of packed 16-bit values (a matrix-core operand).
 //
-// binary16: the pair (1024 + q_a, 1024 + q_b) is made by OR-ing the nibbles into
-// the fraction of 0x6400; adding -(1024 + z) is exact, and the packed multiply by
-// s rounds once, to nearest even -- the definition of the stored weight.
+// binary16: (q - z) is formed exactly (see q_minus_z_f16) and the packed multiply
+// by s rounds once, to nearest even -- the definition of the stored weight.
 // bfloat16: q widens to fp32 exactly, fma(q, s, -z s) is exact in fp32, and the
 // packed fp32 -> bf16 conversion rounds once, to nearest even.
 template <int ACT>
 __device__ inline u32x4_t dequant_word(uint32_t w, const GroupConst<ACT>& g);
 
-template <>
-__device__ inline u32x4_t dequant_word<ACT_F16>(uint32_t w, const GroupConst<ACT_F16>& g) {
+// (x & mask) | magic in one instruction; the mask travels in a scalar register and the
+// magic constant in a vector register (gfx9 three-operand encodings take no literals)
+__device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) {
+  uint32_t r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(magic));
+  return r;
+}
+
+// The eight values (q - z) of one prepared word as binary16 pairs, exact: the pair
+// (1024 + q_a, 1024 + q_b) is made by OR-ing two nibbles into the fraction of 0x6400,
+// and adding -(1024 + z) cancels the offset and the zero-point in one packed add.
+__device__ inline u32x4_t q_minus_z_f16(uint32_t w, half2_t nb2) {
+  const uint32_t magic = 0x64006400u;
   u32x4_t out;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    uint32_t t = ((w >> (4 * i)) & 0x000F000Fu) | 0x64006400u;
-    half2_t v = __builtin_bit_cast(half2_t, t);
-    v = (v + g.nb2) * g.s2;
+    uint32_t t = and_or(w >> (4 * i), 0x000F000Fu, magic);
+    half2_t v = __builtin_bit_cast(half2_t, t) + nb2;
+    out[i] = __builtin_bit_cast(uint32_t, v);
+  }
+  return out;
+}
+
+template <>
+__device__ inline u32x4_t dequant_word<ACT_F16>(uint32_t w, const GroupConst<ACT_F16>& g) {
+  u32x4_t d = q_minus_z_f16(w, g.nb2);
+  u32x4_t out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t di = d[i];   // (bit_cast of a vector element lvalue reads element 0)
+    half2_t v = __builtin_bit_cast(half2_t, di) * g.s2;   // the one rounding
     out[i] = __builtin_bit_cast(uint32_t, v);
   }
   return out;
@@ -122,17 +146,18 @@ __device__ inline uint32_t prepared_nibble(uint32_t w, int e) {
   return (w >> (4 * (e >> 1) + 16 * (e & 1))) & 0xFu;
 }
 
-// D(32x32, fp32) += A(32x16) * B(16x32).  Lane l supplies row (l & 31) of A and
-// column (l & 31) of B, eight consecutive k each, k-half (l >> 5); any k order is
-// fine as long as both operands use the same one.  D: lane l holds column (l & 31),
-// rows 8*(i/4) + 4*(l >> 5) + (i & 3) in element i.
+// D(16x16, fp32) += A(16x32) * B(32x16).  Lane l supplies row (l & 15) of A and
+// column (l & 15) of B, eight k values each, k group (l >> 4); the eight values of
+// lane l in A pair with the eight values of lane l in B, so any k order is fine as
+// long as both operands use the same one.  D: lane l holds column (l & 15), rows
+// 4*(l >> 4) + v in element v.
 template <int ACT>
-__device__ inline float16_t mfma32(u32x4_t a, u32x4_t b, float16_t c) {
+__device__ inline float4_t mfma16(u32x4_t a, u32x4_t b, float4_t c) {
   if constexpr (ACT == ACT_F16) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
                                                   __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
   } else {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
   }
 }

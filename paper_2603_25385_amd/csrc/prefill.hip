@@ -1,13 +1,14 @@
 // Prefill path (T > 32 tokens): Y_i = X dequant(W_q,i)^T + R A_i^T  (paper Eq. 9)
 // as a tiled matrix-core GEMM with the correction folded in as r extra channels.
 //
-// Workgroup tile: (32 MB) tokens x 256 rows, four waves, each wave 64 rows x all
+// Workgroup tile: (16 MB) tokens x 256 rows, four waves, each wave 64 rows x all
 // tokens of the tile.  The packed weights never pass through LDS: a wave fetches
-// its 32-row x 64-channel tiles with one contiguous 1 KiB load each, already in
-// operand order, dequantises a word into eight 16-bit values in registers and
-// feeds them to the matrix core as the A operand; because every wave covers all
-// tokens of the tile, each weight is dequantised once per workgroup.  X is staged
-// through LDS (double buffered, one barrier per 64 channels) and read back as the
+// its 16-row x 128-channel tiles with one contiguous 1 KiB load each, already in
+// operand order, dequantises a word into eight 16-bit values in registers (one
+// rounding, the stored weight exactly) and feeds them to the matrix core as the A
+// operand of a 16x16x32 instruction; because every wave covers all tokens of the
+// tile, each weight is dequantised once per workgroup.  X is staged through LDS in
+// 64-channel stages (double buffered, one barrier per stage) and read back as the
 // B operand with 128-bit reads; the row pitch of 144 bytes keeps those reads
 // conflict free.  D is [row][token], so a lane ends up with four consecutive rows
 // of one token and stores them with one 8- or 16-byte write.
@@ -24,7 +25,7 @@ struct PfModule {
   const uint32_t* sz;
   const uint16_t* A;
   void* Y;
-  int d_out, ldy, rows32, nt_start;   // nt_start: first 256-row tile of this module
+  int d_out, ldy, rows16, nt_start;   // nt_start: first 256-row tile of this module
 };
 
 struct PrefillArgs {
@@ -39,8 +40,9 @@ struct PrefillArgs {
 
 template <int ACT, int MB>
 __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t xs[];   // [2][32 MB][PF_PITCH]
-  constexpr int MT = 32 * MB;
+  extern __shared__ __attribute__((aligned(16))) uint16_t xs[];   // [2][16 MB][PF_PITCH]
+  constexpr int MT = 16 * MB;
+  constexpr int XP = MT / 32;     // X rows per thread and stage
 
   const int mt = (int)(blockIdx.x % (unsigned)a.n_mtiles);
   const int nt = (int)(blockIdx.x / (unsigned)a.n_mtiles);
@@ -50,149 +52,160 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
     if (i < a.n_modules && nt >= a.mod[i].nt_start) mi = i;
   const PfModule& M = a.mod[mi];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int m = lane & 31, h = lane >> 5;
-  const int ktiles = a.K >> 6;
-  const int rows_pad = M.rows32 * 32;
-  const int gshift = (a.G == 128) ? 1 : 0;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 15, kq = lane >> 4;
+  const int ktiles = a.K >> 7;
+  const int rows_pad = M.rows16 * 16;
+  const bool g128 = (a.G == 128);
 
-  // this wave's two 32-row blocks
-  const int nb0 = (nt - M.nt_start) * 8 + 2 * wave;
-  const bool valid[2] = {nb0 < M.rows32, nb0 + 1 < M.rows32};
-  const u32x4_t* wt[2];
-  const uint32_t* szp[2];
+  // this wave's four 16-row blocks
+  const int nb0 = (nt - M.nt_start) * 16 + 4 * wave;
+  bool valid[4];
+  const u32x4_t* wt[4];
+  const uint32_t* szp[4];
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
+  for (int b = 0; b < 4; ++b) {
+    valid[b] = nb0 + b < M.rows16;
     const int nb = valid[b] ? nb0 + b : 0;
     wt[b] = M.tiles + (size_t)nb * ktiles * 64 + lane;
-    szp[b] = M.sz + nb * 32 + m;
+    szp[b] = M.sz + nb * 16 + n;
   }
 
-  // X stage: thread -> (row = tid / 8 + 32 p, 16-byte chunk = tid % 8)
+  // X stage: thread -> (row = tid / 8 + 32 p, 16-byte chunk = tid % 8); rows past T
+  // re-read the last valid token (their columns of D are never stored)
   const int xr = tid >> 3, xc = tid & 7;
   const int tok0 = mt * MT;
-  const uint16_t* xg = a.X + (size_t)(tok0 + xr) * a.K + xc * 8;
+  const uint16_t* xg[XP];
+#pragma unroll
+  for (int p = 0; p < XP; ++p)
+    xg[p] = a.X + (size_t)min(tok0 + xr + 32 * p, a.T - 1) * a.K + xc * 8;
 
-  float16_t acc[2][MB];
+  float4_t acc[4][MB];
 #pragma unroll
-  for (int b = 0; b < 2; ++b)
+  for (int b = 0; b < 4; ++b)
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[b][mb][i] = 0.f;
+    for (int mb = 0; mb < MB; ++mb) acc[b][mb] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-  u32x4_t xreg[MB];
-  u32x4_t wcur[2], wnext[2];
-  uint32_t szcur[2] = {0x3C00u, 0x3C00u}, sznext[2] = {0x3C00u, 0x3C00u};
+  u32x4_t xreg[XP];
+  u32x4_t wcur[4], wnext[4];
+  uint32_t szcur[4][2], sznext[4][2];
 
-  auto load_stage = [&](int kt) {
+  auto load_x = [&](int stage) {
 #pragma unroll
-    for (int p = 0; p < MB; ++p) {
-      xreg[p] = u32x4_t{0u, 0u, 0u, 0u};
-      if (tok0 + xr + 32 * p < a.T)
-        xreg[p] = *(const u32x4_t*)(xg + (size_t)(32 * p) * a.K + kt * 64);
-    }
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      wnext[b] = u32x4_t{0u, 0u, 0u, 0u};
-      if (valid[b]) {
-        wnext[b] = __builtin_nontemporal_load(wt[b] + (size_t)kt * 64);
-        sznext[b] = szp[b][(size_t)(kt >> gshift) * rows_pad];
-      }
-    }
+    for (int p = 0; p < XP; ++p) xreg[p] = *(const u32x4_t*)(xg[p] + stage * 64);
   };
-  auto store_stage = [&](int buf) {
+  auto store_x = [&](int buf) {
     uint16_t* dst = xs + (size_t)buf * MT * PF_PITCH + xr * PF_PITCH + xc * 8;
 #pragma unroll
-    for (int p = 0; p < MB; ++p) *(u32x4_t*)(dst + 32 * p * PF_PITCH) = xreg[p];
+    for (int p = 0; p < XP; ++p) *(u32x4_t*)(dst + 32 * p * PF_PITCH) = xreg[p];
+  };
+  auto load_w = [&](int kt) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      wnext[b] = __builtin_nontemporal_load(wt[b] + (size_t)kt * 64);
+      if (g128) {
+        sznext[b][0] = szp[b][(size_t)kt * rows_pad];
+        sznext[b][1] = sznext[b][0];
+      } else {
+        sznext[b][0] = szp[b][(size_t)(2 * kt) * rows_pad];
+        sznext[b][1] = szp[b][(size_t)(2 * kt + 1) * rows_pad];
+      }
+    }
+  };
+  auto take_w = [&]() {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      wcur[b] = wnext[b];
+      szcur[b][0] = sznext[b][0];
+      szcur[b][1] = sznext[b][1];
+    }
   };
 
-  load_stage(0);
-  store_stage(0);
-  wcur[0] = wnext[0];
-  wcur[1] = wnext[1];
-  szcur[0] = sznext[0];
-  szcur[1] = sznext[1];
+  load_x(0);
+  load_w(0);
+  store_x(0);
+  take_w();
   __syncthreads();
 
+  const int nstages = 2 * ktiles;
   for (int kt = 0; kt < ktiles; ++kt) {
-    if (kt + 1 < ktiles) load_stage(kt + 1);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int stage = 2 * kt + half;
+      if (stage + 1 < nstages) load_x(stage + 1);
+      if (half == 0 && kt + 1 < ktiles) load_w(kt + 1);
 
-    const uint16_t* xb = xs + (size_t)(kt & 1) * MT * PF_PITCH + m * PF_PITCH + 32 * h;
-    GroupConst<ACT> g[2];
-    g[0].set(szcur[0]);
-    g[1].set(szcur[1]);
+      const uint16_t* xb = xs + (size_t)(stage & 1) * MT * PF_PITCH + n * PF_PITCH + 8 * kq;
+      GroupConst<ACT> g[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      u32x4_t wf0 = dequant_word<ACT>(wcur[0][j], g[0]);
-      u32x4_t wf1 = dequant_word<ACT>(wcur[1][j], g[1]);
+      for (int b = 0; b < 4; ++b) g[b].set(szcur[b][half]);
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        u32x4_t xf = *(const u32x4_t*)(xb + mb * 32 * PF_PITCH + 8 * j);
-        if (valid[0]) acc[0][mb] = mfma32<ACT>(wf0, xf, acc[0][mb]);   // D[row][token]
-        if (valid[1]) acc[1][mb] = mfma32<ACT>(wf1, xf, acc[1][mb]);
+      for (int jj = 0; jj < 2; ++jj) {
+        const int j = 2 * half + jj;
+        u32x4_t wf[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) wf[b] = dequant_word<ACT>(wcur[b][j], g[b]);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const u32x4_t xf = *(const u32x4_t*)(xb + mb * 16 * PF_PITCH + 32 * jj);
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (valid[b]) acc[b][mb] = mfma16<ACT>(wf[b], xf, acc[b][mb]);   // D[row][token]
+        }
       }
-    }
 
-    if (kt + 1 < ktiles) {
-      store_stage((kt + 1) & 1);
-      wcur[0] = wnext[0];
-      wcur[1] = wnext[1];
-      szcur[0] = sznext[0];
-      szcur[1] = sznext[1];
+      if (stage + 1 < nstages) store_x((stage + 1) & 1);
+      __syncthreads();
     }
-    __syncthreads();
+    if (kt + 1 < ktiles) take_w();
   }
 
-  // correction: r more channels, operand [A_i] against [R]
+  // correction: r more channels, operand [A_i] against [R]; every lane runs the same
+  // trip count, lanes past the rank contribute zeros on both sides
   if (a.restore) {
-    // the trip count is the same for every lane (matrix-core instructions must not sit
-    // under a divergent branch); a half-wave past the rank contributes zeros
-    for (int jj = 0; jj * 16 < a.r; ++jj) {
-      const int j0 = jj * 16 + 8 * h;
-      const bool j_ok = j0 < a.r;
-      u32x4_t af[2];
+    for (int jj = 0; jj * 32 < a.r; ++jj) {
+      const int j0 = jj * 32 + 8 * kq;
+      const bool ok = j0 < a.r;
+      const int j0c = ok ? j0 : 0;
+      u32x4_t af[4];
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        af[b] = u32x4_t{0u, 0u, 0u, 0u};
-        const int row = (nb0 + b) * 32 + m;
-        if (j_ok && valid[b] && row < M.d_out)
-          af[b] = *(const u32x4_t*)(M.A + (size_t)row * a.r + j0);
+      for (int b = 0; b < 4; ++b) {
+        const int row = min((nb0 + b) * 16 + n, M.d_out - 1);
+        af[b] = *(const u32x4_t*)(M.A + (size_t)row * a.r + j0c);
+        if (!ok) af[b] = u32x4_t{0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        const int tok = tok0 + mb * 32 + m;
-        u32x4_t rf = {0u, 0u, 0u, 0u};
-        if (j_ok && tok < a.T) rf = *(const u32x4_t*)(a.R16 + (size_t)tok * a.r + j0);
-        if (valid[0]) acc[0][mb] = mfma32<ACT>(af[0], rf, acc[0][mb]);
-        if (valid[1]) acc[1][mb] = mfma32<ACT>(af[1], rf, acc[1][mb]);
+        const int tok = min(tok0 + mb * 16 + n, a.T - 1);
+        u32x4_t rf = *(const u32x4_t*)(a.R16 + (size_t)tok * a.r + j0c);
+        if (!ok) rf = u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          if (valid[b]) acc[b][mb] = mfma16<ACT>(af[b], rf, acc[b][mb]);
       }
     }
   }
 
-  // store: lane holds token (mb, m) and rows 8 q + 4 h + {0..3} of each 32-row block
+  // store: lane holds token (mb, n) and rows 4 kq + {0..3} of each 16-row block
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
+  for (int b = 0; b < 4; ++b) {
     if (!valid[b]) continue;
+    const int row = (nb0 + b) * 16 + 4 * kq;
+    if (row >= M.d_out) continue;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-      const int tok = tok0 + mb * 32 + m;
+      const int tok = tok0 + mb * 16 + n;
       if (tok >= a.T) continue;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int row = (nb0 + b) * 32 + 8 * q + 4 * h;
-        if (row >= M.d_out) continue;
-        const size_t off = (size_t)tok * M.ldy + row;
-        const float v0 = acc[b][mb][4 * q], v1 = acc[b][mb][4 * q + 1];
-        const float v2 = acc[b][mb][4 * q + 2], v3 = acc[b][mb][4 * q + 3];
-        if (a.out_f32) {
-          *(float4_t*)((float*)M.Y + off) = float4_t{v0, v1, v2, v3};
-        } else {
-          uint2 pk;
-          pk.x = (uint32_t)to_act16<ACT>(v0) | ((uint32_t)to_act16<ACT>(v1) << 16);
-          pk.y = (uint32_t)to_act16<ACT>(v2) | ((uint32_t)to_act16<ACT>(v3) << 16);
-          *(uint2*)((uint16_t*)M.Y + off) = pk;
-        }
+      const size_t off = (size_t)tok * M.ldy + row;
+      const float4_t v = acc[b][mb];
+      if (a.out_f32) {
+        *(float4_t*)((float*)M.Y + off) = v;
+      } else {
+        uint2 pk;
+        pk.x = (uint32_t)to_act16<ACT>(v[0]) | ((uint32_t)to_act16<ACT>(v[1]) << 16);
+        pk.y = (uint32_t)to_act16<ACT>(v[2]) | ((uint32_t)to_act16<ACT>(v[3]) << 16);
+        *(uint2*)((uint16_t*)M.Y + off) = pk;
       }
     }
   }
@@ -200,11 +213,13 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
 
 template <int ACT, int MB>
 static hipError_t launch_prefill_t(const PrefillArgs& a, int n_ntiles, hipStream_t st) {
-  const size_t lds = (size_t)2 * 32 * MB * PF_PITCH * sizeof(uint16_t);
+  const size_t lds = (size_t)2 * 16 * MB * PF_PITCH * sizeof(uint16_t);
   auto kern = k_prefill<ACT, MB>;
-  hipError_t e = hipFuncSetAttribute((const void*)kern,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
   dim3 grid((unsigned)(a.n_mtiles * n_ntiles)), block(PF_WAVES * 64);
   kern<<<grid, block, lds, st>>>(a);
   return hipGetLastError();
@@ -223,9 +238,9 @@ hipError_t launch_prefill(const glowq_unit& u, const UnitWorkspace& ws, bool res
     a.mod[i].Y = m.Y;
     a.mod[i].d_out = m.d_out;
     a.mod[i].ldy = m.ldy;
-    a.mod[i].rows32 = v.rows32;
+    a.mod[i].rows16 = v.rows16;
     a.mod[i].nt_start = nt;
-    nt += (v.rows32 + 7) / 8;
+    nt += (v.rows16 + 15) / 16;
   }
   for (int i = u.n_modules; i < GLOWQ_MAX_MODULES; ++i) a.mod[i] = a.mod[0];
   a.n_modules = u.n_modules;
@@ -240,14 +255,14 @@ hipError_t launch_prefill(const glowq_unit& u, const UnitWorkspace& ws, bool res
   const bool f16 = (u.act_dtype == GLOWQ_F16);
   if (u.T <= 64) {
     a.n_mtiles = (u.T + 63) / 64;
-    return f16 ? launch_prefill_t<ACT_F16, 2>(a, nt, st) : launch_prefill_t<ACT_BF16, 2>(a, nt, st);
+    return f16 ? launch_prefill_t<ACT_F16, 4>(a, nt, st) : launch_prefill_t<ACT_BF16, 4>(a, nt, st);
   }
   if (u.T <= 128) {
     a.n_mtiles = (u.T + 127) / 128;
-    return f16 ? launch_prefill_t<ACT_F16, 4>(a, nt, st) : launch_prefill_t<ACT_BF16, 4>(a, nt, st);
+    return f16 ? launch_prefill_t<ACT_F16, 8>(a, nt, st) : launch_prefill_t<ACT_BF16, 8>(a, nt, st);
   }
   a.n_mtiles = (u.T + 255) / 256;
-  return f16 ? launch_prefill_t<ACT_F16, 8>(a, nt, st) : launch_prefill_t<ACT_BF16, 8>(a, nt, st);
+  return f16 ? launch_prefill_t<ACT_F16, 16>(a, nt, st) : launch_prefill_t<ACT_BF16, 16>(a, nt, st);
 }
 
 }  // namespace glowq

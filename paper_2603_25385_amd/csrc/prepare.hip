@@ -14,14 +14,14 @@ __global__ void k_prepare_tiles(const uint32_t* __restrict__ wq, uint32_t* __res
                                 int d_out, int d_in, long long n_words) {
   long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n_words) return;
-  const int ktiles = d_in / 64;
+  const int ktiles = d_in / 128;
   int j = (int)(idx & 3);
   int lane = (int)((idx >> 2) & 63);
   long long tile = idx >> 8;
   int kb = (int)(tile % ktiles);
   int rb = (int)(tile / ktiles);
-  int row = rb * 32 + (lane & 31);
-  int k0 = kb * 64 + 32 * (lane >> 5) + 8 * j;
+  int row = rb * 16 + (lane & 15);
+  int k0 = kb * 128 + 32 * j + 8 * (lane >> 4);
   uint32_t c = 0;
   if (row < d_out) c = wq[(long long)row * (d_in / 8) + k0 / 8];
   uint32_t w = 0;
@@ -49,9 +49,9 @@ __global__ void k_prepare_sz(const uint16_t* __restrict__ scales,
 }
 
 __device__ inline uint32_t load_prepared_word(const PreparedView& v, int row, int k) {
-  int rb = row >> 5, kb = k >> 6;
-  int lane = (row & 31) + 32 * ((k >> 5) & 1);
-  int j = (k >> 3) & 3;
+  int rb = row >> 4, kb = k >> 7;
+  int lane = (row & 15) + 16 * ((k >> 3) & 3);
+  int j = (k >> 5) & 3;
   const uint32_t* t = (const uint32_t*)v.tiles;
   return t[(((long long)rb * v.ktiles + kb) * 64 + lane) * 4 + j];
 }
@@ -85,7 +85,7 @@ __global__ void k_debug_dequant(const void* prepared, int d_out, int d_in, int G
   PreparedView v = prepared_view(prepared, d_out, d_in);
   uint32_t w = load_prepared_word(v, row, k);
   GroupConst<ACT> g;
-  g.set(v.sz[(long long)(k / G) * (v.rows32 * 32) + row]);
+  g.set(v.sz[(long long)(k / G) * (v.rows16 * 16) + row]);
   u32x4_t d = dequant_word<ACT>(w, g);
   *(u32x4_t*)(w_out + (long long)row * d_in + k) = d;
 }
@@ -94,7 +94,7 @@ hipError_t launch_prepare(const uint32_t* wq, const uint16_t* scales, const uint
                           int d_out, int d_in, int G, void* prepared, hipStream_t st) {
   PreparedView v = prepared_view(prepared, d_out, d_in);
   long long n_words = (long long)prepared_tile_bytes(d_out, d_in) / 4;
-  int rows_pad = v.rows32 * 32, n_groups = d_in / G;
+  int rows_pad = v.rows16 * 16, n_groups = d_in / G;
   k_prepare_tiles<<<dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st>>>(
       wq, (uint32_t*)v.tiles, d_out, d_in, n_words);
   long long n_sz = (long long)rows_pad * n_groups;

@@ -3,7 +3,7 @@
 //
 // The contraction is split over K slices so that even a one-token call spreads
 // the 2 r d_in bytes of B over many compute units.  Each workgroup owns one
-// (32-token block, K slice): its waves take the slice's 16-channel steps round
+// (16-token block, K slice): its waves take the slice's 32-channel steps round
 // robin, multiply on the matrix cores straight from global memory (both operands
 // are k-contiguous, so a lane's eight values are one 128-bit load), and fold their
 // fp32 tiles through LDS into one partial sum.  The workgroup that arrives last
@@ -52,8 +52,8 @@ ProjArgs make_proj_args(const glowq_unit& u, const UnitWorkspace& ws, float* R32
 hipError_t launch_proj(const glowq_unit& u, const UnitWorkspace& ws, float* R32, bool want_r16,
                        hipStream_t st) {
   ProjArgs a = make_proj_args(u, ws, R32, want_r16);
-  dim3 grid((unsigned)((u.T + 31) / 32), (unsigned)ws.ksplit), block(256);
-  size_t lds = (size_t)(256 / 64) * 16 * 64 * sizeof(float);
+  dim3 grid((unsigned)((u.T + 15) / 16), (unsigned)ws.ksplit), block(256);
+  size_t lds = (size_t)(256 / 64) * 256 * sizeof(float);
   if (u.act_dtype == GLOWQ_F16)
     k_proj<ACT_F16><<<grid, block, lds, st>>>(a);
   else

@@ -11,62 +11,60 @@ struct ProjArgs {
   const uint16_t* B;   // act dtype [r][K]
   int T, K, r;
   int ksplit;          // K slices
-  int kslice;          // channels per slice, multiple of 16
+  int kslice;          // channels per slice, multiple of 32
   float* Rpart;        // fp32 [ksplit][T][r]
   float* R32;          // optional fp32 [T][r]
   uint16_t* R16;       // optional act dtype [T][r]
   Control* ctl;
-  uint32_t* counters;  // one per 32-token block, zero between launches
+  uint32_t* counters;  // one per 16-token block, zero between launches
 };
 
-// One workgroup = (32-token block mb, K slice kz); any whole number of waves.
-// lds: blockDim.x / 64 * 1024 floats.
+// One workgroup = (16-token block tb, K slice kz); any whole number of waves.
+// lds: blockDim.x / 64 * 256 floats.
 template <int ACT>
-__device__ inline void proj_workgroup(const ProjArgs& a, int mb, int kz, float* lds,
+__device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* lds,
                                       bool signal_ready) {
   __shared__ uint32_t s_prev;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
-  const int nbs = (a.r + 31) >> 5;
-  const int m = lane & 31, h = lane >> 5;
-  const int tok = mb * 32 + m;
-  const bool tok_ok = tok < a.T;
+  const int nbs = (a.r + 15) >> 4;
+  const int i = lane & 15, kq = lane >> 4;
+  // tokens past T and ranks past r are computed from clamped (valid, finite) rows and
+  // never stored: row i of D depends on row i of the first operand only, column n on
+  // column n of the second only
+  const int tok = min(tb * 16 + i, a.T - 1);
 
-  float16_t acc[4];
+  float4_t acc[8];
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[nb][i] = 0.f;
+  for (int nb = 0; nb < 8; ++nb) acc[nb] = float4_t{0.f, 0.f, 0.f, 0.f};
 
   const int k_begin = kz * a.kslice;
   const int k_end = min(a.K, k_begin + a.kslice);
-  const uint16_t* xrow = a.X + (size_t)tok * a.K + 8 * h;
-  for (int k = k_begin + wave * 16; k < k_end; k += nw * 16) {
-    u32x4_t xf = {0u, 0u, 0u, 0u};
-    if (tok_ok) xf = *(const u32x4_t*)(xrow + k);
+  const uint16_t* xrow = a.X + (size_t)tok * a.K + 8 * kq;
+  for (int k = k_begin + wave * 32; k < k_end; k += nw * 32) {
+    const u32x4_t xf = *(const u32x4_t*)(xrow + k);
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
+    for (int nb = 0; nb < 8; ++nb) {
       if (nb < nbs) {
-        const int rank = nb * 32 + m;
-        u32x4_t bf = {0u, 0u, 0u, 0u};
-        if (rank < a.r) bf = *(const u32x4_t*)(a.B + (size_t)rank * a.K + k + 8 * h);
-        acc[nb] = mfma32<ACT>(xf, bf, acc[nb]);   // D[token][rank]
+        const int rank = min(nb * 16 + i, a.r - 1);
+        const u32x4_t bf = *(const u32x4_t*)(a.B + (size_t)rank * a.K + k + 8 * kq);
+        acc[nb] = mfma16<ACT>(xf, bf, acc[nb]);   // D[token][rank]
       }
     }
   }
 
   // fold the waves' tiles and store this slice's partial sum
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb) {
+  for (int nb = 0; nb < 8; ++nb) {
     if (nb < nbs) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) lds[(wave * 16 + i) * 64 + lane] = acc[nb][i];
+      for (int v = 0; v < 4; ++v) lds[(wave * 4 + v) * 64 + lane] = acc[nb][v];
       __syncthreads();
-      for (int o = tid; o < 1024; o += blockDim.x) {
-        const int i = o >> 6, ln = o & 63;
+      for (int o = tid; o < 256; o += blockDim.x) {
+        const int v = o >> 6, ln = o & 63;
         float s = 0.f;
-        for (int w = 0; w < nw; ++w) s += lds[(w * 16 + i) * 64 + ln];
-        const int t = mb * 32 + 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
-        const int rank = nb * 32 + (ln & 31);
+        for (int w = 0; w < nw; ++w) s += lds[(w * 4 + v) * 64 + ln];
+        const int t = tb * 16 + 4 * (ln >> 4) + v;
+        const int rank = nb * 16 + (ln & 15);
         if (t < a.T && rank < a.r) a.Rpart[((size_t)kz * a.T + t) * a.r + rank] = s;
       }
       __syncthreads();
@@ -76,12 +74,12 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int mb, int kz, float* 
   // the last slice to arrive for this token block adds the partial sums in slice order
   __threadfence();
   __syncthreads();
-  if (tid == 0) s_prev = atomicAdd(&a.counters[mb], 1u);
+  if (tid == 0) s_prev = atomicAdd(&a.counters[tb], 1u);
   __syncthreads();
   if (s_prev != (uint32_t)(a.ksplit - 1)) return;
   __threadfence();
-  for (int e = tid; e < 32 * a.r; e += blockDim.x) {
-    const int t = mb * 32 + e / a.r, rank = e % a.r;
+  for (int e = tid; e < 16 * a.r; e += blockDim.x) {
+    const int t = tb * 16 + e / a.r, rank = e % a.r;
     if (t < a.T) {
       float s = 0.f;
       for (int z = 0; z < a.ksplit; ++z) s += a.Rpart[((size_t)z * a.T + t) * a.r + rank];
@@ -89,7 +87,7 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int mb, int kz, float* 
       if (a.R16) a.R16[(size_t)t * a.r + rank] = to_act16<ACT>(s);
     }
   }
-  if (tid == 0) a.counters[mb] = 0u;
+  if (tid == 0) a.counters[tb] = 0u;
   if (signal_ready) {
     __threadfence();
     __syncthreads();

@@ -84,22 +84,25 @@ def test_shared_projection(T):
 
 
 def test_token_independence_across_kernel_paths():
-    # column t of a 48-token call (tiled GEMM path) equals the 1-token call (streaming path)
+    # column t of a 48-token call (tiled GEMM path) equals the 1-token call (streaming
+    # path).  The streaming path applies the group scale to the fp32 sum of x (q - z)
+    # instead of multiplying with the 16-bit rounded weight, so the two paths differ by
+    # the weight rounding (2^-11 per term, random sign), not by more.
     u = recipe_unit(O, 1, 0, 48)
     many, _, _ = run_group(u, True)
     for t in (0, 17, 47):
         ut = dict(u, X=u["X"][t:t + 1], T=1)
         one, _, _ = run_group(ut, True)
         for a, b in zip(many, one):
-            assert rel_err(b[0], a[t]) <= 1e-4
+            assert rel_err(b[0], a[t]) <= 1.5e-3
 
 
 def test_block_forward_with_mask():
     units = [recipe_unit(O, 1, 0, T, seed=s, shape=sh, r=16, G=64)
              for s, (T, sh) in enumerate([(4, UnitShape("qkv", 256, (256, 64, 64))),
                                           (4, UnitShape("o", 256, (256,))),
-                                          (40, UnitShape("gu", 128, (320, 320))),
-                                          (40, UnitShape("down", 320, (128,)))])]
+                                          (40, UnitShape("gu", 128, (384, 384))),
+                                          (40, UnitShape("down", 384, (128,)))])]
     mask = [1, 0, 1, 0]
     dus = [DeviceUnit(u) for u in units]
     ws = Workspace([d.desc for d in dus])

@@ -24,7 +24,7 @@ def _module(seed, d_out, d_in, Gs, odd_scales=False):
 
 
 @pytest.mark.parametrize("d_out,d_in,Gs", [(256, 256, 64), (40, 128, 128), (96, 1024, 128),
-                                           (8, 64, 64), (1000, 448, 64)])
+                                           (8, 128, 64), (1000, 384, 64)])
 def test_unpack_bit_exact(d_out, d_in, Gs):
     mod, q = _module(1, d_out, d_in, Gs)
     dm = DeviceModule(mod, d_in, Gs)
@@ -36,7 +36,7 @@ def test_unpack_bit_exact(d_out, d_in, Gs):
 
 @pytest.mark.parametrize("act", ["f16", "bf16"])
 @pytest.mark.parametrize("d_out,d_in,Gs,odd", [(256, 256, 64, False), (40, 256, 128, False),
-                                               (96, 1024, 128, True), (1000, 448, 64, True)])
+                                               (96, 1024, 128, True), (1000, 384, 64, True)])
 def test_dequant_bit_exact(act, d_out, d_in, Gs, odd):
     mod, q = _module(2, d_out, d_in, Gs, odd)
     dm = DeviceModule(mod, d_in, Gs)
