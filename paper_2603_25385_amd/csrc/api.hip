@@ -17,7 +17,9 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   w.ctl_bytes = align_up(w.off_counters + (size_t)tblocks * 4, 256);
   // K slices of the projection: decode spreads B over many compute units; prefill
   // already has T / 16 token blocks and only needs enough slices to fill the chip
-  int ksplit = is_decode(u.T) ? 32 : (256 + tblocks - 1) / tblocks;
+  // (a handful of tokens: the consumers add the slices themselves, so T * slices stays small)
+  int ksplit = u.T <= 1 ? 32 : u.T == 2 ? 16 : u.T <= 4 ? 8
+             : is_decode(u.T) ? 32 : (256 + tblocks - 1) / tblocks;
   if (ksplit > 32) ksplit = 32;
   if (ksplit < 1) ksplit = 1;
   int steps = u.d_in / 32;
@@ -25,7 +27,7 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   w.kslice = per * 32;
   w.ksplit = (u.d_in + w.kslice - 1) / w.kslice;
   w.off_rpart = w.ctl_bytes;
-  size_t rpart = (u.r > 0) ? (size_t)w.ksplit * u.T * u.r * sizeof(float) : 0;
+  size_t rpart = (u.r > 0) ? (size_t)((w.ksplit + 3) / 4 * 4) * u.T * u.r * sizeof(float) : 0;
   w.off_r16 = align_up(w.off_rpart + rpart, 256);
   size_t r16 = (u.r > 0) ? (size_t)u.T * u.r * 2 : 0;
   w.bytes = align_up(w.off_r16 + r16, 256);
@@ -79,7 +81,7 @@ static inline glowq_status hip_status(hipError_t e) {
 static glowq_status forward_one(const glowq_unit& u, bool restore, char* ws_base, hipStream_t st) {
   UnitWorkspace ws = plan_unit_workspace(u, ws_base);
   const bool corr = restore && u.r > 0;
-  if (corr) {
+  if (corr && !is_decode(u.T)) {
     hipError_t e = launch_proj(u, ws, nullptr, true, st);
     if (e != hipSuccess) return hip_status(e);
   }
@@ -208,7 +210,7 @@ glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d
   glowq_status s = check_weights_shape(d_out, d_in, group_size);
   if (s != GLOWQ_OK) return s;
   if (misaligned(w_prepared) || misaligned(q_out)) return GLOWQ_ERR_ALIGN;
-  return hip_status(launch_debug_unpack(w_prepared, d_out, d_in, q_out, (hipStream_t)stream));
+  return hip_status(launch_debug_unpack(w_prepared, d_out, d_in, group_size, q_out, (hipStream_t)stream));
 }
 
 glowq_status glowq_debug_dequant(const void* w_prepared, int32_t d_out, int32_t d_in,

@@ -24,6 +24,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 def build(verbose: bool = False, extra: list | None = None) -> str:
     os.makedirs(LIB_DIR, exist_ok=True)
+    extra = list(extra or []) + os.environ.get("GLOWQ_EXTRA_HIPCC_FLAGS", "").split()
     objs = []
     procs = []
     for src in SOURCES:

@@ -18,35 +18,38 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 enum Act { ACT_F16 = 0, ACT_BF16 = 1 };
 
 // ---------------------------------------------------------------------------
-// Prepared layout of one module's weights (built by prepare.hip):
-//   tiles : [rows16][d_in/128][64 lanes][4 words]  one tile = 16 rows x 128 channels = 1 KiB
-//           lane l holds row 16*rb + (l & 15); word j of lane l holds channels
-//           128*kb + 32*j + 8*(l >> 4) + e, e = 0..7 -- exactly the B operand of one
-//           16x16x32 matrix-core instruction per word; inside a word, nibble i holds
-//           e = 2i and nibble i + 4 holds e = 2i + 1, so that ((w >> 4i) & 0x000F000F)
-//           is the pair (e = 2i, e = 2i + 1)
-//   sz    : [d_in/G][rows16 * 16] words, low half = scale bits, high half = zero-point bits
-// rows16 = ceil(d_out / 16); rows past d_out hold q = 0, s = 1, z = 0 (dequantise to 0).
+// Prepared layout of one module's weights (built by prepare.hip): an array of tile
+// records [rows16][d_in/128], one record = 16 rows x 128 channels:
+//   words 0..255   : the packed weights, [64 lanes][4 words] -- one contiguous 1 KiB
+//                    wave load.  Lane l holds row 16*rb + (l & 15); word j of lane l
+//                    holds channels 128*kb + 32*j + 8*(l >> 4) + e, e = 0..7 -- exactly
+//                    the B operand of one 16x16x32 matrix-core instruction per word;
+//                    inside a word, nibble i holds e = 2i and nibble i + 4 holds
+//                    e = 2i + 1, so that ((w >> 4i) & 0x000F000F) is the pair
+//                    (e = 2i, e = 2i + 1)
+//   words 256..271 : (s, z) of the 16 rows for the tile's first quantisation group,
+//                    low half = scale bits, high half = zero-point bits
+//   words 272..287 : the same for the second group (G = 64 only)
+// so a tile's scales sit in the same DRAM page as its weights.  rows16 =
+// ceil(d_out / 16); rows past d_out hold q = 0, s = 1, z = 0 (dequantise to 0).
 // ---------------------------------------------------------------------------
 struct PreparedView {
-  const u32x4_t* tiles;
-  const uint32_t* sz;
-  int rows16;   // 16-row blocks
-  int ktiles;   // d_in / 128
+  const uint32_t* base;
+  int rows16;      // 16-row blocks
+  int ktiles;      // d_in / 128
+  int rec_words;   // 272 (G = 128) or 288 (G = 64)
 };
 
-__host__ __device__ inline size_t prepared_tile_bytes(int d_out, int d_in) {
-  return (size_t)((d_out + 15) / 16) * 16 * (size_t)d_in / 2;
-}
+__host__ __device__ inline int prepared_rec_words(int G) { return 256 + 16 * (128 / G); }
 __host__ __device__ inline size_t prepared_total_bytes(int d_out, int d_in, int G) {
-  return prepared_tile_bytes(d_out, d_in) + (size_t)(d_in / G) * ((d_out + 15) / 16) * 16 * 4;
+  return (size_t)((d_out + 15) / 16) * (size_t)(d_in / 128) * prepared_rec_words(G) * 4;
 }
-__host__ __device__ inline PreparedView prepared_view(const void* p, int d_out, int d_in) {
+__host__ __device__ inline PreparedView prepared_view(const void* p, int d_out, int d_in, int G) {
   PreparedView v;
-  v.tiles = (const u32x4_t*)p;
-  v.sz = (const uint32_t*)((const char*)p + prepared_tile_bytes(d_out, d_in));
+  v.base = (const uint32_t*)p;
   v.rows16 = (d_out + 15) / 16;
   v.ktiles = d_in / 128;
+  v.rec_words = prepared_rec_words(G);
   return v;
 }
 
@@ -95,6 +98,9 @@ __device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) {
 // (1024 + q_a, 1024 + q_b) is made by OR-ing two nibbles into the fraction of 0x6400,
 // and adding -(1024 + z) cancels the offset and the zero-point in one packed add.
 __device__ inline u32x4_t q_minus_z_f16(uint32_t w, half2_t nb2) {
+#ifdef GLOWQ_PROBE_NODEQ
+  return u32x4_t{w, w ^ 1u, w ^ 2u, w ^ 3u};
+#endif
   const uint32_t magic = 0x64006400u;
   u32x4_t out;
 #pragma unroll
@@ -167,13 +173,37 @@ template <int ACT> __device__ inline uint16_t to_act16(float v) {
   else return __builtin_bit_cast(uint16_t, (__bf16)v);
 }
 
-// Control words at the head of a unit's workspace slice (all zero between calls).
+// Optional stage timestamps (builds with -DGLOWQ_TRACE only): 100 MHz real-time counter
+// values per workgroup and stage, fetched with glowq_debug_trace().
+#ifdef GLOWQ_TRACE
+static __device__ unsigned long long g_trace[8192][8];   // one copy per translation unit
+#define GLOWQ_STAMP(slot)                                                         \
+  do {                                                                            \
+    const unsigned b_ = blockIdx.x + blockIdx.y * gridDim.x;                      \
+    if (threadIdx.x == 0 && b_ < 8192)                                            \
+      g_trace[b_][slot] = __builtin_amdgcn_s_memrealtime();                       \
+  } while (0)
+#else
+#define GLOWQ_STAMP(slot) do { } while (0)
+#endif
+
+// Control words at the head of a unit's workspace slice.
 struct Control {
-  uint32_t proj_arrivals;   // projection workgroups that have stored their partial sums
-  uint32_t r_ready;         // 1 once R is complete (single-launch decode path only)
-  uint32_t consumers_done;  // workgroups that have consumed R in this launch
-  uint32_t status;          // nonzero: a bounded wait expired (cannot happen in order dispatch)
+  unsigned long long r_tag;  // launch tag of the launch whose R is complete in the workspace
+  uint32_t blocks_done;      // token blocks of the projection finished in the running launch
+  uint32_t status;           // nonzero: a bounded wait expired (cannot happen: see wait_r_ready)
   uint32_t pad[12];
+  unsigned long long slice_tag[32];  // direct mode: launch tag per K slice of the projection
 };
+
+// A value that is the same for every workgroup of one kernel launch and differs from
+// launch to launch, graph replays included: the queue's packet index of this dispatch
+// mixed with the address of the queue it sits in.  Odd, hence never zero.
+extern "C" __device__ unsigned long long glowq_llvm_dispatch_id(void) __asm("llvm.amdgcn.dispatch.id");
+__device__ inline unsigned long long launch_tag() {
+  const unsigned long long q = (unsigned long long)__builtin_amdgcn_queue_ptr();
+  const unsigned long long t = q * 0x9E3779B97F4A7C15ull + glowq_llvm_dispatch_id();
+  return (t << 1) | 1ull;
+}
 
 }  // namespace glowq

@@ -19,26 +19,49 @@
 // the rounded weight itself.
 //
 // The correction is r more channels of the same contraction: operand [A_i]
-// against [R], with R already reduced by the projection.  The four waves' fp32
-// tiles are folded through LDS and stored.
+// against [R].  R = X B^T is produced inside the same launch: the first workgroups
+// of the grid run the projection (K slices, last arrival reduces), everyone else
+// streams weights in the meantime and only polls a ready counter right before the
+// correction -- a kernel boundary would cost as much as the whole weight stream.
+// The four waves' fp32 tiles are folded through LDS and stored.
 #include "decode_device.hpp"
+#include "proj_device.hpp"
 #include "launch.hpp"
 
 namespace glowq {
 
+static_assert(GLOWQ_MAX_RANK <= DEC_WAVES * 32, "one 32-rank correction step per wave");
+
+// Grid: [n_prod projection workgroups][one workgroup per 16-row block].
 template <int ACT, int TBK>
-__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a) {
+__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArgs p, int n_prod) {
   __shared__ float lds[DEC_WAVES * TBK * 4 * 64];
-  decode_workgroup<ACT, TBK>(a, (int)blockIdx.x, lds);
+  if ((int)blockIdx.x < n_prod) {
+    proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds, PROJ_TAG);
+    return;
+  }
+  decode_workgroup<ACT, TBK>(a, (int)blockIdx.x - n_prod, lds);
+}
+
+template <int ACT>
+__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeArgs a, ProjArgs p,
+                                                                 int n_prod) {
+  __shared__ float lds[DEC_WAVES * 4 * 64];
+  __shared__ __attribute__((aligned(16))) char lds_x[DEC_WAVES * DEC_XWAVE];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_r[DEC_SMALL_T * GLOWQ_MAX_RANK];
+  if ((int)blockIdx.x < n_prod) {
+    proj_workgroup<ACT>(p, 0, (int)blockIdx.x, lds, PROJ_DIRECT);
+    return;
+  }
+  decode_workgroup_small<ACT>(a, p, (int)blockIdx.x - n_prod, lds, lds_x, lds_r);
 }
 
 int fill_decode_args(const glowq_unit& u, const UnitWorkspace& ws, bool restore, DecodeArgs& a) {
   int blk = 0;
   for (int i = 0; i < u.n_modules; ++i) {
     const glowq_module& m = u.modules[i];
-    PreparedView v = prepared_view(m.w_prepared, m.d_out, u.d_in);
-    a.mod[i].tiles = v.tiles;
-    a.mod[i].sz = v.sz;
+    PreparedView v = prepared_view(m.w_prepared, m.d_out, u.d_in, u.group_size);
+    a.mod[i].rec = v.base;
     a.mod[i].A = (const uint16_t*)m.A;
     a.mod[i].Y = m.Y;
     a.mod[i].d_out = m.d_out;
@@ -64,16 +87,36 @@ hipError_t launch_decode(const glowq_unit& u, const UnitWorkspace& ws, bool rest
                          hipStream_t st) {
   DecodeArgs a;
   const int blocks = fill_decode_args(u, ws, restore, a);
-  dim3 grid((unsigned)blocks), block(DEC_WAVES * 64);
+  ProjArgs p = {};
+  int n_prod = 0;
+  a.ctl = (Control*)ws.base;
+  a.in_launch_proj = 0;
+  if (restore) {
+    p = make_proj_args(u, ws, nullptr, true);
+    const int tblocks = (u.T + 15) / 16;
+    n_prod = tblocks * ws.ksplit;
+    a.in_launch_proj = 1;
+  }
+  dim3 grid((unsigned)(n_prod + blocks)), block(DEC_WAVES * 64);
   const bool f16 = (u.act_dtype == GLOWQ_F16);
-  if (u.T <= 16) {
-    if (f16) k_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a);
-    else k_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a);
+  if (u.T <= DEC_SMALL_T) {
+    if (f16) k_decode_small<ACT_F16><<<grid, block, 0, st>>>(a, p, n_prod);
+    else k_decode_small<ACT_BF16><<<grid, block, 0, st>>>(a, p, n_prod);
+  } else if (u.T <= 16) {
+    if (f16) k_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
+    else k_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
   } else {
-    if (f16) k_decode<ACT_F16, 2><<<grid, block, 0, st>>>(a);
-    else k_decode<ACT_BF16, 2><<<grid, block, 0, st>>>(a);
+    if (f16) k_decode<ACT_F16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
+    else k_decode<ACT_BF16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
   }
   return hipGetLastError();
 }
 
 }  // namespace glowq
+
+#ifdef GLOWQ_TRACE
+// stage timestamps of the decode kernels' most recent launch (tracing builds only)
+extern "C" int glowq_debug_trace(unsigned long long* host_out /* [8192][8] */) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(glowq::g_trace), sizeof(glowq::g_trace));
+}
+#endif

@@ -21,8 +21,7 @@ constexpr int PF_WAVES = 4;
 constexpr int PF_PITCH = 72;   // LDS row pitch of the X stage, in 16-bit elements
 
 struct PfModule {
-  const u32x4_t* tiles;
-  const uint32_t* sz;
+  const uint32_t* rec;   // tile records (see common.hpp)
   const uint16_t* A;
   void* Y;
   int d_out, ldy, rows16, nt_start;   // nt_start: first 256-row tile of this module
@@ -56,20 +55,18 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, kq = lane >> 4;
   const int ktiles = a.K >> 7;
-  const int rows_pad = M.rows16 * 16;
   const bool g128 = (a.G == 128);
+  const int rw = g128 ? 272 : 288;             // words per tile record
 
   // this wave's four 16-row blocks
   const int nb0 = (nt - M.nt_start) * 16 + 4 * wave;
   bool valid[4];
-  const u32x4_t* wt[4];
-  const uint32_t* szp[4];
+  const uint32_t* wt[4];
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
     valid[b] = nb0 + b < M.rows16;
     const int nb = valid[b] ? nb0 + b : 0;
-    wt[b] = M.tiles + (size_t)nb * ktiles * 64 + lane;
-    szp[b] = M.sz + nb * 16 + n;
+    wt[b] = M.rec + (size_t)nb * ktiles * rw;
   }
 
   // X stage: thread -> (row = tid / 8 + 32 p, 16-byte chunk = tid % 8); rows past T
@@ -103,14 +100,10 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
   auto load_w = [&](int kt) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-      wnext[b] = __builtin_nontemporal_load(wt[b] + (size_t)kt * 64);
-      if (g128) {
-        sznext[b][0] = szp[b][(size_t)kt * rows_pad];
-        sznext[b][1] = sznext[b][0];
-      } else {
-        sznext[b][0] = szp[b][(size_t)(2 * kt) * rows_pad];
-        sznext[b][1] = szp[b][(size_t)(2 * kt + 1) * rows_pad];
-      }
+      const uint32_t* rec = wt[b] + (size_t)kt * rw;
+      wnext[b] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
+      sznext[b][0] = rec[256 + n];
+      sznext[b][1] = g128 ? sznext[b][0] : rec[272 + n];
     }
   };
   auto take_w = [&]() {
@@ -231,9 +224,8 @@ hipError_t launch_prefill(const glowq_unit& u, const UnitWorkspace& ws, bool res
   int nt = 0;
   for (int i = 0; i < u.n_modules; ++i) {
     const glowq_module& m = u.modules[i];
-    PreparedView v = prepared_view(m.w_prepared, m.d_out, u.d_in);
-    a.mod[i].tiles = v.tiles;
-    a.mod[i].sz = v.sz;
+    PreparedView v = prepared_view(m.w_prepared, m.d_out, u.d_in, u.group_size);
+    a.mod[i].rec = v.base;
     a.mod[i].A = (const uint16_t*)m.A;
     a.mod[i].Y = m.Y;
     a.mod[i].d_out = m.d_out;

@@ -17,7 +17,7 @@ namespace glowq {
 template <int ACT>
 __global__ void __launch_bounds__(256) k_proj(ProjArgs a) {
   extern __shared__ float proj_lds[];
-  proj_workgroup<ACT>(a, (int)blockIdx.x, (int)blockIdx.y, proj_lds, /*signal_ready=*/false);
+  proj_workgroup<ACT>(a, (int)blockIdx.x, (int)blockIdx.y, proj_lds, PROJ_ALONE);
 }
 
 __global__ void k_fill_zero(uint32_t* p, long long n_words) {
@@ -41,11 +41,13 @@ ProjArgs make_proj_args(const glowq_unit& u, const UnitWorkspace& ws, float* R32
   a.r = u.r;
   a.ksplit = ws.ksplit;
   a.kslice = ws.kslice;
+  a.kstride = (ws.ksplit + 3) / 4 * 4;
   a.Rpart = (float*)(ws.base + ws.off_rpart);
   a.R32 = R32;
   a.R16 = want_r16 ? (uint16_t*)(ws.base + ws.off_r16) : nullptr;
   a.ctl = (Control*)ws.base;
   a.counters = (uint32_t*)(ws.base + ws.off_counters);
+  a.tblocks = (u.T + 15) / 16;
   return a;
 }
 
@@ -62,3 +64,9 @@ hipError_t launch_proj(const glowq_unit& u, const UnitWorkspace& ws, float* R32,
 }
 
 }  // namespace glowq
+
+#ifdef GLOWQ_TRACE
+extern "C" int glowq_debug_trace_proj(unsigned long long* host_out /* [8192][8] */) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(glowq::g_trace), sizeof(glowq::g_trace));
+}
+#endif

@@ -12,18 +12,27 @@ struct ProjArgs {
   int T, K, r;
   int ksplit;          // K slices
   int kslice;          // channels per slice, multiple of 32
-  float* Rpart;        // fp32 [ksplit][T][r]
+  int kstride;         // ksplit rounded up to a multiple of 4
+  float* Rpart;        // fp32 [T][r][kstride]: the slices of one output are contiguous
   float* R32;          // optional fp32 [T][r]
   uint16_t* R16;       // optional act dtype [T][r]
   Control* ctl;
   uint32_t* counters;  // one per 16-token block, zero between launches
+  int tblocks;         // 16-token blocks in the launch (single-launch mode)
 };
 
 // One workgroup = (16-token block tb, K slice kz); any whole number of waves.
 // lds: blockDim.x / 64 * 256 floats.
+// mode PROJ_ALONE : stand-alone kernel; the last slice of a token block reduces it.
+// mode PROJ_TAG   : same, and the workgroup that completes the last token block then
+//                   publishes the launch tag (consumers in the same launch wait for it).
+// mode PROJ_DIRECT: no second stage -- every slice publishes its own tag once its
+//                   partial sums are visible, and the consumers add the slices themselves
+//                   (fewest dependent memory round trips; used for a handful of tokens).
+enum { PROJ_ALONE = 0, PROJ_TAG = 1, PROJ_DIRECT = 2 };
+
 template <int ACT>
-__device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* lds,
-                                      bool signal_ready) {
+__device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* lds, int mode) {
   __shared__ uint32_t s_prev;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
   const int nbs = (a.r + 15) >> 4;
@@ -36,6 +45,7 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
   float4_t acc[8];
 #pragma unroll
   for (int nb = 0; nb < 8; ++nb) acc[nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+  GLOWQ_STAMP(0);
 
   const int k_begin = kz * a.kslice;
   const int k_end = min(a.K, k_begin + a.kslice);
@@ -53,6 +63,7 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
   }
 
   // fold the waves' tiles and store this slice's partial sum
+  GLOWQ_STAMP(1);
 #pragma unroll
   for (int nb = 0; nb < 8; ++nb) {
     if (nb < nbs) {
@@ -65,10 +76,21 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
         for (int w = 0; w < nw; ++w) s += lds[(w * 4 + v) * 64 + ln];
         const int t = tb * 16 + 4 * (ln >> 4) + v;
         const int rank = nb * 16 + (ln & 15);
-        if (t < a.T && rank < a.r) a.Rpart[((size_t)kz * a.T + t) * a.r + rank] = s;
+        if (t < a.T && rank < a.r) a.Rpart[((size_t)t * a.r + rank) * a.kstride + kz] = s;
       }
       __syncthreads();
     }
+  }
+
+  GLOWQ_STAMP(2);
+  if (mode == PROJ_DIRECT) {
+    __threadfence();     // release: the partial sums are visible device-wide ...
+    __syncthreads();
+    GLOWQ_STAMP(3);
+    if (tid == 0)        // ... before this slice's tag is
+      __hip_atomic_store(&a.ctl->slice_tag[kz], launch_tag(), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    return;
   }
 
   // the last slice to arrive for this token block adds the partial sums in slice order
@@ -76,22 +98,42 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
   __syncthreads();
   if (tid == 0) s_prev = atomicAdd(&a.counters[tb], 1u);
   __syncthreads();
+  GLOWQ_STAMP(3);
   if (s_prev != (uint32_t)(a.ksplit - 1)) return;
   __threadfence();
+  GLOWQ_STAMP(4);
   for (int e = tid; e < 16 * a.r; e += blockDim.x) {
     const int t = tb * 16 + e / a.r, rank = e % a.r;
     if (t < a.T) {
+      const float4_t* p = (const float4_t*)(a.Rpart + ((size_t)t * a.r + rank) * a.kstride);
       float s = 0.f;
-      for (int z = 0; z < a.ksplit; ++z) s += a.Rpart[((size_t)z * a.T + t) * a.r + rank];
+#pragma unroll 4
+      for (int z = 0; z < a.ksplit; z += 4) {     // independent 16-byte loads, slice order
+        const float4_t v = p[z >> 2];
+        s += v[0];
+        if (z + 1 < a.ksplit) s += v[1];
+        if (z + 2 < a.ksplit) s += v[2];
+        if (z + 3 < a.ksplit) s += v[3];
+      }
       if (a.R32) a.R32[(size_t)t * a.r + rank] = s;
       if (a.R16) a.R16[(size_t)t * a.r + rank] = to_act16<ACT>(s);
     }
   }
+  GLOWQ_STAMP(5);
   if (tid == 0) a.counters[tb] = 0u;
-  if (signal_ready) {
+  if (mode == PROJ_TAG) {
+    // single-launch mode: the workgroup that completes the last token block publishes
+    // this launch's tag; consumers of the same launch wait for exactly that value
     __threadfence();
     __syncthreads();
-    if (tid == 0) atomicAdd(&a.ctl->r_ready, 1u);
+    if (tid == 0) {
+      const uint32_t done = atomicAdd(&a.ctl->blocks_done, 1u);
+      if (done == (uint32_t)(a.tblocks - 1)) {
+        a.ctl->blocks_done = 0u;
+        __hip_atomic_store(&a.ctl->r_tag, launch_tag(), __ATOMIC_RELEASE,
+                           __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
   }
 }
 

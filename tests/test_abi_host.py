@@ -75,5 +75,5 @@ def test_workspace_and_misc_errors():
     with pytest.raises(G.GlowqError) as e:
         G.glowq_prepared_bytes(64, 250, 64)
     assert e.value.status == G.GLOWQ_ERR_SHAPE
-    assert G.glowq_prepared_bytes(40, 128, 128) == 48 * 128 // 2 + 1 * 48 * 4
+    assert G.glowq_prepared_bytes(40, 128, 128) == 3 * 1 * 272 * 4
     assert "NULL" in G.glowq_status_string(G.GLOWQ_ERR_NULL)

@@ -112,3 +112,38 @@ def test_block_forward_with_mask():
         G.glowq_block_forward([d.desc for d in dus], bytes(mask), ws.ptr, ws.bytes, stream())
         for d, u, f in zip(dus, units, mask):
             _check(d.outputs(), O.group_forward(u, bool(f)), TOL)
+        ws.assert_idle()
+
+
+@pytest.mark.parametrize("T", [1, 12, 40])
+def test_graph_replay_matches_eager(T):
+    """A captured group forward replayed several times, with new activations written
+    into the same buffers between replays, gives the eager result every time (the
+    single-launch decode path must tell one replay's projection from the previous)."""
+    u = recipe_unit(O, 1, 0, T)
+    du = DeviceUnit(u)
+    ws = Workspace([du.desc])
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        G.glowq_group_forward(du.desc, True, ws.ptr, ws.bytes, side.cuda_stream)   # warm-up
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            G.glowq_group_forward(du.desc, True, ws.ptr, ws.bytes,
+                                  torch.cuda.current_stream().cuda_stream)
+    from glowq_inputs import gen_activations
+    from gpu_util import dev_bits
+    for rep in range(4):
+        xb = gen_activations(100 + rep, 0, T, u["d_in"], u["act"], False)
+        du.X.copy_(dev_bits(xb))
+        du.clear()
+        torch.cuda.synchronize()
+        graph.replay()
+        got = du.outputs()
+        ref = O.group_forward(dict(u, X=xb), True)
+        _check(got, ref, TOL)
+        # eager work and a synchronisation between the replays
+        du.clear()
+        G.glowq_group_forward(du.desc, True, ws.ptr, ws.bytes, stream())
+        _check(du.outputs(), ref, TOL)
+    ws.assert_idle()
