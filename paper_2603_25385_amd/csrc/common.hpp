@@ -193,7 +193,6 @@ struct Control {
   uint32_t blocks_done;      // token blocks of the projection finished in the running launch
   uint32_t status;           // nonzero: a bounded wait expired (cannot happen: see wait_r_ready)
   uint32_t pad[12];
-  unsigned long long slice_tag[32];  // direct mode: launch tag per K slice of the projection
 };
 
 // A value that is the same for every workgroup of one kernel launch and differs from

@@ -50,7 +50,10 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeArgs a, P
   __shared__ __attribute__((aligned(16))) char lds_x[DEC_WAVES * DEC_XWAVE];
   __shared__ __attribute__((aligned(16))) uint16_t lds_r[DEC_SMALL_T * GLOWQ_MAX_RANK];
   if ((int)blockIdx.x < n_prod) {
-    proj_workgroup<ACT>(p, 0, (int)blockIdx.x, lds, PROJ_DIRECT);
+    GLOWQ_STAMP(0);
+    proj_wave_direct<ACT>(p, (int)blockIdx.x * DEC_WAVES + (int)(threadIdx.x >> 6),
+                          (int)(threadIdx.x & 63));
+    GLOWQ_STAMP(1);
     return;
   }
   decode_workgroup_small<ACT>(a, p, (int)blockIdx.x - n_prod, lds, lds_x, lds_r);
@@ -94,7 +97,8 @@ hipError_t launch_decode(const glowq_unit& u, const UnitWorkspace& ws, bool rest
   if (restore) {
     p = make_proj_args(u, ws, nullptr, true);
     const int tblocks = (u.T + 15) / 16;
-    n_prod = tblocks * ws.ksplit;
+    if (u.T <= DEC_SMALL_T) n_prod = (u.r * ws.ksplit + DEC_WAVES - 1) / DEC_WAVES;   // one wave per (rank, part)
+    else n_prod = tblocks * ws.ksplit;
     a.in_launch_proj = 1;
   }
   dim3 grid((unsigned)(n_prod + blocks)), block(DEC_WAVES * 64);

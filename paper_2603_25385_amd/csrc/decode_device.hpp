@@ -34,7 +34,9 @@ struct DecodeArgs {
 // sz0 / sz1: the (s, z) words of the tile's first and second 64 channels (equal
 // when the quantisation group is 128 wide).  xfrag(tb, j) returns the A operand of
 // word j: lane (i, kq) holds X[token 16 tb + i][32 j + 8 kq .. + 8] of this tile.
-template <int ACT, int TBK, bool G128, class XF>
+// NV: elements of a lane's accumulator that can hold real tokens (1 when T == 1: token 0
+// is element 0 of lanes 0..15), so that the per-group scaling touches nothing else.
+template <int ACT, int TBK, bool G128, int NV = 4, class XF>
 __device__ inline void decode_tile(const u32x4_t w, uint32_t sz0, uint32_t sz1, XF xfrag,
                                    float4_t (&acc)[TBK]) {
   if constexpr (ACT == ACT_F16) {
@@ -60,7 +62,7 @@ __device__ inline void decode_tile(const u32x4_t w, uint32_t sz0, uint32_t sz1, 
 #pragma unroll
       for (int tb = 0; tb < TBK; ++tb)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc[tb][v] = __builtin_fmaf(s, tmp[tb][v], acc[tb][v]);
+        for (int v = 0; v < NV; ++v) acc[tb][v] = __builtin_fmaf(s, tmp[tb][v], acc[tb][v]);
     }
   } else {
     GroupConst<ACT> g0, g1;
@@ -146,15 +148,17 @@ constexpr int DEC_XROW = 1040;                       // bytes per token and chun
 constexpr int DEC_XBUF = DEC_SMALL_T * DEC_XROW;     // one chunk buffer
 constexpr int DEC_XWAVE = 2 * DEC_XBUF;              // two chunk buffers per wave
 
-template <int ACT, bool G128>
+// `mid` runs once, after the wave's first chunk has been consumed (or right away if the
+// wave has no tiles).
+template <int ACT, bool G128, int NV, class MID>
 __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs& M, int rb,
                                            int wave, int lane, float4_t (&acc)[1],
-                                           char* lds_wave) {
+                                           char* lds_wave, MID mid) {
   const int n = lane & 15, kq = lane >> 4;
   const int ktiles = a.K >> 7;
   const int rw = G128 ? 272 : 288;             // words per tile record
   const int ntw = (ktiles - wave + DEC_WAVES - 1) / DEC_WAVES;
-  if (ntw <= 0) return;
+  if (ntw <= 0) { mid(); return; }
   const uint32_t* rec0 = M.rec + ((size_t)rb * ktiles + wave) * rw;
   // staging: lane -> (tile of the chunk, 16-byte piece of its 128 channels)
   const int lc = lane >> 4, lp = lane & 15;
@@ -166,6 +170,14 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
   uint32_t sA[DEC_CHUNK][2], sB[DEC_CHUNK][2];
 
   auto load_chunk = [&](int t0, int buf, u32x4_t (&w)[DEC_CHUNK], uint32_t (&s)[DEC_CHUNK][2]) {
+    // X first: loads return in order, and a tile needs its X before anything else
+    const int tx = min(t0 + lc, ntw - 1);
+    const uint16_t* src = xsrc + (size_t)tx * (128 * DEC_WAVES);
+    for (int tok = 0; tok < a.T; ++tok)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src + (size_t)tok * a.K),
+          (__attribute__((address_space(3))) void*)(lds_wave + buf * DEC_XBUF + tok * DEC_XROW),
+          16, 0, 0);
 #pragma unroll
     for (int c = 0; c < DEC_CHUNK; ++c) {
       const int t = min(t0 + c, ntw - 1);          // clamped: a duplicate tile is never used
@@ -175,13 +187,6 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
       if constexpr (G128) s[c][1] = s[c][0];
       else s[c][1] = __builtin_nontemporal_load(rec + 272 + n);
     }
-    const int tx = min(t0 + lc, ntw - 1);
-    const uint16_t* src = xsrc + (size_t)tx * (128 * DEC_WAVES);
-    for (int tok = 0; tok < a.T; ++tok)
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src + (size_t)tok * a.K),
-          (__attribute__((address_space(3))) void*)(lds_wave + buf * DEC_XBUF + tok * DEC_XROW),
-          16, 0, 0);
   };
   auto run_chunk = [&](int t0, int buf, const u32x4_t (&w)[DEC_CHUNK],
                        const uint32_t (&s)[DEC_CHUNK][2]) {
@@ -189,7 +194,7 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
     for (int c = 0; c < DEC_CHUNK; ++c) {
       if (t0 + c < ntw) {
         const char* xc = xrd + buf * DEC_XBUF + c * 256;
-        decode_tile<ACT, 1, G128>(w[c], s[c][0], s[c][1], [&](int, int j) {
+        decode_tile<ACT, 1, G128, NV>(w[c], s[c][0], s[c][1], [&](int, int j) {
           return *(const u32x4_t*)(xc + 64 * j); }, acc);
       }
     }
@@ -199,6 +204,7 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
   for (int t0 = 0; t0 < ntw; t0 += 2 * DEC_CHUNK) {
     if (t0 + DEC_CHUNK < ntw) load_chunk(t0 + DEC_CHUNK, 1, wB, sB);
     run_chunk(t0, 0, wA, sA);
+    if (t0 == 0) mid();
     if (t0 + DEC_CHUNK < ntw) {
       if (t0 + 2 * DEC_CHUNK < ntw) load_chunk(t0 + 2 * DEC_CHUNK, 0, wA, sA);
       run_chunk(t0 + DEC_CHUNK, 1, wB, sB);
@@ -242,52 +248,112 @@ __device__ inline u32x4_t load_r16(const uint16_t* p) {
   return v;
 }
 
-// Direct mode (T <= 4): wait until every K slice of the projection has published this
-// launch's tag, then add the slices' partial sums in slice order and leave R, rounded to
+// Direct mode (T <= 4): every (rank, K part) wave of the projection leaves, per token,
+// one 8-byte slot {partial sum, low word of its launch tag}.  The workgroup loads all
+// slots of its unit (all of a thread's loads are in flight together), checks that every
+// slot carries THIS launch's tag, adds the parts in part order and leaves R, rounded to
 // the activation type, in LDS.  All threads of the workgroup take part.
-// lds_r: T * r 16-bit values; returns false if the bounded wait expired.
-template <int ACT>
-__device__ inline bool gather_r_direct(const DecodeArgs& a, const ProjArgs& p, uint16_t* lds_r,
-                                       int wave, int lane) {
-  __shared__ int s_ok;
-  if (wave == 0) {
-    const unsigned long long tag = launch_tag();
-    bool ok = false;
-    for (int spin = 0; spin < (1 << 20); ++spin) {
-      unsigned long long v = tag;
-      if (lane < p.ksplit)
-        v = __hip_atomic_load(&p.ctl->slice_tag[lane], __ATOMIC_RELAXED,
-                              __HIP_MEMORY_SCOPE_AGENT);
-      if (__builtin_amdgcn_ballot_w64(v != tag) == 0ull) { ok = true; break; }
-      __builtin_amdgcn_s_sleep(8);
-    }
-    if (lane == 0) {
-      s_ok = ok ? 1 : 0;
-      if (!ok) atomicOr(&p.ctl->status, 1u);
-    }
-  }
-  __syncthreads();
-  GLOWQ_STAMP(2);
-  __atomic_signal_fence(__ATOMIC_SEQ_CST);
-  if (!s_ok) return false;
-  for (int e = threadIdx.x; e < a.T * a.r; e += DEC_WAVES * 64) {
-    // device-scope loads: they bypass anything older this compute unit or XCD may hold
-    const uint32_t* q = (const uint32_t*)(p.Rpart + (size_t)e * p.kstride);
-    float s = 0.f;
-    for (int z = 0; z < p.ksplit; z += 4) {
-      float v[4];
+//
+// The first attempt uses ordinary (L2-cached) loads and is issued in the middle of the
+// weight stream, so its latency is hidden: the projection waves publish within the first
+// couple of microseconds, long before any weight chunk has been consumed, and one
+// workgroup per XCD pays the miss.  A slot read too early shows an older tag; then, and
+// only then, the retries use device-scope loads, which cannot be served from a stale
+// cached line.  The wait is bounded (the projection waves wait for nothing, so it cannot
+// expire); if it did, ctl->status is set and the correction is left out rather than hang.
+struct GatherR {
+  unsigned long long v[8];
+  const unsigned long long* q;
+  int outputs, groups, g, e, z0, z1;
+  bool active, issued;
+};
+
+__device__ inline void gather_r_plan(const DecodeArgs& a, const ProjArgs& p, GatherR& st) {
+  st.outputs = a.T * a.r;                               // <= 512
+  st.groups = 1;
+  while (st.groups * 2 * st.outputs <= DEC_WAVES * 64 && st.groups * 2 <= p.ksplit)
+    st.groups *= 2;
+  st.issued = false;
+}
+
+__device__ inline void gather_r_slice(const ProjArgs& p, GatherR& st, int idx) {
+  const int spg = (p.ksplit + st.groups - 1) / st.groups;   // parts per group
+  st.g = idx / st.outputs;
+  st.e = idx - st.g * st.outputs;
+  st.active = st.g < st.groups;
+  st.q = (const unsigned long long*)p.Rpart + (size_t)(st.active ? st.e : 0) * p.kstride;
+  st.z0 = st.active ? st.g * spg : 0;
+  st.z1 = st.active ? min(p.ksplit, st.z0 + spg) : 0;
+}
+
+// issue the first (cached) attempt for this thread's first eight parts
+__device__ inline void gather_r_issue(const DecodeArgs& a, const ProjArgs& p, GatherR& st) {
+  if (!a.restore) return;
+  gather_r_slice(p, st, threadIdx.x);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        v[i] = __builtin_bit_cast(float, __hip_atomic_load(q + z + i, __ATOMIC_RELAXED,
-                                                            __HIP_MEMORY_SCOPE_AGENT));
-      s += v[0];
-      if (z + 1 < p.ksplit) s += v[1];
-      if (z + 2 < p.ksplit) s += v[2];
-      if (z + 3 < p.ksplit) s += v[3];
+  for (int i = 0; i < 8; ++i) {
+    st.v[i] = 0ull;
+    if (st.z0 < st.z1)
+      st.v[i] = __hip_atomic_load(st.q + min(st.z0 + i, st.z1 - 1), __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  st.issued = true;
+}
+
+// lds_f: 512 floats of scratch; lds_r: T * r 16-bit values
+template <int ACT>
+__device__ inline bool gather_r_finish(const DecodeArgs& a, const ProjArgs& p, GatherR& st,
+                                       float* lds_f, uint16_t* lds_r) {
+  const int tid = threadIdx.x;
+  const uint32_t tag = (uint32_t)(launch_tag() & 0xffffffffull);
+  const int passes = (st.outputs + DEC_WAVES * 64 - 1) / (DEC_WAVES * 64);   // 2 only if groups == 1
+  for (int pass = 0; pass < passes; ++pass) {
+    gather_r_slice(p, st, tid + pass * DEC_WAVES * 64);
+    const bool use_prefetch = st.issued && pass == 0;
+    float s = 0.f;
+    bool done = false;
+    for (int spin = 0; spin < (1 << 14); ++spin) {
+      bool ok = true;
+      s = 0.f;
+      for (int zb = st.z0; zb < st.z1; zb += 8) {
+        unsigned long long v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const unsigned long long* qi = st.q + min(zb + i, st.z1 - 1);
+          if (spin == 0 && use_prefetch && zb == st.z0) v[i] = st.v[i];
+          else if (spin == 0)
+            v[i] = __hip_atomic_load(qi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          else v[i] = __hip_atomic_load(qi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          if (zb + i < st.z1) {
+            ok = ok && ((uint32_t)(v[i] >> 32) == tag);
+            s += __builtin_bit_cast(float, (uint32_t)v[i]);
+          }
+        }
+      }
+      if (__syncthreads_and(ok ? 1 : 0)) { done = true; break; }
+      __builtin_amdgcn_s_sleep(32);
     }
-    lds_r[e] = to_act16<ACT>(s);
+    if (!done) {
+      if (tid == 0) atomicOr(&p.ctl->status, 1u);
+      return false;
+    }
+    if (st.active) {
+      if (st.groups == 1) lds_r[st.e] = to_act16<ACT>(s);
+      else lds_f[st.g * st.outputs + st.e] = s;
+    }
   }
   __syncthreads();
+  if (st.groups > 1) {
+    if (tid < st.outputs) {
+      float s = 0.f;
+      for (int g = 0; g < st.groups; ++g) s += lds_f[g * st.outputs + tid];
+      lds_r[tid] = to_act16<ACT>(s);
+    }
+    __syncthreads();
+  }
   return true;
 }
 
@@ -404,11 +470,19 @@ __device__ inline void decode_workgroup_small(const DecodeArgs& a, const ProjArg
   }
 #endif
   const CorrFrag cf = correction_prefetch(a, M, rb, wave, lane);
-  if (a.G == 128) decode_stream_small<ACT, true>(a, M, rb, wave, lane, acc, lds_x + wave * DEC_XWAVE);
-  else decode_stream_small<ACT, false>(a, M, rb, wave, lane, acc, lds_x + wave * DEC_XWAVE);
+  GatherR gr;
+  gather_r_plan(a, p, gr);
+  auto mid = [&]() { gather_r_issue(a, p, gr); };
+  char* lds_wave = lds_x + wave * DEC_XWAVE;
+  if (a.G == 128) {
+    if (a.T == 1) decode_stream_small<ACT, true, 1>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    else decode_stream_small<ACT, true, 4>(a, M, rb, wave, lane, acc, lds_wave, mid);
+  } else {
+    decode_stream_small<ACT, false, 4>(a, M, rb, wave, lane, acc, lds_wave, mid);
+  }
   GLOWQ_STAMP(1);
   if (a.restore) {
-    const bool got = gather_r_direct<ACT>(a, p, lds_r, wave, lane);
+    const bool got = gather_r_finish<ACT>(a, p, gr, lds, lds_r);
     GLOWQ_STAMP(3);
     if (got && cf.active) {
       const int tok = min(lane & 15, a.T - 1);

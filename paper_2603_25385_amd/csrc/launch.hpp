@@ -15,7 +15,8 @@ struct UnitWorkspace {
   size_t off_r16;     // act dtype [T][r]
   size_t ctl_bytes;   // leading bytes that must be zero between calls
   int ksplit;         // K slices of the projection
-  int kslice;         // channels per slice (multiple of 16)
+  int kslice;         // channels per slice (multiple of 32)
+  int kstride;        // elements between the slice arrays of two outputs in the partial-sum area
 };
 
 // decode path = one pass over the weights with all tokens in one matrix-core tile

@@ -41,7 +41,7 @@ ProjArgs make_proj_args(const glowq_unit& u, const UnitWorkspace& ws, float* R32
   a.r = u.r;
   a.ksplit = ws.ksplit;
   a.kslice = ws.kslice;
-  a.kstride = (ws.ksplit + 3) / 4 * 4;
+  a.kstride = ws.kstride;
   a.Rpart = (float*)(ws.base + ws.off_rpart);
   a.R32 = R32;
   a.R16 = want_r16 ? (uint16_t*)(ws.base + ws.off_r16) : nullptr;

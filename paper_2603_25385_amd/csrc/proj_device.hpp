@@ -14,6 +14,7 @@ struct ProjArgs {
   int kslice;          // channels per slice, multiple of 32
   int kstride;         // ksplit rounded up to a multiple of 4
   float* Rpart;        // fp32 [T][r][kstride]: the slices of one output are contiguous
+                       // (direct mode: 8-byte slots {fp32 bits, launch tag} instead)
   float* R32;          // optional fp32 [T][r]
   uint16_t* R16;       // optional act dtype [T][r]
   Control* ctl;
@@ -26,10 +27,7 @@ struct ProjArgs {
 // mode PROJ_ALONE : stand-alone kernel; the last slice of a token block reduces it.
 // mode PROJ_TAG   : same, and the workgroup that completes the last token block then
 //                   publishes the launch tag (consumers in the same launch wait for it).
-// mode PROJ_DIRECT: no second stage -- every slice publishes its own tag once its
-//                   partial sums are visible, and the consumers add the slices themselves
-//                   (fewest dependent memory round trips; used for a handful of tokens).
-enum { PROJ_ALONE = 0, PROJ_TAG = 1, PROJ_DIRECT = 2 };
+enum { PROJ_ALONE = 0, PROJ_TAG = 1 };
 
 template <int ACT>
 __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* lds, int mode) {
@@ -62,8 +60,8 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
     }
   }
 
-  // fold the waves' tiles and store this slice's partial sum
   GLOWQ_STAMP(1);
+  // fold the waves' tiles and store this slice's partial sum
 #pragma unroll
   for (int nb = 0; nb < 8; ++nb) {
     if (nb < nbs) {
@@ -81,17 +79,7 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
       __syncthreads();
     }
   }
-
   GLOWQ_STAMP(2);
-  if (mode == PROJ_DIRECT) {
-    __threadfence();     // release: the partial sums are visible device-wide ...
-    __syncthreads();
-    GLOWQ_STAMP(3);
-    if (tid == 0)        // ... before this slice's tag is
-      __hip_atomic_store(&a.ctl->slice_tag[kz], launch_tag(), __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-    return;
-  }
 
   // the last slice to arrive for this token block adds the partial sums in slice order
   __threadfence();
@@ -133,6 +121,65 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
         __hip_atomic_store(&a.ctl->r_tag, launch_tag(), __ATOMIC_RELEASE,
                            __HIP_MEMORY_SCOPE_AGENT);
       }
+    }
+  }
+}
+
+// Projection for a handful of tokens (T <= 4), built for the shortest dependency chain:
+// one WAVE computes, for one rank j and one of `ksplit` K parts, the T partial sums
+// sum_k X[t][k] B[j][k] -- a contiguous read of B, fp32 accumulation, a butterfly
+// reduction -- and publishes each as ONE 8-byte device-scope store {fp32 bits, low word
+// of the launch tag}.  A slot therefore validates itself: no fence, no flag, no ordering
+// between stores, and the wave never waits for anything.  The consumers add the parts
+// (gather_r_direct).  Slot of (t, j, part): slots[(t r + j) kstride + part]; kstride
+// spreads the outputs over memory channels.
+template <int ACT>
+__device__ inline void proj_wave_direct(const ProjArgs& a, int wave_global, int lane) {
+  const int rank = wave_global % a.r, part = wave_global / a.r;   // a workgroup shares a part
+  if (part >= a.ksplit) return;
+  const int k_begin = part * a.kslice;
+  const int k_end = min(a.K, k_begin + a.kslice);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  const uint16_t* brow = a.B + (size_t)rank * a.K;
+  for (int k = k_begin + 8 * lane; k < k_end; k += 512) {
+    const u32x4_t bv = *(const u32x4_t*)(brow + k);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (t < a.T) {
+        const u32x4_t xv = *(const u32x4_t*)(a.X + (size_t)t * a.K + k);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t bw = bv[i], xw = xv[i];
+          float b0, b1, x0, x1;
+          if constexpr (ACT == ACT_F16) {
+            b0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(bw & 0xffffu));
+            b1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(bw >> 16));
+            x0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(xw & 0xffffu));
+            x1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(xw >> 16));
+          } else {
+            b0 = __builtin_bit_cast(float, bw << 16);
+            b1 = __builtin_bit_cast(float, bw & 0xffff0000u);
+            x0 = __builtin_bit_cast(float, xw << 16);
+            x1 = __builtin_bit_cast(float, xw & 0xffff0000u);
+          }
+          acc[t] = __builtin_fmaf(b0, x0, acc[t]);
+          acc[t] = __builtin_fmaf(b1, x1, acc[t]);
+        }
+      }
+    }
+  }
+  const unsigned long long tag_hi = (launch_tag() & 0xffffffffull) << 32;
+  unsigned long long* slots = (unsigned long long*)a.Rpart;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    if (t < a.T) {
+      float s = acc[t];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+      if (lane == 0)
+        __hip_atomic_store(&slots[((size_t)t * a.r + rank) * a.kstride + part],
+                           tag_hi | (unsigned long long)__builtin_bit_cast(uint32_t, s),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }

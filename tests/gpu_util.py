@@ -85,9 +85,10 @@ class Workspace:
         self.buf = torch.empty(max(self.bytes, 256), dtype=torch.uint8, device="cuda")
         G.glowq_workspace_init(self.buf.data_ptr(), self.buf.numel(), stream())
 
-        self.offsets, off = [], 0
+        self.offsets, self.tblocks, off = [], [], 0
         for d in descs:
             self.offsets.append(off)
+            self.tblocks.append((d.T + 15) // 16)
             off += G.glowq_workspace_bytes([d])
 
     @property
@@ -96,17 +97,15 @@ class Workspace:
 
     def control_words(self):
         """Control words of every unit slice as 32-bit words: launch tag (2 words),
-        token blocks done, status, padding to 16 words, 32 per-slice launch tags
-        (64 words), then the per-token-block arrival counters.  Everything but the
-        tags must be zero between calls."""
+        token blocks done, status, padding to 16 words, then one arrival counter per
+        16-token block.  Everything but the tag must be zero between calls."""
         torch.cuda.synchronize()
         w = self.buf.view(torch.int32).cpu().numpy()
-        return [w[o // 4:o // 4 + 16].tolist() + w[o // 4 + 80:o // 4 + 96].tolist()
-                for o in self.offsets]
+        return [w[o // 4:o // 4 + 16 + nb].tolist() for o, nb in zip(self.offsets, self.tblocks)]
 
     def assert_idle(self):
         for cw in self.control_words():
-            assert not any(cw[2:]), cw      # (the tag words 16..79 are not in cw)
+            assert not any(cw[2:]), cw
 
 
 def run_group(unit: dict, restore: bool = True, out: str = "f32", ldy_pad: int = 0):
