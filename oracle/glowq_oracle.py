@@ -27,9 +27,24 @@ are in tests/test_oracle_*.py (nothing here is "parity unpinned").
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
+
+
+def _by_row_chunks(fn, n_rows: int, min_rows: int = 256):
+    """Apply fn(lo, hi) to row ranges on a few threads (numpy releases the GIL inside its
+    loops) and return the results in order.  Rows are independent in everything this is
+    used for, so chunking changes no value."""
+    workers = max(1, min(16, os.cpu_count() or 1, n_rows // min_rows))
+    if workers == 1:
+        return [fn(0, n_rows)]
+    step = -(-n_rows // workers)
+    bounds = [(lo, min(n_rows, lo + step)) for lo in range(0, n_rows, step)]
+    with ThreadPoolExecutor(workers) as ex:
+        return list(ex.map(lambda b: fn(*b), bounds))
 
 # --------------------------------------------------------------------------
 # 16-bit formats: widening and round-to-nearest-even, written out
@@ -105,16 +120,21 @@ def quantize_rtn(W: np.ndarray, G: int) -> Tuple[np.ndarray, np.ndarray, np.ndar
     W = np.asarray(W, dtype=np.float32)
     O, d = W.shape
     assert d % G == 0
-    Wg = W.reshape(O, d // G, G).astype(np.float64)
-    lo = np.minimum(Wg.min(axis=2), 0.0)
-    hi = np.maximum(Wg.max(axis=2), 0.0)
-    s = np.maximum((hi - lo) / 15.0, 2.0 ** -14)
-    s_bits = f64_to_bits(s, "f16")
-    s_hat = bits_to_f64(s_bits, "f16")
-    z = np.clip(np.rint(-lo / s_hat), 0, 15)
-    q = np.clip(np.rint(Wg / s_hat[:, :, None]) + z[:, :, None], 0, 15)
-    z_bits = f64_to_bits(z, "f16")
-    return q.reshape(O, d).astype(np.uint8), s_bits, z_bits
+
+    def rows(lo_r, hi_r):
+        Wg = W[lo_r:hi_r].reshape(hi_r - lo_r, d // G, G).astype(np.float64)
+        lo = np.minimum(Wg.min(axis=2), 0.0)
+        hi = np.maximum(Wg.max(axis=2), 0.0)
+        s = np.maximum((hi - lo) / 15.0, 2.0 ** -14)
+        s_bits = f64_to_bits(s, "f16")
+        s_hat = bits_to_f64(s_bits, "f16")
+        z = np.clip(np.rint(-lo / s_hat), 0, 15)
+        q = np.clip(np.rint(Wg / s_hat[:, :, None]) + z[:, :, None], 0, 15)
+        return q.reshape(hi_r - lo_r, d).astype(np.uint8), s_bits, f64_to_bits(z, "f16")
+
+    parts = _by_row_chunks(rows, O)
+    return (np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts]),
+            np.concatenate([p[2] for p in parts]))
 
 
 def pack_int4(q: np.ndarray) -> np.ndarray:
@@ -146,15 +166,22 @@ def dequant_bits(q: np.ndarray, s_bits: np.ndarray, z_bits: np.ndarray, G: int,
     product are exact in float64, so there is exactly one rounding, to the
     activation type.  Returns the uint16 bit patterns [O][d]."""
     q = np.asarray(q)
-    O, d = q.shape
-    s = np.repeat(bits_to_f64(s_bits, "f16"), G, axis=1)
-    z = np.repeat(bits_to_f64(z_bits, "f16"), G, axis=1)
-    return f64_to_bits((q.astype(np.float64) - z) * s, act)
+    s_bits = np.asarray(s_bits)
+    z_bits = np.asarray(z_bits)
+
+    def rows(lo, hi):
+        s = np.repeat(bits_to_f64(s_bits[lo:hi], "f16"), G, axis=1)
+        z = np.repeat(bits_to_f64(z_bits[lo:hi], "f16"), G, axis=1)
+        return f64_to_bits((q[lo:hi].astype(np.float64) - z) * s, act)
+
+    return np.concatenate(_by_row_chunks(rows, q.shape[0]))
 
 
 def dequant(q, s_bits, z_bits, G: int, act: str) -> np.ndarray:
     """dequant_bits widened to float64: the weight the forward multiplies with."""
-    return bits_to_f64(dequant_bits(q, s_bits, z_bits, G, act), act)
+    bits = dequant_bits(q, s_bits, z_bits, G, act)
+    return np.concatenate(_by_row_chunks(lambda lo, hi: bits_to_f64(bits[lo:hi], act),
+                                         bits.shape[0]))
 
 
 # --------------------------------------------------------------------------
@@ -202,6 +229,10 @@ def thin_qr(E: np.ndarray, method: str = "householder") -> Tuple[np.ndarray, np.
     E = np.asarray(E, np.float64)
     if method == "householder":
         return np.linalg.qr(E, mode="reduced")
+    if method == "none":
+        # no reduction: Q_e = I, R_e = E (the randomised steps then run on the stack itself;
+        # same estimator, used where a QR of the stack would dominate a test's run time)
+        return None, E
     if method == "cholesky":
         L = np.linalg.cholesky(E.T @ E)
         Re = L.T
@@ -243,7 +274,8 @@ def factors_alg1(E_cat: np.ndarray, r: int, p: int, q: int, Omega: np.ndarray,
     A_hat = U[:, :r] * rs[None, :]
     B_hat = rs[:, None] * Vt[:r]
     inv_root = np.where(root > 0, 1.0 / np.where(root > 0, root, 1.0), 0.0)
-    return Qe @ A_hat, B_hat * inv_root[None, :]
+    A = A_hat if Qe is None else Qe @ A_hat
+    return A, B_hat * inv_root[None, :]
 
 
 # --------------------------------------------------------------------------
@@ -298,7 +330,7 @@ def layerwise_forward(unit: dict) -> List[np.ndarray]:
 # --------------------------------------------------------------------------
 def build_unit(W_list: Sequence[np.ndarray], X_bits: np.ndarray, r: int, G: int,
                act: str, method: str = "svd", Omega: Optional[np.ndarray] = None,
-               p: int = 16, q: int = 2) -> dict:
+               p: int = 16, q: int = 2, qr: str = "cholesky") -> dict:
     """Quantise each module, factorise the stacked error, round the factors to
     the activation type, and return the stored operands of the unit."""
     modules, What_list = [], []
@@ -313,7 +345,7 @@ def build_unit(W_list: Sequence[np.ndarray], X_bits: np.ndarray, r: int, G: int,
         if method == "svd":
             A, B, _ = factors_svd(E_cat, r)
         elif method == "alg1":
-            A, B = factors_alg1(E_cat, r, p, q, Omega, None, qr="cholesky")
+            A, B = factors_alg1(E_cat, r, p, q, Omega, None, qr=qr)
         else:
             raise ValueError(method)
         for m, A_i in zip(modules, split_rows(A, [W.shape[0] for W in W_list])):

@@ -101,7 +101,7 @@ def test_thin_qr(qr):
     assert np.allclose(np.tril(R, -1), 0.0)
 
 
-@pytest.mark.parametrize("qr", ["householder", "cholesky"])
+@pytest.mark.parametrize("qr", ["householder", "cholesky", "none"])
 def test_alg1_identity_covariance_matches_exact_svd(qr):
     # a decaying spectrum with a clear gap after r: with p = 8, q = 2 the sketch
     # captures the leading subspace to rounding, so the products agree

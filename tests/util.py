@@ -16,7 +16,7 @@ def rel_err(y, y_ref):
 
 
 def recipe_unit(oracle, cfg_id, unit_index, T, r=None, method="svd", shape=None, act=None,
-                G=None, seed=None, rows_scale=1):
+                G=None, seed=None, rows_scale=1, qr="cholesky"):
     """Stored operands of one unit made the way the workload recipe says:
     Gaussian weights -> RTN INT4 -> stacked-error factors -> 16-bit storage."""
     cfg = CONFIGS[cfg_id]
@@ -31,6 +31,6 @@ def recipe_unit(oracle, cfg_id, unit_index, T, r=None, method="svd", shape=None,
     Omega = None
     if method == "alg1":
         Omega = np.random.default_rng([seed, unit_index, 505]).standard_normal((shape.d_in, r + 16))
-    unit = oracle.build_unit(W, X, r, G, act, method=method, Omega=Omega)
+    unit = oracle.build_unit(W, X, r, G, act, method=method, Omega=Omega, qr=qr)
     unit["W"] = W
     return unit
