@@ -81,15 +81,47 @@ static inline glowq_status hip_status(hipError_t e) {
   return GLOWQ_ERR_HIP;
 }
 
-static glowq_status forward_one(const glowq_unit& u, bool restore, char* ws_base, hipStream_t st) {
-  UnitWorkspace ws = plan_unit_workspace(u, ws_base);
-  const bool corr = restore && u.r > 0;
-  if (corr && !is_decode(u.T)) {
-    hipError_t e = launch_proj(u, ws, nullptr, true, st);
+// Enqueue all units: decode-sized units one launch each (projection inside); prefill-sized
+// units in batches of compatible neighbours, projections first, then one GEMM launch.
+static glowq_status forward_all(const glowq_unit* units, int n_units, const uint8_t* mask,
+                                char* workspace, hipStream_t st) {
+  size_t off = 0;
+  int i = 0;
+  while (i < n_units) {
+    const glowq_unit& u = units[i];
+    if (is_decode(u.T)) {
+      UnitWorkspace ws = plan_unit_workspace(u, workspace + off);
+      const bool corr = (!mask || mask[i]) && u.r > 0;
+      hipError_t e = launch_decode(u, ws, corr, st);
+      if (e != hipSuccess) return hip_status(e);
+      off += ws.bytes;
+      ++i;
+      continue;
+    }
+    const glowq_unit* batch[8];
+    UnitWorkspace bws[8];
+    bool corr[8];
+    int nb = 0, nmods = 0;
+    while (i < n_units && nb < prefill_max_units() && nb < 8 && !is_decode(units[i].T) &&
+           (nb == 0 || prefill_compatible(*batch[0], units[i])) &&
+           nmods + units[i].n_modules <= prefill_max_modules()) {
+      batch[nb] = &units[i];
+      bws[nb] = plan_unit_workspace(units[i], workspace + off);
+      corr[nb] = (!mask || mask[i]) && units[i].r > 0;
+      off += bws[nb].bytes;
+      nmods += units[i].n_modules;
+      ++nb;
+      ++i;
+    }
+    for (int j = 0; j < nb; ++j) {
+      if (!corr[j]) continue;
+      hipError_t e = launch_proj(*batch[j], bws[j], nullptr, true, st);
+      if (e != hipSuccess) return hip_status(e);
+    }
+    hipError_t e = launch_prefill_multi(batch, bws, corr, nb, st);
     if (e != hipSuccess) return hip_status(e);
   }
-  hipError_t e = is_decode(u.T) ? launch_decode(u, ws, corr, st) : launch_prefill(u, ws, corr, st);
-  return hip_status(e);
+  return GLOWQ_OK;
 }
 
 }  // namespace glowq
@@ -197,14 +229,7 @@ glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,
     if (misaligned(workspace)) return GLOWQ_ERR_ALIGN;
     if (workspace_bytes < need) return GLOWQ_ERR_WORKSPACE;
   }
-  size_t off = 0;
-  for (int i = 0; i < n_units; ++i) {
-    const bool restore = !restore_mask || restore_mask[i];
-    glowq_status s = forward_one(units[i], restore, (char*)workspace + off, (hipStream_t)stream);
-    if (s != GLOWQ_OK) return s;
-    off += plan_unit_workspace(units[i], nullptr).bytes;
-  }
-  return GLOWQ_OK;
+  return forward_all(units, n_units, restore_mask, (char*)workspace, (hipStream_t)stream);
 }
 
 glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d_in,

@@ -43,8 +43,12 @@ hipError_t launch_proj(const glowq_unit& u, const UnitWorkspace& ws, float* R32,
 // in the first workgroups of the same launch
 hipError_t launch_decode(const glowq_unit& u, const UnitWorkspace& ws, bool restore,
                          hipStream_t st);
-// T > 32: tiled matrix-core GEMM, correction folded in as an extra K slab
-hipError_t launch_prefill(const glowq_unit& u, const UnitWorkspace& ws, bool restore,
-                          hipStream_t st);
+// T > 32: tiled matrix-core GEMM, correction folded in as an extra K slab.  One launch
+// covers several compatible units (same types, group size and token-tile size).
+bool prefill_compatible(const glowq_unit& a, const glowq_unit& b);
+int prefill_max_units();
+int prefill_max_modules();
+hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorkspace* ws,
+                                const bool* restore, int n_units, hipStream_t st);
 
 }  // namespace glowq

@@ -1,82 +1,117 @@
 // Prefill path (T > 32 tokens): Y_i = X dequant(W_q,i)^T + R A_i^T  (paper Eq. 9)
 // as a tiled matrix-core GEMM with the correction folded in as r extra channels.
 //
-// Workgroup tile: (16 MB) tokens x 256 rows, four waves, each wave 64 rows x all
-// tokens of the tile.  The packed weights never pass through LDS: a wave fetches
-// its 16-row x 128-channel tiles with one contiguous 1 KiB load each, already in
-// operand order, dequantises a word into eight 16-bit values in registers (one
-// rounding, the stored weight exactly) and feeds them to the matrix core as the A
-// operand of a 16x16x32 instruction; because every wave covers all tokens of the
-// tile, each weight is dequantised once per workgroup.  X is staged through LDS in
-// 64-channel stages (double buffered, one barrier per stage) and read back as the
-// B operand with 128-bit reads; the row pitch of 144 bytes keeps those reads
-// conflict free.  D is [row][token], so a lane ends up with four consecutive rows
-// of one token and stores them with one 8- or 16-byte write.
+// Workgroup tile: (16 MB) tokens x 256 rows (MB = 8: 128 tokens), four waves, each wave
+// 64 rows x all tokens of the tile; 128 accumulator registers per lane leave room for
+// two workgroups per compute unit, so one wave's dequantisation overlaps another's
+// matrix work.  The packed weights never pass through LDS: a wave fetches its 16-row x
+// 128-channel tiles with one contiguous 1 KiB load each, already in operand order,
+// dequantises a word into eight 16-bit values in registers (one rounding, the stored
+// weight exactly) and feeds them to the matrix core as the A operand of a 16x16x32
+// instruction; because every wave covers all tokens of the tile, each weight is
+// dequantised once per workgroup.  X is staged through LDS in 64-channel stages, double
+// buffered; the 16-byte chunks of a row are XOR-swizzled by the row index so that the
+// 128-bit operand reads are conflict free without padding.  One barrier per stage, and
+// it waits for LDS traffic only: the weight loads of the next tile stay in flight
+// across it.  D is [row][token], so a
+// lane ends up with four consecutive rows of one token and stores them with one 8- or
+// 16-byte write.
 #include "common.hpp"
 #include "launch.hpp"
 
 namespace glowq {
 
 constexpr int PF_WAVES = 4;
-constexpr int PF_PITCH = 72;   // LDS row pitch of the X stage, in 16-bit elements
+
+// One launch covers up to PF_MAX_UNITS units (PF_MAX_MODS modules in all) that share the
+// activation type, group size, output type and token-tile size; the grid is the
+// concatenation of the modules' tile lists, longest contraction first, so that the
+// hardware's in-order dispatch starts the long tiles first.
+constexpr int PF_MAX_UNITS = 8;
+constexpr int PF_MAX_MODS = 16;
+
+struct PfUnit {
+  const uint16_t* X;
+  const uint16_t* R16;
+  int T, K, r, restore, n_mtiles;
+};
 
 struct PfModule {
   const uint32_t* rec;   // tile records (see common.hpp)
   const uint16_t* A;
   void* Y;
-  int d_out, ldy, rows16, nt_start;   // nt_start: first 256-row tile of this module
+  int d_out, ldy, rows16;
+  int unit;              // index into PrefillArgs::unit
+  int wg_start;          // first workgroup of this module in the grid
 };
 
 struct PrefillArgs {
-  PfModule mod[GLOWQ_MAX_MODULES];
-  int n_modules;
-  const uint16_t* X;
-  const uint16_t* R16;
-  int T, K, r, G;
-  int restore, out_f32;
-  int n_mtiles;
+  PfUnit unit[PF_MAX_UNITS];
+  PfModule mod[PF_MAX_MODS];
+  int n_mods;
+  int out_f32;
 };
 
-template <int ACT, int MB>
-__global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t xs[];   // [2][16 MB][PF_PITCH]
-  constexpr int MT = 16 * MB;
-  constexpr int XP = MT / 32;     // X rows per thread and stage
+// s_waitcnt lgkmcnt(0) only (LDS traffic of this wave has completed); vector-memory
+// loads stay in flight.  gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] |
+// vmcnt[5:4] at [15:14].
+__device__ inline void wait_lds_only() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
-  const int mt = (int)(blockIdx.x % (unsigned)a.n_mtiles);
-  const int nt = (int)(blockIdx.x / (unsigned)a.n_mtiles);
+template <int ACT, int MB, bool G128>
+__global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
+  constexpr int MT = 16 * MB;          // tokens per workgroup tile
+  constexpr int XI = MT / 32;          // 16-byte X loads per thread and stage
+  constexpr int RW = G128 ? 272 : 288; // words per tile record
+  // one stage = MT rows x 64 channels, 128 bytes per row, no padding
+  __shared__ __attribute__((aligned(1024))) uint16_t xs0[MT * 64];
+  __shared__ __attribute__((aligned(1024))) uint16_t xs1[MT * 64];
+
   int mi = 0;
 #pragma unroll
-  for (int i = 1; i < GLOWQ_MAX_MODULES; ++i)
-    if (i < a.n_modules && nt >= a.mod[i].nt_start) mi = i;
+  for (int i = 1; i < PF_MAX_MODS; ++i)
+    if (i < a.n_mods && (int)blockIdx.x >= a.mod[i].wg_start) mi = i;
   const PfModule& M = a.mod[mi];
+  const PfUnit& U = a.unit[M.unit];
+  const int local = (int)blockIdx.x - M.wg_start;
+  const int mt = local % U.n_mtiles;
+  const int nt = local / U.n_mtiles;      // 256-row tile within the module
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, kq = lane >> 4;
-  const int ktiles = a.K >> 7;
-  const bool g128 = (a.G == 128);
-  const int rw = g128 ? 272 : 288;             // words per tile record
+  const int ktiles = U.K >> 7;
 
-  // this wave's four 16-row blocks
-  const int nb0 = (nt - M.nt_start) * 16 + 4 * wave;
-  bool valid[4];
+  // this wave's four 16-row blocks; blocks past the module's last one are computed from
+  // a clamped (valid) block and never stored, so that the hot loop carries no branch
+  const int nb0 = nt * 16 + 4 * wave;
   const uint32_t* wt[4];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    valid[b] = nb0 + b < M.rows16;
-    const int nb = valid[b] ? nb0 + b : 0;
-    wt[b] = M.rec + (size_t)nb * ktiles * rw;
-  }
+  for (int b = 0; b < 4; ++b)
+    wt[b] = M.rec + (size_t)min(nb0 + b, M.rows16 - 1) * ktiles * RW;
 
-  // X stage: thread -> (row = tid / 8 + 32 p, 16-byte chunk = tid % 8); rows past T
-  // re-read the last valid token (their columns of D are never stored)
-  const int xr = tid >> 3, xc = tid & 7;
+  // X staging: thread -> (row 32 i + tid / 8, LDS slot tid % 8); the slot holds channel
+  // chunk slot ^ ((row >> 1) & 7).  Rows past T re-read the last valid token (their
+  // columns of D are never stored).
   const int tok0 = mt * MT;
-  const uint16_t* xg[XP];
+  const uint16_t* xsrc[XI];
+  u32x4_t xreg[XI];
 #pragma unroll
-  for (int p = 0; p < XP; ++p)
-    xg[p] = a.X + (size_t)min(tok0 + xr + 32 * p, a.T - 1) * a.K + xc * 8;
+  for (int i = 0; i < XI; ++i) {
+    const int row = 32 * i + (tid >> 3);
+    const int chunk = (tid & 7) ^ ((row >> 1) & 7);
+    xsrc[i] = U.X + (size_t)min(tok0 + row, U.T - 1) * U.K + chunk * 8;
+  }
+  auto load_x = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < XI; ++i) xreg[i] = *(const u32x4_t*)(xsrc[i] + stage * 64);
+  };
+  auto store_x = [&](uint16_t* buf) {
+#pragma unroll
+    for (int i = 0; i < XI; ++i) *(u32x4_t*)(buf + (32 * i) * 64 + tid * 8) = xreg[i];
+  };
+  // operand read: token row mb*16 + n, channel chunk c = 4 jj + kq
+  const int rd_row = n * 64;                    // elements
+  const int rd_sw = (n >> 1) & 7;
 
   float4_t acc[4][MB];
 #pragma unroll
@@ -84,26 +119,15 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[b][mb] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-  u32x4_t xreg[XP];
   u32x4_t wcur[4], wnext[4];
   uint32_t szcur[4][2], sznext[4][2];
-
-  auto load_x = [&](int stage) {
-#pragma unroll
-    for (int p = 0; p < XP; ++p) xreg[p] = *(const u32x4_t*)(xg[p] + stage * 64);
-  };
-  auto store_x = [&](int buf) {
-    uint16_t* dst = xs + (size_t)buf * MT * PF_PITCH + xr * PF_PITCH + xc * 8;
-#pragma unroll
-    for (int p = 0; p < XP; ++p) *(u32x4_t*)(dst + 32 * p * PF_PITCH) = xreg[p];
-  };
   auto load_w = [&](int kt) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-      const uint32_t* rec = wt[b] + (size_t)kt * rw;
+      const uint32_t* rec = wt[b] + (size_t)kt * RW;
       wnext[b] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
       sznext[b][0] = rec[256 + n];
-      sznext[b][1] = g128 ? sznext[b][0] : rec[272 + n];
+      sznext[b][1] = G128 ? sznext[b][0] : rec[272 + n];
     }
   };
   auto take_w = [&]() {
@@ -117,7 +141,7 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
 
   load_x(0);
   load_w(0);
-  store_x(0);
+  store_x(xs0);
   take_w();
   __syncthreads();
 
@@ -126,56 +150,66 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int stage = 2 * kt + half;
+      uint16_t* cur = half == 0 ? xs0 : xs1;
+      uint16_t* nxt = half == 0 ? xs1 : xs0;
+      // next stage's X first, then (first half only) the next tile's weights: loads
+      // retire in order, so the X values can be taken without waiting for the weights
       if (stage + 1 < nstages) load_x(stage + 1);
+      __builtin_amdgcn_sched_barrier(0);
       if (half == 0 && kt + 1 < ktiles) load_w(kt + 1);
+      __builtin_amdgcn_sched_barrier(0);
 
-      const uint16_t* xb = xs + (size_t)(stage & 1) * MT * PF_PITCH + n * PF_PITCH + 8 * kq;
       GroupConst<ACT> g[4];
 #pragma unroll
-      for (int b = 0; b < 4; ++b) g[b].set(szcur[b][half]);
+      for (int b = 0; b < 4; ++b) g[b].set(szcur[b][G128 ? 0 : half]);
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int j = 2 * half + jj;
         u32x4_t wf[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) wf[b] = dequant_word<ACT>(wcur[b][j], g[b]);
+        const uint16_t* xb = cur + rd_row + (((4 * jj + kq) ^ rd_sw) << 3);
+        u32x4_t xf = *(const u32x4_t*)xb;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-          const u32x4_t xf = *(const u32x4_t*)(xb + mb * 16 * PF_PITCH + 32 * jj);
+          u32x4_t xn = xf;
+          if (mb + 1 < MB) xn = *(const u32x4_t*)(xb + (mb + 1) * 16 * 64);
 #pragma unroll
-          for (int b = 0; b < 4; ++b)
-            if (valid[b]) acc[b][mb] = mfma16<ACT>(wf[b], xf, acc[b][mb]);   // D[row][token]
+          for (int b = 0; b < 4; ++b) acc[b][mb] = mfma16<ACT>(wf[b], xf, acc[b][mb]);   // D[row][token]
+          xf = xn;
         }
       }
 
-      if (stage + 1 < nstages) store_x((stage + 1) & 1);
-      __syncthreads();
+      // park the next stage, then one barrier: everyone is done reading `cur` and
+      // everyone's part of `nxt` is in LDS
+      if (stage + 1 < nstages) store_x(nxt);
+      wait_lds_only();
+      __builtin_amdgcn_s_barrier();
     }
     if (kt + 1 < ktiles) take_w();
   }
 
   // correction: r more channels, operand [A_i] against [R]; every lane runs the same
   // trip count, lanes past the rank contribute zeros on both sides
-  if (a.restore) {
-    for (int jj = 0; jj * 32 < a.r; ++jj) {
+  if (U.restore) {
+    for (int jj = 0; jj * 32 < U.r; ++jj) {
       const int j0 = jj * 32 + 8 * kq;
-      const bool ok = j0 < a.r;
+      const bool ok = j0 < U.r;
       const int j0c = ok ? j0 : 0;
       u32x4_t af[4];
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
-        const int row = min((nb0 + b) * 16 + n, M.d_out - 1);
-        af[b] = *(const u32x4_t*)(M.A + (size_t)row * a.r + j0c);
+        const int row = min((nb0 + b) * 16 + n, M.d_out - 1);   // clamped like the tiles
+        af[b] = *(const u32x4_t*)(M.A + (size_t)row * U.r + j0c);
         if (!ok) af[b] = u32x4_t{0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        const int tok = min(tok0 + mb * 16 + n, a.T - 1);
-        u32x4_t rf = *(const u32x4_t*)(a.R16 + (size_t)tok * a.r + j0c);
+        const int tok = min(tok0 + mb * 16 + n, U.T - 1);
+        u32x4_t rf = *(const u32x4_t*)(U.R16 + (size_t)tok * U.r + j0c);
         if (!ok) rf = u32x4_t{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-          if (valid[b]) acc[b][mb] = mfma16<ACT>(af[b], rf, acc[b][mb]);
+        for (int b = 0; b < 4; ++b) acc[b][mb] = mfma16<ACT>(af[b], rf, acc[b][mb]);
       }
     }
   }
@@ -183,13 +217,12 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
   // store: lane holds token (mb, n) and rows 4 kq + {0..3} of each 16-row block
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
-    if (!valid[b]) continue;
     const int row = (nb0 + b) * 16 + 4 * kq;
-    if (row >= M.d_out) continue;
+    if (nb0 + b >= M.rows16 || row >= M.d_out) continue;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       const int tok = tok0 + mb * 16 + n;
-      if (tok >= a.T) continue;
+      if (tok >= U.T) continue;
       const size_t off = (size_t)tok * M.ldy + row;
       const float4_t v = acc[b][mb];
       if (a.out_f32) {
@@ -205,56 +238,73 @@ __global__ void __launch_bounds__(PF_WAVES * 64) k_prefill(PrefillArgs a) {
 }
 
 template <int ACT, int MB>
-static hipError_t launch_prefill_t(const PrefillArgs& a, int n_ntiles, hipStream_t st) {
-  const size_t lds = (size_t)2 * 16 * MB * PF_PITCH * sizeof(uint16_t);
-  auto kern = k_prefill<ACT, MB>;
-  if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
-  dim3 grid((unsigned)(a.n_mtiles * n_ntiles)), block(PF_WAVES * 64);
-  kern<<<grid, block, lds, st>>>(a);
+static hipError_t launch_prefill_t(const PrefillArgs& a, int n_wgs, int G, hipStream_t st) {
+  dim3 grid((unsigned)n_wgs), block(PF_WAVES * 64);
+  if (G == 128) k_prefill<ACT, MB, true><<<grid, block, 0, st>>>(a);
+  else k_prefill<ACT, MB, false><<<grid, block, 0, st>>>(a);
   return hipGetLastError();
 }
 
-hipError_t launch_prefill(const glowq_unit& u, const UnitWorkspace& ws, bool restore,
-                          hipStream_t st) {
+static inline int prefill_mb(int T) { return T <= 64 ? 4 : 8; }
+
+bool prefill_compatible(const glowq_unit& a, const glowq_unit& b) {
+  return a.act_dtype == b.act_dtype && a.out_dtype == b.out_dtype &&
+         a.group_size == b.group_size && prefill_mb(a.T) == prefill_mb(b.T);
+}
+
+int prefill_max_units() { return PF_MAX_UNITS; }
+int prefill_max_modules() { return PF_MAX_MODS; }
+
+// units[i] uses workspace slice ws[i]; restore[i] says whether its R16 is valid.
+hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorkspace* ws,
+                                const bool* restore, int n_units, hipStream_t st) {
   PrefillArgs a;
-  int nt = 0;
-  for (int i = 0; i < u.n_modules; ++i) {
-    const glowq_module& m = u.modules[i];
-    PreparedView v = prepared_view(m.w_prepared, m.d_out, u.d_in, u.group_size);
-    a.mod[i].rec = v.base;
-    a.mod[i].A = (const uint16_t*)m.A;
-    a.mod[i].Y = m.Y;
-    a.mod[i].d_out = m.d_out;
-    a.mod[i].ldy = m.ldy;
-    a.mod[i].rows16 = v.rows16;
-    a.mod[i].nt_start = nt;
-    nt += (v.rows16 + 15) / 16;
+  const glowq_unit& u0 = *units[0];
+  const int MB = prefill_mb(u0.T);
+  // longest contraction first
+  int order[PF_MAX_UNITS];
+  for (int i = 0; i < n_units; ++i) order[i] = i;
+  for (int i = 1; i < n_units; ++i)
+    for (int j = i; j > 0 && units[order[j]]->d_in > units[order[j - 1]]->d_in; --j) {
+      int t = order[j]; order[j] = order[j - 1]; order[j - 1] = t;
+    }
+  int n_mods = 0, wg = 0;
+  for (int oi = 0; oi < n_units; ++oi) {
+    const int ui = order[oi];
+    const glowq_unit& u = *units[ui];
+    PfUnit& pu = a.unit[oi];
+    pu.X = (const uint16_t*)u.X;
+    pu.R16 = (const uint16_t*)(ws[ui].base + ws[ui].off_r16);
+    pu.T = u.T;
+    pu.K = u.d_in;
+    pu.r = u.r;
+    pu.restore = restore[ui] ? 1 : 0;
+    pu.n_mtiles = (u.T + 16 * MB - 1) / (16 * MB);
+    for (int i = 0; i < u.n_modules; ++i) {
+      const glowq_module& m = u.modules[i];
+      PreparedView v = prepared_view(m.w_prepared, m.d_out, u.d_in, u.group_size);
+      PfModule& pm = a.mod[n_mods++];
+      pm.rec = v.base;
+      pm.A = (const uint16_t*)m.A;
+      pm.Y = m.Y;
+      pm.d_out = m.d_out;
+      pm.ldy = m.ldy;
+      pm.rows16 = v.rows16;
+      pm.unit = oi;
+      pm.wg_start = wg;
+      wg += pu.n_mtiles * ((v.rows16 + 15) / 16);
+    }
   }
-  for (int i = u.n_modules; i < GLOWQ_MAX_MODULES; ++i) a.mod[i] = a.mod[0];
-  a.n_modules = u.n_modules;
-  a.X = (const uint16_t*)u.X;
-  a.R16 = (const uint16_t*)(ws.base + ws.off_r16);
-  a.T = u.T;
-  a.K = u.d_in;
-  a.r = u.r;
-  a.G = u.group_size;
-  a.restore = restore ? 1 : 0;
-  a.out_f32 = (u.out_dtype == GLOWQ_F32) ? 1 : 0;
-  const bool f16 = (u.act_dtype == GLOWQ_F16);
-  if (u.T <= 64) {
-    a.n_mtiles = (u.T + 63) / 64;
-    return f16 ? launch_prefill_t<ACT_F16, 4>(a, nt, st) : launch_prefill_t<ACT_BF16, 4>(a, nt, st);
-  }
-  if (u.T <= 128) {
-    a.n_mtiles = (u.T + 127) / 128;
-    return f16 ? launch_prefill_t<ACT_F16, 8>(a, nt, st) : launch_prefill_t<ACT_BF16, 8>(a, nt, st);
-  }
-  a.n_mtiles = (u.T + 255) / 256;
-  return f16 ? launch_prefill_t<ACT_F16, 16>(a, nt, st) : launch_prefill_t<ACT_BF16, 16>(a, nt, st);
+  for (int i = n_units; i < PF_MAX_UNITS; ++i) a.unit[i] = a.unit[0];
+  for (int i = n_mods; i < PF_MAX_MODS; ++i) a.mod[i] = a.mod[0];
+  a.n_mods = n_mods;
+  a.out_f32 = (u0.out_dtype == GLOWQ_F32) ? 1 : 0;
+  const bool f16 = (u0.act_dtype == GLOWQ_F16);
+  if (MB == 4)
+    return f16 ? launch_prefill_t<ACT_F16, 4>(a, wg, u0.group_size, st)
+               : launch_prefill_t<ACT_BF16, 4>(a, wg, u0.group_size, st);
+  return f16 ? launch_prefill_t<ACT_F16, 8>(a, wg, u0.group_size, st)
+             : launch_prefill_t<ACT_BF16, 8>(a, wg, u0.group_size, st);
 }
 
 }  // namespace glowq
