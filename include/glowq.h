@@ -90,11 +90,10 @@ const char* glowq_last_hip_error(void);
 glowq_status glowq_validate_unit(const glowq_unit* u, int32_t check_pointers);
 
 /* ---- weight preparation (one-off, at load time) --------------------------
- * The kernels read weights from a tiled layout in which one 64-lane wavefront
- * fetches 16 rows x 128 input channels with a single contiguous 1 KiB load and
- * every lane's four words are already in matrix-core operand order; scales and
- * zero-points are stored as (s, z) pairs, transposed so that the 16 rows of a
- * tile are contiguous.  d_in must be a multiple of 128, d_out a multiple of 8.
+ * The kernels read weights from tile records of 16 rows x 128 input channels: one
+ * contiguous 1 KiB wave load in which every lane's four words are already in
+ * matrix-core operand order, followed by the tile's (s, z) pairs.  d_in must be a
+ * multiple of 128, d_out a multiple of 8.
  * glowq_prepared_bytes gives the size of that buffer,
  * glowq_prepare_weights fills it from the canonical W4A16 arrays:
  *   wq      DEVICE uint32 [d_out][d_in/8], element 8j+e of a row in bits 4e..4e+3 of word j
@@ -108,19 +107,24 @@ glowq_status glowq_prepare_weights(const uint32_t* wq, const uint16_t* scales,
                                    int32_t group_size, void* w_prepared, void* stream);
 
 /* ---- workspace ------------------------------------------------------------
- * Scratch for a call over `n_units` units (R in 16-bit and fp32 partial sums of
- * the projection, plus a few control words).  The control words must be zero
- * before the first call that uses the buffer: glowq_workspace_init enqueues
- * that clear.  Every call leaves them zero again, so one buffer can serve any
- * number of consecutive calls on one stream; calls that may overlap in time
- * need separate workspaces. */
+ * Scratch for a call over `n_units` units (R in 16 bit, fp32 partial sums of the
+ * projection, a few control words).  glowq_workspace_init clears it; it must be
+ * called once before the first forward call that uses the buffer.  After that one
+ * buffer can serve any number of consecutive calls on one stream, eager or replayed
+ * from a captured graph: a launch recognises its own projection by a tag that is
+ * unique per kernel launch, and every call leaves the arrival counters at zero.  Calls
+ * that may overlap in time need separate workspaces.  Word 3 of a unit's slice (byte
+ * offset 12) is a status word: nonzero means a bounded in-kernel wait expired and the
+ * correction of that unit was left out; it cannot happen unless workgroups of a launch
+ * are prevented from running, and is there so that nothing can ever hang. */
 glowq_status glowq_workspace_bytes(const glowq_unit* units, int32_t n_units, size_t* bytes);
 glowq_status glowq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- the forward (Sec. 3.3) ------------------------------------------------
  * glowq_shared_proj: Eq. 8 alone.  R_out DEVICE fp32 [T][r] receives X B^T
- * (fp32 accumulation).  Exists so that the cached projection can be inspected;
- * the group forward does not need it to be called first.  r must be > 0. */
+ * (fp32 accumulation, K slices added in slice order).  Exists so that the cached
+ * projection can be inspected; the group forward does not need it to be called
+ * first (it computes R itself, inside its own launch for T <= 32).  r must be > 0. */
 glowq_status glowq_shared_proj(const glowq_unit* u, float* R_out, void* workspace,
                                size_t workspace_bytes, void* stream);
 
