@@ -34,6 +34,8 @@ WORKLOADS = {
     "cfg5_T1": (5, 1, "hbm"),
     "cfg5_T1024": (5, 1024, "mfma"),
     "cfg1": (1, 16, "hbm"),
+    # calibration of the HBM traffic counters: a plain device copy of 256 MiB
+    "copy256": (0, 0, "copy"),
 }
 
 
@@ -76,6 +78,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = "cuda"
     cfg_id, T, bound = WORKLOADS[args.workload]
+    if bound == "copy":
+        return copy_calibration(torch, args)
     cfg = CONFIGS[cfg_id]
     r, Gs, act = cfg["r"], cfg["G"], cfg["act"]
     shapes = config_units(cfg_id)
@@ -218,6 +222,29 @@ def main() -> int:
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host_unit0, shapes[0], T, r, Gs, decode)
     print(json.dumps(out))
+    return 0
+
+
+def copy_calibration(torch, args):
+    """Plain device-to-device copy of 256 MiB (reads 256 MiB, writes 256 MiB per step):
+    the known quantity against which the FETCH_SIZE / WRITE_SIZE counters are scaled."""
+    n = 256 << 20
+    steps = args.steps or 20
+    srcs = [torch.empty(n, dtype=torch.uint8, device="cuda").fill_(i) for i in range(3)]
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    for i in range(3):
+        dst.copy_(srcs[i])
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for i in range(steps):
+        dst.copy_(srcs[i % 3])
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    print(json.dumps({"metric": "device copy (counter calibration)", "value": 2 * n / ms / 1e6,
+                      "unit": "GB/s", "bytes_read_per_step": n, "bytes_written_per_step": n,
+                      "steps": steps, "ms_per_step": ms}))
     return 0
 
 
