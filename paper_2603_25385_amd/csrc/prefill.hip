@@ -19,9 +19,13 @@
 #include "common.hpp"
 #include "launch.hpp"
 
+#ifndef PF_EXP
+#define PF_EXP 0
+#endif
 namespace glowq {
 
-constexpr int PF_WAVES = 4;
+constexpr int PF_WAVES = 8;   // two per SIMD
+constexpr int RB = 2;         // 16-row blocks per wave (8 waves x 32 rows = 256 rows per tile)
 
 // One launch covers up to PF_MAX_UNITS units (PF_MAX_MODS modules in all) that share the
 // activation type, group size, output type and token-tile size; the grid is the
@@ -60,7 +64,8 @@ __device__ inline void wait_lds_only() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 template <int ACT, int MB, bool G128>
 __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
   constexpr int MT = 16 * MB;          // tokens per workgroup tile
-  constexpr int XI = MT / 32;          // 16-byte X loads per thread and stage
+  constexpr int XR = PF_WAVES * 8;     // X rows covered by one load instruction of the workgroup
+  constexpr int XI = MT / XR;          // 16-byte X loads per thread and stage
   constexpr int RW = G128 ? 272 : 288; // words per tile record
   // one stage = MT rows x 64 channels, 128 bytes per row, no padding
   __shared__ __attribute__((aligned(1024))) uint16_t xs0[MT * 64];
@@ -83,10 +88,10 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
 
   // this wave's four 16-row blocks; blocks past the module's last one are computed from
   // a clamped (valid) block and never stored, so that the hot loop carries no branch
-  const int nb0 = nt * 16 + 4 * wave;
-  const uint32_t* wt[4];
+  const int nb0 = nt * 16 + RB * wave;
+  const uint32_t* wt[RB];
 #pragma unroll
-  for (int b = 0; b < 4; ++b)
+  for (int b = 0; b < RB; ++b)
     wt[b] = M.rec + (size_t)min(nb0 + b, M.rows16 - 1) * ktiles * RW;
 
   // X staging: thread -> (row 32 i + tid / 8, LDS slot tid % 8); the slot holds channel
@@ -94,37 +99,41 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
   // columns of D are never stored).
   const int tok0 = mt * MT;
   const uint16_t* xsrc[XI];
-  u32x4_t xreg[XI];
+  u32x4_t xreg[2][XI];   // two stages in flight: [parity of the stage]
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
-    const int row = 32 * i + (tid >> 3);
+    const int row = XR * i + (tid >> 3);
     const int chunk = (tid & 7) ^ ((row >> 1) & 7);
     xsrc[i] = U.X + (size_t)min(tok0 + row, U.T - 1) * U.K + chunk * 8;
   }
-  auto load_x = [&](int stage) {
+  const int nstages = 2 * ktiles;
+  // stage indices past the end re-read the last stage (kept in bounds, never used)
+  auto load_x = [&](int stage, u32x4_t (&dst)[XI]) {
+    const int st = min(stage, nstages - 1);
 #pragma unroll
-    for (int i = 0; i < XI; ++i) xreg[i] = *(const u32x4_t*)(xsrc[i] + stage * 64);
+    for (int i = 0; i < XI; ++i) dst[i] = *(const u32x4_t*)(xsrc[i] + st * 64);
   };
-  auto store_x = [&](uint16_t* buf) {
+  auto store_x = [&](uint16_t* buf, const u32x4_t (&src)[XI]) {
 #pragma unroll
-    for (int i = 0; i < XI; ++i) *(u32x4_t*)(buf + (32 * i) * 64 + tid * 8) = xreg[i];
+    for (int i = 0; i < XI; ++i) *(u32x4_t*)(buf + (XR * i) * 64 + tid * 8) = src[i];
   };
   // operand read: token row mb*16 + n, channel chunk c = 4 jj + kq
   const int rd_row = n * 64;                    // elements
   const int rd_sw = (n >> 1) & 7;
 
-  float4_t acc[4][MB];
+  float4_t acc[RB][MB];
 #pragma unroll
-  for (int b = 0; b < 4; ++b)
+  for (int b = 0; b < RB; ++b)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[b][mb] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-  u32x4_t wcur[4], wnext[4];
-  uint32_t szcur[4][2], sznext[4][2];
+  u32x4_t wcur[RB], wnext[RB];
+  uint32_t szcur[RB][2], sznext[RB][2];
   auto load_w = [&](int kt) {
+    const int k = min(kt, ktiles - 1);
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const uint32_t* rec = wt[b] + (size_t)kt * RW;
+    for (int b = 0; b < RB; ++b) {
+      const uint32_t* rec = wt[b] + (size_t)k * RW;
       wnext[b] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
       sznext[b][0] = rec[256 + n];
       sznext[b][1] = G128 ? sznext[b][0] : rec[272 + n];
@@ -132,63 +141,117 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
   };
   auto take_w = [&]() {
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
+    for (int b = 0; b < RB; ++b) {
       wcur[b] = wnext[b];
       szcur[b][0] = sznext[b][0];
       szcur[b][1] = sznext[b][1];
     }
   };
+  // operand words of step j (32 channels) of the current tile, one per 16-row block
+  u32x4_t wf[2][RB];
+  GroupConst<ACT> g[RB];
+  DequantLockstep<ACT, RB> dq;
 
-  load_x(0);
+  GLOWQ_STAMP(0);
+#ifdef GLOWQ_TRACE
+  const unsigned long long clk0 = __builtin_amdgcn_s_memtime();
+#endif
+  load_x(0, xreg[0]);
   load_w(0);
-  store_x(xs0);
+  load_x(1, xreg[1]);
+  store_x(xs0, xreg[0]);
   take_w();
+#pragma unroll
+  for (int b = 0; b < RB; ++b) {
+    g[b].set(szcur[b][0]);
+    wf[0][b] = dequant_word<ACT>(wcur[b][0], g[b]);
+  }
   __syncthreads();
+  GLOWQ_STAMP(1);
 
-  const int nstages = 2 * ktiles;
+  // The loop is software-pipelined over steps of 32 channels, and scheduled by hand in
+  // slices of one matrix instruction each (32 per step, fenced so that the compiler
+  // keeps them apart): behind product (b, mb) of step j rides one slice of the
+  // dequantisation of the operand words of step j+1; the LDS reads of the X fragments
+  // run two token blocks ahead; global loads run two stages (X) and one tile (W) ahead
+  // and are spread over the first slices of a stage, the LDS writes of the next
+  // stage's X over the later ones.
   for (int kt = 0; kt < ktiles; ++kt) {
+#ifdef GLOWQ_TRACE
+    if (kt == 8) GLOWQ_STAMP(2);
+    if (kt == 16) GLOWQ_STAMP(3);
+#endif
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int stage = 2 * kt + half;
       uint16_t* cur = half == 0 ? xs0 : xs1;
       uint16_t* nxt = half == 0 ? xs1 : xs0;
-      // next stage's X first, then (first half only) the next tile's weights: loads
-      // retire in order, so the X values can be taken without waiting for the weights
-      if (stage + 1 < nstages) load_x(stage + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      if (half == 0 && kt + 1 < ktiles) load_w(kt + 1);
-      __builtin_amdgcn_sched_barrier(0);
-
-      GroupConst<ACT> g[4];
-#pragma unroll
-      for (int b = 0; b < 4; ++b) g[b].set(szcur[b][G128 ? 0 : half]);
+      // X fragment f = MB jj + mb of this stage: token block mb, channel chunk 4 jj + kq
+      const uint16_t* xb[2];
+      xb[0] = cur + rd_row + (((0 + kq) ^ rd_sw) << 3);
+      xb[1] = cur + rd_row + (((4 + kq) ^ rd_sw) << 3);
+      auto frag = [&](int f) { return *(const u32x4_t*)(xb[f / MB] + (f % MB) * 16 * 64); };
+      u32x4_t xq[3];
+      xq[0] = frag(0);
+      xq[1] = frag(1);
+      const int xst = min(stage + 2, nstages - 1) * 64;   // X of stage+2 (clamped: re-read, unused)
+      const int wkt = min(kt + 1, ktiles - 1);            // W of the next tile (same)
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int j = 2 * half + jj;
-        u32x4_t wf[4];
+        const int jn = (j + 1) & 3;                        // the step being dequantised
+        if (!(PF_EXP & 2) && j == 3) take_w();
+        const bool new_group = G128 ? (j == 3) : ((j & 1) == 1);
+        const u32x4_t (&wa)[RB] = wf[j & 1];
+        u32x4_t (&wn)[RB] = wf[jn & 1];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) wf[b] = dequant_word<ACT>(wcur[b][j], g[b]);
-        const uint16_t* xb = cur + rd_row + (((4 * jj + kq) ^ rd_sw) << 3);
-        u32x4_t xf = *(const u32x4_t*)xb;
+        for (int i = 0; i < RB * MB; ++i) {
+          const int mb = i / RB, b = i % RB;
+          const int f = MB * jj + mb;
+          // memory slots
+          if (!(PF_EXP & 8) && b == 0 && f + 2 < 2 * MB) xq[(f + 2) % 3] = frag(f + 2);
+          if (!(PF_EXP & 1) && jj == 0 && i < XI) xreg[half][i] = *(const u32x4_t*)(xsrc[i] + xst);
+          if (!(PF_EXP & 2) && j == 0 && i >= XI && i < XI + RB) {
+            const int bb = i - XI;
+            const uint32_t* rec = wt[bb] + (size_t)wkt * RW;
+            wnext[bb] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
+            sznext[bb][0] = rec[256 + n];
+            sznext[bb][1] = G128 ? sznext[bb][0] : rec[272 + n];
+          }
+          if (!(PF_EXP & 16) && jj == 1 && b == RB - 1 && mb >= MB - XI) {
+            const int k = mb - (MB - XI);
+            *(u32x4_t*)(nxt + (XR * k) * 64 + tid * 8) = xreg[half ^ 1][k];
+          }
+          // the product
+          acc[b][mb] = mfma16<ACT>(wa[b], xq[f % 3], acc[b][mb]);   // D[row][token]
+          // its vector-ALU shadow: word i / 8 of the next step, slice i % 8
+          // its vector-ALU shadow: the next instructions of the next step's dequantisation
+          {
+            constexpr int NS = RB * MB;
+            constexpr int NO = DequantLockstep<ACT, RB>::N_OPS;
+            if (i < RB && new_group && !(PF_EXP & 4)) g[i].set(szcur[i][G128 ? 0 : (jn >> 1)]);
+            // the first RB slots carry the group constants when a new group starts; the
+            // recipe's instructions are spread evenly over the slots after them
+            const int lo = i < RB ? 0 : ((i - RB) * NO) / (NS - RB);
+            const int hi = i < RB ? 0 : ((i - RB + 1) * NO) / (NS - RB);
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          u32x4_t xn = xf;
-          if (mb + 1 < MB) xn = *(const u32x4_t*)(xb + (mb + 1) * 16 * 64);
-#pragma unroll
-          for (int b = 0; b < 4; ++b) acc[b][mb] = mfma16<ACT>(wf[b], xf, acc[b][mb]);   // D[row][token]
-          xf = xn;
+            for (int o = lo; o < hi; ++o)
+              if (!(PF_EXP & 4)) dq.op(o, wcur, jn, g, wn);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
-
-      // park the next stage, then one barrier: everyone is done reading `cur` and
-      // everyone's part of `nxt` is in LDS
-      if (stage + 1 < nstages) store_x(nxt);
+      // one barrier per stage: everyone is done reading `cur` and everyone's part of
+      // `nxt` is in LDS
       wait_lds_only();
-      __builtin_amdgcn_s_barrier();
+      if (!(PF_EXP & 32)) __builtin_amdgcn_s_barrier();
     }
-    if (kt + 1 < ktiles) take_w();
   }
 
+  GLOWQ_STAMP(4);
+#ifdef GLOWQ_TRACE
+  if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace[blockIdx.x][7] = __builtin_amdgcn_s_memtime() - clk0;
+#endif
   // correction: r more channels, operand [A_i] against [R]; every lane runs the same
   // trip count, lanes past the rank contribute zeros on both sides
   if (U.restore) {
@@ -196,9 +259,9 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
       const int j0 = jj * 32 + 8 * kq;
       const bool ok = j0 < U.r;
       const int j0c = ok ? j0 : 0;
-      u32x4_t af[4];
+      u32x4_t af[RB];
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
+      for (int b = 0; b < RB; ++b) {
         const int row = min((nb0 + b) * 16 + n, M.d_out - 1);   // clamped like the tiles
         af[b] = *(const u32x4_t*)(M.A + (size_t)row * U.r + j0c);
         if (!ok) af[b] = u32x4_t{0u, 0u, 0u, 0u};
@@ -209,14 +272,15 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
         u32x4_t rf = *(const u32x4_t*)(U.R16 + (size_t)tok * U.r + j0c);
         if (!ok) rf = u32x4_t{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[b][mb] = mfma16<ACT>(af[b], rf, acc[b][mb]);
+        for (int b = 0; b < RB; ++b) acc[b][mb] = mfma16<ACT>(af[b], rf, acc[b][mb]);
       }
     }
   }
 
+  GLOWQ_STAMP(5);
   // store: lane holds token (mb, n) and rows 4 kq + {0..3} of each 16-row block
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
+  for (int b = 0; b < RB; ++b) {
     const int row = (nb0 + b) * 16 + 4 * kq;
     if (nb0 + b >= M.rows16 || row >= M.d_out) continue;
 #pragma unroll
@@ -235,6 +299,7 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
       }
     }
   }
+  GLOWQ_STAMP(6);
 }
 
 template <int ACT, int MB>
@@ -308,3 +373,10 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
 }
 
 }  // namespace glowq
+
+#ifdef GLOWQ_TRACE
+// stage timestamps of the prefill kernel's most recent launch (tracing builds only)
+extern "C" int glowq_debug_trace_prefill(unsigned long long* host_out /* [8192][8] */) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(glowq::g_trace), sizeof(glowq::g_trace));
+}
+#endif
