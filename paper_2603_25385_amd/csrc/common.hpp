@@ -152,34 +152,37 @@ __device__ inline u32x4_t dequant_word<ACT_BF16>(uint32_t w, const GroupConst<AC
 // instruction (16x16x32) takes 8 of its 16 cycles of issue, two more instructions ride
 // free behind it, every further one costs 4 cycles, and a vector-ALU instruction that
 // reads the result of one of the two instructions before it stalls 4 cycles.  Hence the
-// order: instruction `idx` works on word idx % NW and is phase idx / NW of that word's
-// recipe, so that dependent instructions are NW apart.  Running idx =
+// order: the words are taken two at a time, and within a pair instruction `idx`
+// alternates between the two words, so that dependent instructions are two apart
+// (with two waves per SIMD the other wave's instructions fall in between as well).  Running idx =
 // 0 .. N_OPS-1 in order leaves in out[w] exactly what dequant_word returns for w[w].
 template <int ACT, int NW> struct DequantLockstep;
 template <int NW> struct DequantLockstep<ACT_F16, NW> {
-  static constexpr int N_OPS = NW * 15;
-  uint32_t ws[NW];   // the word, shifted for the pair in flight
-  half2_t d[NW];     // (q - z) pair in flight
+  static constexpr int PH = 15, GS = NW < 2 ? NW : 2;
+  static constexpr int N_OPS = NW * PH;
+  uint32_t ws[GS];   // the word, shifted for the pair in flight
+  half2_t d[GS];     // (q - z) pair in flight
   __device__ inline void op(int idx, const u32x4_t (&wq)[NW], int j, const GroupConst<ACT_F16> (&g)[NW],
                             u32x4_t (&out)[NW]) {
-    const int w = idx % NW, ph = idx / NW;
+    const int r_ = idx % (GS * PH), c = r_ % GS, w = (idx / (GS * PH)) * GS + c, ph = r_ / GS;
     // phases: ao0 add0 mul0 | shr1 ao1 add1 mul1 | shr2 ao2 add2 mul2 | shr3 ao3 add3 mul3
     const int i = (ph + 1) >> 2, kind = (ph + 1) & 3;   // kind 0 shr, 1 and_or, 2 add, 3 mul
-    if (kind == 0) ws[w] = wq[w][j] >> (4 * i);
+    if (kind == 0) ws[c] = wq[w][j] >> (4 * i);
     else if (kind == 1) {
-      const uint32_t t = and_or(i == 0 ? wq[w][j] : ws[w], 0x000F000Fu, 0x64006400u);
-      d[w] = __builtin_bit_cast(half2_t, t);
-    } else if (kind == 2) d[w] = d[w] + g[w].nb2;
+      const uint32_t t = and_or(i == 0 ? wq[w][j] : ws[c], 0x000F000Fu, 0x64006400u);
+      d[c] = __builtin_bit_cast(half2_t, t);
+    } else if (kind == 2) d[c] = d[c] + g[w].nb2;
     else {
-      const half2_t v = d[w] * g[w].s2;   // the one rounding
+      const half2_t v = d[c] * g[w].s2;   // the one rounding
       out[w][i] = __builtin_bit_cast(uint32_t, v);
     }
   }
 };
 template <int NW> struct DequantLockstep<ACT_BF16, NW> {
-  static constexpr int N_OPS = NW * 23;
-  uint32_t m0[NW], m1[NW];
-  float f[NW][2];
+  static constexpr int PH = 23, GS = NW < 2 ? NW : 2;
+  static constexpr int N_OPS = NW * PH;
+  uint32_t m0[GS], m1[GS];
+  float f[GS][2];
   __device__ static inline float ub(int byte, uint32_t m) {
     float r;
     if (byte == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(m));
@@ -193,23 +196,23 @@ template <int NW> struct DequantLockstep<ACT_BF16, NW> {
   // pair 0 = (m0.b0, m0.b2), pair 1 = (m1.b0, m1.b2), pair 2 = (m0.b1, m0.b3), pair 3 = (m1.b1, m1.b3)
   __device__ inline void op(int idx, const u32x4_t (&wq)[NW], int j, const GroupConst<ACT_BF16> (&g)[NW],
                             u32x4_t (&out)[NW]) {
-    const int w = idx % NW, ph = idx / NW;
-    if (ph == 0) m0[w] = wq[w][j] & 0x0F0F0F0Fu;
-    else if (ph == 1) m1[w] = wq[w][j] >> 4;
-    else if (ph == 2) m1[w] = m1[w] & 0x0F0F0F0Fu;
+    const int r_ = idx % (GS * PH), c = r_ % GS, w = (idx / (GS * PH)) * GS + c, ph = r_ / GS;
+    if (ph == 0) m0[c] = wq[w][j] & 0x0F0F0F0Fu;
+    else if (ph == 1) m1[c] = wq[w][j] >> 4;
+    else if (ph == 2) m1[c] = m1[c] & 0x0F0F0F0Fu;
     else {
       // phases per pair i: cvt a, cvt b, fma a, fma b, pack
       const int i = (ph - 3) / 5, kind = (ph - 3) % 5;
-      const uint32_t src = (i & 1) ? m1[w] : m0[w];
+      const uint32_t src = (i & 1) ? m1[c] : m0[c];
       const int byte_a = (i >> 1), byte_b = (i >> 1) + 2;
-      if (kind == 0) f[w][0] = ub(byte_a, src);
-      else if (kind == 1) f[w][1] = ub(byte_b, src);
-      else if (kind == 2) f[w][0] = __builtin_fmaf(f[w][0], g[w].s, g[w].nzs);
-      else if (kind == 3) f[w][1] = __builtin_fmaf(f[w][1], g[w].s, g[w].nzs);
+      if (kind == 0) f[c][0] = ub(byte_a, src);
+      else if (kind == 1) f[c][1] = ub(byte_b, src);
+      else if (kind == 2) f[c][0] = __builtin_fmaf(f[c][0], g[w].s, g[w].nzs);
+      else if (kind == 3) f[c][1] = __builtin_fmaf(f[c][1], g[w].s, g[w].nzs);
       else {
         bf16x2_t v;
-        v[0] = (__bf16)f[w][0];
-        v[1] = (__bf16)f[w][1];
+        v[0] = (__bf16)f[c][0];
+        v[1] = (__bf16)f[c][1];
         out[w][i] = __builtin_bit_cast(uint32_t, v);
       }
     }

@@ -24,8 +24,15 @@
 #endif
 namespace glowq {
 
-constexpr int PF_WAVES = 8;   // two per SIMD
-constexpr int RB = 2;         // 16-row blocks per wave (8 waves x 32 rows = 256 rows per tile)
+// Two waves per SIMD either way: binary16 runs two workgroups of four waves per compute
+// unit (64 rows per wave; a workgroup waiting at its barrier or for memory leaves the
+// matrix cores to the other one), bfloat16, whose dequantiser needs more registers, one
+// workgroup of eight waves (32 rows per wave).
+template <int ACT> struct PfShape {
+  static constexpr int WAVES = ACT == ACT_F16 ? 4 : 8;
+  static constexpr int RB = 16 / WAVES;    // 16-row blocks per wave (256 rows per tile)
+  static constexpr int OCC = 8 / WAVES;    // workgroups per compute unit
+};
 
 // One launch covers up to PF_MAX_UNITS units (PF_MAX_MODS modules in all) that share the
 // activation type, group size, output type and token-tile size; the grid is the
@@ -61,15 +68,25 @@ struct PrefillArgs {
 // vmcnt[5:4] at [15:14].
 __device__ inline void wait_lds_only() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
+__device__ inline void lds_read(u32x4_t& v, uint32_t addr, int imm) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");
+}
+template <int N> __device__ inline void lds_wait(u32x4_t& v) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
+}
+
 template <int ACT, int MB, bool G128>
-__global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
+__global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k_prefill(PrefillArgs a) {
+  constexpr int PF_WAVES = PfShape<ACT>::WAVES, RB = PfShape<ACT>::RB;
   constexpr int MT = 16 * MB;          // tokens per workgroup tile
   constexpr int XR = PF_WAVES * 8;     // X rows covered by one load instruction of the workgroup
   constexpr int XI = MT / XR;          // 16-byte X loads per thread and stage
   constexpr int RW = G128 ? 272 : 288; // words per tile record
-  // one stage = MT rows x 64 channels, 128 bytes per row, no padding
-  __shared__ __attribute__((aligned(1024))) uint16_t xs0[MT * 64];
-  __shared__ __attribute__((aligned(1024))) uint16_t xs1[MT * 64];
+  // one stage = MT rows x 64 channels, 128 bytes per row, no padding; a ring of three:
+  // the stage being read, the next one (landed or landing), the one after (landing)
+  constexpr int NBUF = 3;
+  constexpr uint32_t STAGE_BYTES = MT * 64 * 2;
+  __shared__ __attribute__((aligned(1024))) uint16_t xs[NBUF * MT * 64];
 
   int mi = 0;
 #pragma unroll
@@ -94,12 +111,13 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
   for (int b = 0; b < RB; ++b)
     wt[b] = M.rec + (size_t)min(nb0 + b, M.rows16 - 1) * ktiles * RW;
 
-  // X staging: thread -> (row 32 i + tid / 8, LDS slot tid % 8); the slot holds channel
-  // chunk slot ^ ((row >> 1) & 7).  Rows past T re-read the last valid token (their
-  // columns of D are never stored).
+  // X staging, global memory straight into LDS (no registers in between): the wave's
+  // load i covers rows XR i + 8 wave + (lane >> 3), one 16-byte chunk per lane, 1 KiB
+  // contiguous in LDS; lane (row, slot = lane & 7) fetches channel chunk
+  // slot ^ ((row >> 1) & 7), which is what makes the operand reads conflict free.  Rows
+  // past T re-read the last valid token (their columns of D are never stored).
   const int tok0 = mt * MT;
   const uint16_t* xsrc[XI];
-  u32x4_t xreg[2][XI];   // two stages in flight: [parity of the stage]
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
     const int row = XR * i + (tid >> 3);
@@ -107,19 +125,24 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
     xsrc[i] = U.X + (size_t)min(tok0 + row, U.T - 1) * U.K + chunk * 8;
   }
   const int nstages = 2 * ktiles;
-  // stage indices past the end re-read the last stage (kept in bounds, never used)
-  auto load_x = [&](int stage, u32x4_t (&dst)[XI]) {
+  // stage indices past the end re-read the last stage into a ring slot nobody reads
+  auto dma_x = [&](int stage, int slot, int i) {
     const int st = min(stage, nstages - 1);
-#pragma unroll
-    for (int i = 0; i < XI; ++i) dst[i] = *(const u32x4_t*)(xsrc[i] + st * 64);
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(xsrc[i] + st * 64),
+        (__attribute__((address_space(3))) void*)(xs + slot * (MT * 64) + (XR * i + 8 * wave) * 64),
+        16, 0, 0);
   };
-  auto store_x = [&](uint16_t* buf, const u32x4_t (&src)[XI]) {
-#pragma unroll
-    for (int i = 0; i < XI; ++i) *(u32x4_t*)(buf + (XR * i) * 64 + tid * 8) = src[i];
-  };
+  // The operand reads are issued as assembly, because the compiler orders every LDS
+  // read it can see behind all LDS-bound loads in flight; so the waits are placed here
+  // too: lds_read leaves its result pending, lds_wait<N> makes `v` usable once at most
+  // N younger reads are outstanding (LDS reads of a wave return in order).
+  const uint32_t xs_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)xs;
   // operand read: token row mb*16 + n, channel chunk c = 4 jj + kq
   const int rd_row = n * 64;                    // elements
   const int rd_sw = (n >> 1) & 7;
+  const uint32_t rd_lane[2] = {xs_base + 2u * (uint32_t)(rd_row + (((0 + kq) ^ rd_sw) << 3)),
+                               xs_base + 2u * (uint32_t)(rd_row + (((4 + kq) ^ rd_sw) << 3))};
 
   float4_t acc[RB][MB];
 #pragma unroll
@@ -156,17 +179,19 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
 #ifdef GLOWQ_TRACE
   const unsigned long long clk0 = __builtin_amdgcn_s_memtime();
 #endif
-  load_x(0, xreg[0]);
+#pragma unroll
+  for (int i = 0; i < XI; ++i) dma_x(0, 0, i);
   load_w(0);
-  load_x(1, xreg[1]);
-  store_x(xs0, xreg[0]);
+#pragma unroll
+  for (int i = 0; i < XI; ++i) dma_x(1, 1, i);
   take_w();
 #pragma unroll
   for (int b = 0; b < RB; ++b) {
     g[b].set(szcur[b][0]);
     wf[0][b] = dequant_word<ACT>(wcur[b][0], g[b]);
   }
-  __syncthreads();
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
   GLOWQ_STAMP(1);
 
   // The loop is software-pipelined over steps of 32 channels, and scheduled by hand in
@@ -176,6 +201,7 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
   // run two token blocks ahead; global loads run two stages (X) and one tile (W) ahead
   // and are spread over the first slices of a stage, the LDS writes of the next
   // stage's X over the later ones.
+  int slot_cur = 0, slot_next2 = 2;   // ring slots of the stage being read and of stage+2
   for (int kt = 0; kt < ktiles; ++kt) {
 #ifdef GLOWQ_TRACE
     if (kt == 8) GLOWQ_STAMP(2);
@@ -184,17 +210,12 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int stage = 2 * kt + half;
-      uint16_t* cur = half == 0 ? xs0 : xs1;
-      uint16_t* nxt = half == 0 ? xs1 : xs0;
       // X fragment f = MB jj + mb of this stage: token block mb, channel chunk 4 jj + kq
-      const uint16_t* xb[2];
-      xb[0] = cur + rd_row + (((0 + kq) ^ rd_sw) << 3);
-      xb[1] = cur + rd_row + (((4 + kq) ^ rd_sw) << 3);
-      auto frag = [&](int f) { return *(const u32x4_t*)(xb[f / MB] + (f % MB) * 16 * 64); };
+      const uint32_t xa[2] = {rd_lane[0] + (uint32_t)slot_cur * STAGE_BYTES,
+                              rd_lane[1] + (uint32_t)slot_cur * STAGE_BYTES};
       u32x4_t xq[3];
-      xq[0] = frag(0);
-      xq[1] = frag(1);
-      const int xst = min(stage + 2, nstages - 1) * 64;   // X of stage+2 (clamped: re-read, unused)
+      lds_read(xq[0], xa[0], 0);
+      lds_read(xq[1], xa[0], 2048);
       const int wkt = min(kt + 1, ktiles - 1);            // W of the next tile (same)
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
@@ -209,18 +230,23 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
           const int mb = i / RB, b = i % RB;
           const int f = MB * jj + mb;
           // memory slots
-          if (!(PF_EXP & 8) && b == 0 && f + 2 < 2 * MB) xq[(f + 2) % 3] = frag(f + 2);
-          if (!(PF_EXP & 1) && jj == 0 && i < XI) xreg[half][i] = *(const u32x4_t*)(xsrc[i] + xst);
+          if (b == 0) {
+            if (f + 2 < 2 * MB) {
+              lds_read(xq[(f + 2) % 3], xa[(f + 2) / MB], ((f + 2) % MB) * 2048);
+              lds_wait<2>(xq[f % 3]);
+            } else if (f + 2 == 2 * MB) lds_wait<1>(xq[f % 3]);
+            else lds_wait<0>(xq[f % 3]);
+          }
+          // X of stage+2: in the tile's first stage right away, in its second stage
+          // behind the point where the next tile's weights are taken (the compiler
+          // waits there for every load in flight, and these should not be among them)
+          if (jj == half && i < XI) dma_x(stage + 2, slot_next2, i);
           if (!(PF_EXP & 2) && j == 0 && i >= XI && i < XI + RB) {
             const int bb = i - XI;
             const uint32_t* rec = wt[bb] + (size_t)wkt * RW;
             wnext[bb] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
             sznext[bb][0] = rec[256 + n];
             sznext[bb][1] = G128 ? sznext[bb][0] : rec[272 + n];
-          }
-          if (!(PF_EXP & 16) && jj == 1 && b == RB - 1 && mb >= MB - XI) {
-            const int k = mb - (MB - XI);
-            *(u32x4_t*)(nxt + (XR * k) * 64 + tid * 8) = xreg[half ^ 1][k];
           }
           // the product
           acc[b][mb] = mfma16<ACT>(wa[b], xq[f % 3], acc[b][mb]);   // D[row][token]
@@ -241,12 +267,21 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      // one barrier per stage: everyone is done reading `cur` and everyone's part of
-      // `nxt` is in LDS
-      wait_lds_only();
+      // one barrier per stage: everyone is done reading this stage, and everyone's part
+      // of the next stage has landed.  Vector-memory operations complete in order, and
+      // the ones issued after the next stage's loads are the XI loads of the stage after
+      // it plus one tile's weight loads (issued in this stage or in the one before).
+      {
+        constexpr int YOUNGER = XI + RB * (G128 ? 2 : 3);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(YOUNGER) : "memory");
+      }
       if (!(PF_EXP & 32)) __builtin_amdgcn_s_barrier();
+      slot_cur = slot_cur == NBUF - 1 ? 0 : slot_cur + 1;
+      slot_next2 = slot_next2 == NBUF - 1 ? 0 : slot_next2 + 1;
     }
   }
+  // nothing of this workgroup may still be on its way into LDS when the workgroup ends
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   GLOWQ_STAMP(4);
 #ifdef GLOWQ_TRACE
@@ -304,7 +339,7 @@ __global__ void __launch_bounds__(PF_WAVES * 64, 1) k_prefill(PrefillArgs a) {
 
 template <int ACT, int MB>
 static hipError_t launch_prefill_t(const PrefillArgs& a, int n_wgs, int G, hipStream_t st) {
-  dim3 grid((unsigned)n_wgs), block(PF_WAVES * 64);
+  dim3 grid((unsigned)n_wgs), block(PfShape<ACT>::WAVES * 64);
   if (G == 128) k_prefill<ACT, MB, true><<<grid, block, 0, st>>>(a);
   else k_prefill<ACT, MB, false><<<grid, block, 0, st>>>(a);
   return hipGetLastError();
