@@ -113,11 +113,7 @@ static glowq_status forward_all(const glowq_unit* units, int n_units, const uint
       ++nb;
       ++i;
     }
-    for (int j = 0; j < nb; ++j) {
-      if (!corr[j]) continue;
-      hipError_t e = launch_proj(*batch[j], bws[j], nullptr, true, st);
-      if (e != hipSuccess) return hip_status(e);
-    }
+    // (the projections of the batch run as the first tiles of the same launch)
     hipError_t e = launch_prefill_multi(batch, bws, corr, nb, st);
     if (e != hipSuccess) return hip_status(e);
   }

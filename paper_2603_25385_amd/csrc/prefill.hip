@@ -32,6 +32,7 @@ template <int ACT> struct PfShape {
   static constexpr int WAVES = ACT == ACT_F16 ? 4 : 8;
   static constexpr int RB = 16 / WAVES;    // 16-row blocks per wave (256 rows per tile)
   static constexpr int OCC = 8 / WAVES;    // workgroups per compute unit
+  static constexpr int XD = ACT == ACT_F16 ? 2 : 4;   // LDS operand reads in flight per wave
 };
 
 // One launch covers up to PF_MAX_UNITS units (PF_MAX_MODS modules in all) that share the
@@ -43,8 +44,12 @@ constexpr int PF_MAX_MODS = 16;
 
 struct PfUnit {
   const uint16_t* X;
-  const uint16_t* R16;
+  const uint16_t* B;       // shared right factor [r][K]
+  uint16_t* R16;           // R = X B^T rounded to the activation type, [T][r], in the workspace
+  uint32_t* flags;         // one word per 16-token block; word MB*mt is token tile mt's ready flag
+  uint32_t* status;        // the unit's status word (see Control)
   int T, K, r, restore, n_mtiles;
+  int proj_start;          // first workgroup of this unit's projection tiles in the grid
 };
 
 struct PfModule {
@@ -60,6 +65,8 @@ struct PrefillArgs {
   PfUnit unit[PF_MAX_UNITS];
   PfModule mod[PF_MAX_MODS];
   int n_mods;
+  int n_units;
+  int n_proj_wgs;          // the grid starts with this many projection tiles
   int out_f32;
 };
 
@@ -75,6 +82,181 @@ template <int N> __device__ inline void lds_wait(u32x4_t& v) {
   asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
 }
 
+// A 16-byte global load whose completion is waited for by hand (vm_wait): the compiler
+// does not see it as a memory operation, so it adds no wait of its own, and the waits
+// it does add for loads it knows never cover these.
+__device__ inline void vm_load(u32x4_t& v, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+}
+template <int N> __device__ inline void vm_wait() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// ties a value to a point behind a wait, so that nothing that uses it moves above
+__device__ inline void after_wait(u32x4_t& v) { asm volatile("" : "+v"(v)); }
+
+// Projection tile of the prefill launch: R[tile] = X[tile] B^T  (paper Eq. 8), MT tokens x
+// all r ranks over the whole contraction, rounded once to the activation type and
+// stored in the workspace; then the tile's flag is set to this launch's tag.  These
+// tiles are the first workgroups of the grid, so they are running before any tile that
+// needs their result has started, and they wait for nothing.
+// X takes the same path as in the main tiles (LDS ring, swizzled rows); the rows of B
+// are read straight into operand registers, one stage ahead.
+template <int ACT, int MB>
+__device__ inline void proj_tile(const PrefillArgs& a, uint16_t* xs) {
+  constexpr int PF_WAVES = PfShape<ACT>::WAVES;
+  constexpr int RBP = 8 / PF_WAVES;      // 16-rank blocks per wave (r <= 128)
+  constexpr int MT = 16 * MB, XR = PF_WAVES * 8, XI = MT / XR, NBUF = 3;
+  constexpr uint32_t STAGE_BYTES = MT * 64 * 2;
+  // units without a projection carry proj_start = -1; the others' increase with the index
+  int ui = 0;
+#pragma unroll
+  for (int i = 0; i < PF_MAX_UNITS; ++i)
+    if (i < a.n_units && a.unit[i].proj_start >= 0 && (int)blockIdx.x >= a.unit[i].proj_start) ui = i;
+  const PfUnit& U = a.unit[ui];
+  const int mt = (int)blockIdx.x - U.proj_start;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 15, kq = lane >> 4;
+  const int nstages = U.K >> 6;
+  const int tok0 = mt * MT;
+
+  const uint16_t* xsrc[XI];
+#pragma unroll
+  for (int i = 0; i < XI; ++i) {
+    const int row = XR * i + (tid >> 3);
+    const int chunk = (tid & 7) ^ ((row >> 1) & 7);
+    xsrc[i] = U.X + (size_t)min(tok0 + row, U.T - 1) * U.K + chunk * 8;
+  }
+  auto dma_x = [&](int stage, int slot, int i) {
+    const int st = min(stage, nstages - 1);
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(xsrc[i] + st * 64),
+        (__attribute__((address_space(3))) void*)(xs + slot * (MT * 64) + (XR * i + 8 * wave) * 64),
+        16, 0, 0);
+  };
+  const uint32_t xs_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)xs;
+  const int rd_row = n * 64, rd_sw = (n >> 1) & 7;
+  const uint32_t rd_lane[2] = {xs_base + 2u * (uint32_t)(rd_row + (((0 + kq) ^ rd_sw) << 3)),
+                               xs_base + 2u * (uint32_t)(rd_row + (((4 + kq) ^ rd_sw) << 3))};
+  // rank rows of this lane, clamped (ranks past r are computed from row r-1, not stored)
+  const uint16_t* bsrc[RBP];
+#pragma unroll
+  for (int b = 0; b < RBP; ++b)
+    bsrc[b] = U.B + (size_t)min((wave * RBP + b) * 16 + n, U.r - 1) * U.K + 8 * kq;
+  u32x4_t bcur[RBP][2], bnext[RBP][2];   // operand words of the two 32-channel steps of a stage
+  auto load_b = [&](int stage) {
+    const int st = min(stage, nstages - 1);
+#pragma unroll
+    for (int b = 0; b < RBP; ++b)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) vm_load(bnext[b][jj], bsrc[b] + st * 64 + jj * 32);
+  };
+
+  float4_t acc[RBP][MB];
+#pragma unroll
+  for (int b = 0; b < RBP; ++b)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[b][mb] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+  for (int i = 0; i < XI; ++i) dma_x(0, 0, i);
+#pragma unroll
+  for (int i = 0; i < XI; ++i) dma_x(1, 1, i);
+  load_b(0);
+  vm_wait<0>();
+#pragma unroll
+  for (int b = 0; b < RBP; ++b)
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) { after_wait(bnext[b][jj]); bcur[b][jj] = bnext[b][jj]; }
+  __builtin_amdgcn_s_barrier();
+
+  int slot_cur = 0, slot_next2 = 2;
+  for (int stage = 0; stage < nstages; ++stage) {
+    const uint32_t xa[2] = {rd_lane[0] + (uint32_t)slot_cur * STAGE_BYTES,
+                            rd_lane[1] + (uint32_t)slot_cur * STAGE_BYTES};
+    u32x4_t xq[3];
+    lds_read(xq[0], xa[0], 0);
+    lds_read(xq[1], xa[0], 2048);
+    // in this order: the next stage's B words, then X of the stage after next
+    load_b(stage + 1);
+#pragma unroll
+    for (int i = 0; i < XI; ++i) dma_x(stage + 2, slot_next2, i);
+#pragma unroll
+    for (int f = 0; f < 2 * MB; ++f) {
+      if (f + 2 < 2 * MB) {
+        lds_read(xq[(f + 2) % 3], xa[(f + 2) / MB], ((f + 2) % MB) * 2048);
+        lds_wait<2>(xq[f % 3]);
+      } else if (f + 2 == 2 * MB) lds_wait<1>(xq[f % 3]);
+      else lds_wait<0>(xq[f % 3]);
+#pragma unroll
+      for (int b = 0; b < RBP; ++b)
+        acc[b][f % MB] = mfma16<ACT>(bcur[b][f / MB], xq[f % 3], acc[b][f % MB]);   // D[rank][token]
+    }
+    // everything older than this stage's XI X loads has completed after this: the next
+    // stage's X (issued a stage ago) and the next stage's B words
+    vm_wait<XI>();
+#pragma unroll
+    for (int b = 0; b < RBP; ++b)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) { after_wait(bnext[b][jj]); bcur[b][jj] = bnext[b][jj]; }
+    __builtin_amdgcn_s_barrier();
+    slot_cur = slot_cur == NBUF - 1 ? 0 : slot_cur + 1;
+    slot_next2 = slot_next2 == NBUF - 1 ? 0 : slot_next2 + 1;
+  }
+  vm_wait<0>();   // nothing may still be on its way into LDS when the workgroup ends
+
+  // lane holds token (mb, n) and ranks 16 blk + 4 kq + {0..3}
+#pragma unroll
+  for (int b = 0; b < RBP; ++b) {
+    const int rank0 = (wave * RBP + b) * 16 + 4 * kq;
+    if (rank0 >= U.r) continue;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int tok = tok0 + mb * 16 + n;
+      if (tok >= U.T) continue;
+      const float4_t v = acc[b][mb];
+      uint2 pk;
+      pk.x = (uint32_t)to_act16<ACT>(v[0]) | ((uint32_t)to_act16<ACT>(v[1]) << 16);
+      pk.y = (uint32_t)to_act16<ACT>(v[2]) | ((uint32_t)to_act16<ACT>(v[3]) << 16);
+      *(uint2*)(U.R16 + (size_t)tok * U.r + rank0) = pk;
+    }
+  }
+  // publish: every wave makes its stores visible device-wide, then one thread sets the flag
+  __threadfence();
+  __syncthreads();
+  if (tid == 0)
+    __hip_atomic_store(U.flags + MB * mt, (uint32_t)launch_tag(), __ATOMIC_RELEASE,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Waits until token tile mt's part of R carries this launch's tag.  The projection tiles
+// lead the grid and wait for nothing, so by the time a main tile has run through its
+// whole contraction they have long finished; the loop is bounded all the same, and a
+// wave that gives up records it in the unit's status word and leaves the correction out
+// rather than hang.
+__device__ inline bool wait_tile_ready(const uint32_t* flag, uint32_t* status) {
+  const uint32_t tag = (uint32_t)launch_tag();
+  bool ok = false;
+  for (int spin = 0; spin < (1 << 20); ++spin) {
+    if (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == tag) { ok = true; break; }
+    __builtin_amdgcn_s_sleep(8);
+  }
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  if (!ok && (threadIdx.x & 63) == 0) atomicOr(status, 1u);
+  return ok;
+}
+// Eight 16-bit values read with device-scope loads: they bypass whatever this compute
+// unit or this XCD's L2 may still hold for the address from an earlier launch.
+__device__ inline u32x4_t load16_device(const uint16_t* p) {
+  const uint32_t* q = (const uint32_t*)p;
+  u32x4_t v;
+  v[0] = __hip_atomic_load(q + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  v[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  v[2] = __hip_atomic_load(q + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  v[3] = __hip_atomic_load(q + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return v;
+}
+
 template <int ACT, int MB, bool G128>
 __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k_prefill(PrefillArgs a) {
   constexpr int PF_WAVES = PfShape<ACT>::WAVES, RB = PfShape<ACT>::RB;
@@ -88,6 +270,10 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   constexpr uint32_t STAGE_BYTES = MT * 64 * 2;
   __shared__ __attribute__((aligned(1024))) uint16_t xs[NBUF * MT * 64];
 
+  if ((int)blockIdx.x < a.n_proj_wgs) {
+    proj_tile<ACT, MB>(a, xs);
+    return;
+  }
   int mi = 0;
 #pragma unroll
   for (int i = 1; i < PF_MAX_MODS; ++i)
@@ -213,10 +399,12 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
       // X fragment f = MB jj + mb of this stage: token block mb, channel chunk 4 jj + kq
       const uint32_t xa[2] = {rd_lane[0] + (uint32_t)slot_cur * STAGE_BYTES,
                               rd_lane[1] + (uint32_t)slot_cur * STAGE_BYTES};
-      u32x4_t xq[3];
-      lds_read(xq[0], xa[0], 0);
-      lds_read(xq[1], xa[0], 2048);
-      const int wkt = min(kt + 1, ktiles - 1);            // W of the next tile (same)
+      // operand fragments are read XD token blocks ahead of their use
+      constexpr int XD = PfShape<ACT>::XD;
+      u32x4_t xq[XD + 1];
+#pragma unroll
+      for (int f = 0; f < XD; ++f) lds_read(xq[f], xa[f / MB], (f % MB) * 2048);
+      const int wkt = (PF_EXP & 64) ? 0 : min(kt + 1, ktiles - 1);            // W of the next tile (same)
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int j = 2 * half + jj;
@@ -231,11 +419,16 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
           const int f = MB * jj + mb;
           // memory slots
           if (b == 0) {
-            if (f + 2 < 2 * MB) {
-              lds_read(xq[(f + 2) % 3], xa[(f + 2) / MB], ((f + 2) % MB) * 2048);
-              lds_wait<2>(xq[f % 3]);
-            } else if (f + 2 == 2 * MB) lds_wait<1>(xq[f % 3]);
-            else lds_wait<0>(xq[f % 3]);
+            if (f + XD < 2 * MB) {
+              lds_read(xq[(f + XD) % (XD + 1)], xa[(f + XD) / MB], ((f + XD) % MB) * 2048);
+              lds_wait<XD>(xq[f % (XD + 1)]);
+            } else {
+              // the tail of the stage: 2 MB - 1 - f younger reads are outstanding
+              if (2 * MB - 1 - f == 3) lds_wait<3>(xq[f % (XD + 1)]);
+              else if (2 * MB - 1 - f == 2) lds_wait<2>(xq[f % (XD + 1)]);
+              else if (2 * MB - 1 - f == 1) lds_wait<1>(xq[f % (XD + 1)]);
+              else lds_wait<0>(xq[f % (XD + 1)]);
+            }
           }
           // X of stage+2: in the tile's first stage right away, in its second stage
           // behind the point where the next tile's weights are taken (the compiler
@@ -249,7 +442,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
             sznext[bb][1] = G128 ? sznext[bb][0] : rec[272 + n];
           }
           // the product
-          acc[b][mb] = mfma16<ACT>(wa[b], xq[f % 3], acc[b][mb]);   // D[row][token]
+          acc[b][mb] = mfma16<ACT>(wa[b], xq[f % (XD + 1)], acc[b][mb]);   // D[row][token]
           // its vector-ALU shadow: word i / 8 of the next step, slice i % 8
           // its vector-ALU shadow: the next instructions of the next step's dequantisation
           {
@@ -289,7 +482,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 #endif
   // correction: r more channels, operand [A_i] against [R]; every lane runs the same
   // trip count, lanes past the rank contribute zeros on both sides
-  if (U.restore) {
+  if (U.restore && wait_tile_ready(U.flags + MB * mt, U.status)) {
     for (int jj = 0; jj * 32 < U.r; ++jj) {
       const int j0 = jj * 32 + 8 * kq;
       const bool ok = j0 < U.r;
@@ -304,7 +497,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         const int tok = min(tok0 + mb * 16 + n, U.T - 1);
-        u32x4_t rf = *(const u32x4_t*)(U.R16 + (size_t)tok * U.r + j0c);
+        u32x4_t rf = load16_device(U.R16 + (size_t)tok * U.r + j0c);
         if (!ok) rf = u32x4_t{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int b = 0; b < RB; ++b) acc[b][mb] = mfma16<ACT>(af[b], rf, acc[b][mb]);
@@ -368,17 +561,35 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
     for (int j = i; j > 0 && units[order[j]]->d_in > units[order[j - 1]]->d_in; --j) {
       int t = order[j]; order[j] = order[j - 1]; order[j - 1] = t;
     }
-  int n_mods = 0, wg = 0;
+  // projection tiles of the restored units lead the grid
+  int n_proj = 0;
+  for (int oi = 0; oi < n_units; ++oi) {
+    const int ui = order[oi];
+    const glowq_unit& u = *units[ui];
+    PfUnit& pu = a.unit[oi];
+    const int n_mtiles = (u.T + 16 * MB - 1) / (16 * MB);
+    pu.proj_start = -1;
+    if (restore[ui] && u.r > 0) {
+      pu.proj_start = n_proj;
+      n_proj += n_mtiles;
+    }
+  }
+  a.n_proj_wgs = n_proj;
+  a.n_units = n_units;
+  int n_mods = 0, wg = n_proj;
   for (int oi = 0; oi < n_units; ++oi) {
     const int ui = order[oi];
     const glowq_unit& u = *units[ui];
     PfUnit& pu = a.unit[oi];
     pu.X = (const uint16_t*)u.X;
-    pu.R16 = (const uint16_t*)(ws[ui].base + ws[ui].off_r16);
+    pu.B = (const uint16_t*)u.B;
+    pu.R16 = (uint16_t*)(ws[ui].base + ws[ui].off_r16);
+    pu.flags = (uint32_t*)(ws[ui].base + ws[ui].off_counters);
+    pu.status = &((Control*)ws[ui].base)->status;
     pu.T = u.T;
     pu.K = u.d_in;
     pu.r = u.r;
-    pu.restore = restore[ui] ? 1 : 0;
+    pu.restore = (restore[ui] && u.r > 0) ? 1 : 0;
     pu.n_mtiles = (u.T + 16 * MB - 1) / (16 * MB);
     for (int i = 0; i < u.n_modules; ++i) {
       const glowq_module& m = u.modules[i];

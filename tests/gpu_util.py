@@ -85,10 +85,11 @@ class Workspace:
         self.buf = torch.empty(max(self.bytes, 256), dtype=torch.uint8, device="cuda")
         G.glowq_workspace_init(self.buf.data_ptr(), self.buf.numel(), stream())
 
-        self.offsets, self.tblocks, off = [], [], 0
+        self.offsets, self.tblocks, self.tokens, off = [], [], [], 0
         for d in descs:
             self.offsets.append(off)
             self.tblocks.append((d.T + 15) // 16)
+            self.tokens.append(d.T)
             off += G.glowq_workspace_bytes([d])
 
     @property
@@ -98,14 +99,19 @@ class Workspace:
     def control_words(self):
         """Control words of every unit slice as 32-bit words: launch tag (2 words),
         token blocks done, status, padding to 16 words, then one arrival counter per
-        16-token block.  Everything but the tag must be zero between calls."""
+        16-token block (decode) or launch-tag word per token tile (prefill)."""
         torch.cuda.synchronize()
         w = self.buf.view(torch.int32).cpu().numpy()
         return [w[o // 4:o // 4 + 16 + nb].tolist() for o, nb in zip(self.offsets, self.tblocks)]
 
     def assert_idle(self):
-        for cw in self.control_words():
-            assert not any(cw[2:]), cw
+        # words 2, 3: the decode handshake's block count (back to zero) and the status word
+        # (nonzero: a bounded wait expired); the per-block words behind them hold counters
+        # (decode: back to zero) or launch tags (prefill tiles)
+        for cw, T in zip(self.control_words(), self.tokens):
+            assert cw[2] == 0 and cw[3] == 0, cw
+            if T <= 32:
+                assert not any(cw[2:]), cw
 
 
 def run_group(unit: dict, restore: bool = True, out: str = "f32", ldy_pad: int = 0):
