@@ -19,7 +19,23 @@ LIB = os.path.join(LIB_DIR, "libglowq.so")
 SOURCES = ["api.hip", "prepare.hip", "proj.hip", "decode.hip", "prefill.hip"]
 # packed-fp32 instructions are switched off for device code on purpose
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Rpass-analysis=kernel-resource-usage"]
+# Kernels that count their own outstanding memory operations (hand-placed s_waitcnt): a
+# register spill would add loads of the compiler's to that count, so they must have none.
+NO_SPILL = ("k_prefill",)
+
+
+def check_no_spills(src: str, remarks: str) -> None:
+    name = None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].strip()
+        elif "ScratchSize [bytes/lane]:" in line and name:
+            n = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if n and any(k in name for k in NO_SPILL):
+                raise RuntimeError(f"{src}: {name} uses {n} bytes of scratch per lane (register "
+                                   "spills); this kernel must not spill")
 
 
 def build(verbose: bool = False, extra: list | None = None) -> str:
@@ -38,7 +54,9 @@ def build(verbose: bool = False, extra: list | None = None) -> str:
     failed = False
     for src, p in procs:
         out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "is not a recognized feature" not in l)
+        check_no_spills(src, out)
+        out = "\n".join(l for l in out.splitlines()
+                        if "is not a recognized feature" not in l and "remark:" not in l)
         if p.returncode != 0:
             failed = True
             print(f"--- {src} failed ---\n{out}", file=sys.stderr)

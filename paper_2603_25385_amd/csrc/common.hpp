@@ -179,7 +179,7 @@ template <int NW> struct DequantLockstep<ACT_F16, NW> {
   }
 };
 template <int NW> struct DequantLockstep<ACT_BF16, NW> {
-  static constexpr int PH = 23, GS = NW < 2 ? NW : 2;
+  static constexpr int PH = 23, GS = 1;
   static constexpr int N_OPS = NW * PH;
   uint32_t m0[GS], m1[GS];
   float f[GS][2];

@@ -29,10 +29,13 @@ namespace glowq {
 // matrix cores to the other one), bfloat16, whose dequantiser needs more registers, one
 // workgroup of eight waves (32 rows per wave).
 template <int ACT> struct PfShape {
-  static constexpr int WAVES = ACT == ACT_F16 ? 4 : 8;
-  static constexpr int RB = 16 / WAVES;    // 16-row blocks per wave (256 rows per tile)
+  static constexpr int WAVES = 4;
+  // 16-row blocks per wave: 256-row tiles for binary16; bfloat16, whose dequantiser
+  // holds more in registers, takes 192-row tiles to stay within 256 registers per lane
+  static constexpr int RB = ACT == ACT_F16 ? 4 : 3;
+  static constexpr int TILE_BLOCKS = WAVES * RB;   // 16-row blocks per workgroup tile
   static constexpr int OCC = 8 / WAVES;    // workgroups per compute unit
-  static constexpr int XD = ACT == ACT_F16 ? 2 : 4;   // LDS operand reads in flight per wave
+  static constexpr int XD = 2;              // LDS operand reads in flight per wave
 };
 
 // One launch covers up to PF_MAX_UNITS units (PF_MAX_MODS modules in all) that share the
@@ -75,8 +78,19 @@ struct PrefillArgs {
 // vmcnt[5:4] at [15:14].
 __device__ inline void wait_lds_only() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
+// a pointer that is the same in every lane, moved to scalar registers
+template <typename T> __device__ inline T* uniform_ptr(T* p) {
+  const unsigned long long v = (unsigned long long)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (T*)(((unsigned long long)hi << 32) | lo);
+}
+
 __device__ inline void lds_read(u32x4_t& v, uint32_t addr, int imm) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");
+}
+__device__ inline void lds_read32(uint32_t& v, uint32_t addr, int imm) {
+  asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");
 }
 template <int N> __device__ inline void lds_wait(u32x4_t& v) {
   asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
@@ -93,6 +107,7 @@ template <int N> __device__ inline void vm_wait() {
 }
 // ties a value to a point behind a wait, so that nothing that uses it moves above
 __device__ inline void after_wait(u32x4_t& v) { asm volatile("" : "+v"(v)); }
+__device__ inline void after_wait32(uint32_t& v) { asm volatile("" : "+v"(v)); }
 
 // Projection tile of the prefill launch: R[tile] = X[tile] B^T  (paper Eq. 8), MT tokens x
 // all r ranks over the whole contraction, rounded once to the activation type and
@@ -269,6 +284,11 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   constexpr int NBUF = 3;
   constexpr uint32_t STAGE_BYTES = MT * 64 * 2;
   __shared__ __attribute__((aligned(1024))) uint16_t xs[NBUF * MT * 64];
+  // per wave: its RB tile records of the next tile (1 KiB of words each, then 128 bytes
+  // of scale/zero words each), landed here by the same kind of load and taken into
+  // registers once per tile
+  constexpr int WREC = 1024 + 128;
+  __shared__ __attribute__((aligned(1024))) uint8_t wstage[PF_WAVES * RB * WREC];
 
   if ((int)blockIdx.x < a.n_proj_wgs) {
     proj_tile<ACT, MB>(a, xs);
@@ -291,11 +311,11 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 
   // this wave's four 16-row blocks; blocks past the module's last one are computed from
   // a clamped (valid) block and never stored, so that the hot loop carries no branch
-  const int nb0 = nt * 16 + RB * wave;
+  const int nb0 = nt * (PF_WAVES * RB) + RB * wave;
   const uint32_t* wt[RB];
 #pragma unroll
   for (int b = 0; b < RB; ++b)
-    wt[b] = M.rec + (size_t)min(nb0 + b, M.rows16 - 1) * ktiles * RW;
+    wt[b] = uniform_ptr(M.rec + (size_t)min(nb0 + b, M.rows16 - 1) * ktiles * RW);
 
   // X staging, global memory straight into LDS (no registers in between): the wave's
   // load i covers rows XR i + 8 wave + (lane >> 3), one 16-byte chunk per lane, 1 KiB
@@ -303,19 +323,22 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   // slot ^ ((row >> 1) & 7), which is what makes the operand reads conflict free.  Rows
   // past T re-read the last valid token (their columns of D are never stored).
   const int tok0 = mt * MT;
-  const uint16_t* xsrc[XI];
+  // byte offsets of this thread's rows from the tile's first row (below 2^31: MT rows of
+  // at most 2^16 channels)
+  const uint16_t* xtile = uniform_ptr(U.X + (size_t)tok0 * U.K);
+  uint32_t xoff[XI];
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
     const int row = XR * i + (tid >> 3);
     const int chunk = (tid & 7) ^ ((row >> 1) & 7);
-    xsrc[i] = U.X + (size_t)min(tok0 + row, U.T - 1) * U.K + chunk * 8;
+    xoff[i] = (uint32_t)(min(tok0 + row, U.T - 1) - tok0) * (uint32_t)U.K * 2u + chunk * 16;
   }
   const int nstages = 2 * ktiles;
   // stage indices past the end re-read the last stage into a ring slot nobody reads
   auto dma_x = [&](int stage, int slot, int i) {
     const int st = min(stage, nstages - 1);
     __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(xsrc[i] + st * 64),
+        (const __attribute__((address_space(1))) void*)((const char*)(xtile + st * 64) + xoff[i]),
         (__attribute__((address_space(3))) void*)(xs + slot * (MT * 64) + (XR * i + 8 * wave) * 64),
         16, 0, 0);
   };
@@ -336,24 +359,41 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[b][mb] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-  u32x4_t wcur[RB], wnext[RB];
-  uint32_t szcur[RB][2], sznext[RB][2];
-  auto load_w = [&](int kt) {
+  u32x4_t wcur[RB];
+  uint32_t szcur[RB][2];
+  uint8_t* wmine = wstage + wave * (RB * WREC);
+  const uint32_t wmine_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)wmine;
+  // two loads per 16-row block: the 256 words (16 bytes per lane) and the 16 or 32
+  // scale/zero words (4 bytes per lane, low lanes only)
+  auto dma_w = [&](int kt, int b) {
     const int k = min(kt, ktiles - 1);
-#pragma unroll
-    for (int b = 0; b < RB; ++b) {
-      const uint32_t* rec = wt[b] + (size_t)k * RW;
-      wnext[b] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
-      sznext[b][0] = rec[256 + n];
-      sznext[b][1] = G128 ? sznext[b][0] : rec[272 + n];
-    }
+    const uint32_t* rec = wt[b] + (size_t)k * RW;
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(rec + lane * 4),
+        (__attribute__((address_space(3))) void*)(wmine + b * 1024), 16, 0, 0);
+    if (lane < (G128 ? 16 : 32))
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(rec + 256 + lane),
+          (__attribute__((address_space(3))) void*)(wmine + RB * 1024 + b * 128), 4, 0, 0);
   };
+  // LDS -> registers (the loads that filled the stage must have completed: vm_wait);
+  // the results are pending until an lds wait
+  const uint32_t wl16 = wmine_lds + lane * 16, wl4 = wmine_lds + RB * 1024 + n * 4;
   auto take_w = [&]() {
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
-      wcur[b] = wnext[b];
-      szcur[b][0] = sznext[b][0];
-      szcur[b][1] = sznext[b][1];
+      lds_read(wcur[b], wl16, b * 1024);
+      lds_read32(szcur[b][0], wl4, b * 128);
+      if (!G128) lds_read32(szcur[b][1], wl4, b * 128 + 64);
+    }
+  };
+  auto tie_w = [&]() {
+#pragma unroll
+    for (int b = 0; b < RB; ++b) {
+      after_wait(wcur[b]);
+      after_wait32(szcur[b][0]);
+      if (!G128) after_wait32(szcur[b][1]);
+      else szcur[b][1] = szcur[b][0];
     }
   };
   // operand words of step j (32 channels) of the current tile, one per 16-row block
@@ -367,16 +407,19 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 #endif
 #pragma unroll
   for (int i = 0; i < XI; ++i) dma_x(0, 0, i);
-  load_w(0);
+#pragma unroll
+  for (int b = 0; b < RB; ++b) dma_w(0, b);
 #pragma unroll
   for (int i = 0; i < XI; ++i) dma_x(1, 1, i);
+  vm_wait<0>();
   take_w();
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  tie_w();
 #pragma unroll
   for (int b = 0; b < RB; ++b) {
     g[b].set(szcur[b][0]);
     wf[0][b] = dequant_word<ACT>(wcur[b][0], g[b]);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   GLOWQ_STAMP(1);
 
@@ -404,12 +447,10 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
       u32x4_t xq[XD + 1];
 #pragma unroll
       for (int f = 0; f < XD; ++f) lds_read(xq[f], xa[f / MB], (f % MB) * 2048);
-      const int wkt = (PF_EXP & 64) ? 0 : min(kt + 1, ktiles - 1);            // W of the next tile (same)
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int j = 2 * half + jj;
         const int jn = (j + 1) & 3;                        // the step being dequantised
-        if (!(PF_EXP & 2) && j == 3) take_w();
         const bool new_group = G128 ? (j == 3) : ((j & 1) == 1);
         const u32x4_t (&wa)[RB] = wf[j & 1];
         u32x4_t (&wn)[RB] = wf[jn & 1];
@@ -418,7 +459,16 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
           const int mb = i / RB, b = i % RB;
           const int f = MB * jj + mb;
           // memory slots
-          if (b == 0) {
+          if (j == 3 && i == 0) {
+            // the next tile's words: everything this wave has asked for has landed
+            // (its loads of this stage come later), so take them out of the stage,
+            // issue this slot's operand read, and wait for all but that one
+            vm_wait<0>();
+            take_w();
+            lds_read(xq[(f + XD) % (XD + 1)], xa[(f + XD) / MB], ((f + XD) % MB) * 2048);
+            lds_wait<1>(xq[f % (XD + 1)]);
+            tie_w();
+          } else if (b == 0) {
             if (f + XD < 2 * MB) {
               lds_read(xq[(f + XD) % (XD + 1)], xa[(f + XD) / MB], ((f + XD) % MB) * 2048);
               lds_wait<XD>(xq[f % (XD + 1)]);
@@ -431,16 +481,11 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
             }
           }
           // X of stage+2: in the tile's first stage right away, in its second stage
-          // behind the point where the next tile's weights are taken (the compiler
-          // waits there for every load in flight, and these should not be among them)
+          // behind the point where the next tile's weights are taken (which waits for
+          // every load in flight, and these should not be among them)
           if (jj == half && i < XI) dma_x(stage + 2, slot_next2, i);
-          if (!(PF_EXP & 2) && j == 0 && i >= XI && i < XI + RB) {
-            const int bb = i - XI;
-            const uint32_t* rec = wt[bb] + (size_t)wkt * RW;
-            wnext[bb] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
-            sznext[bb][0] = rec[256 + n];
-            sznext[bb][1] = G128 ? sznext[bb][0] : rec[272 + n];
-          }
+          // the next tile's records, into this wave's stage (free since the last take)
+          if (j == 0 && i >= XI && i < XI + RB) dma_w(kt + 1, i - XI);
           // the product
           acc[b][mb] = mfma16<ACT>(wa[b], xq[f % (XD + 1)], acc[b][mb]);   // D[row][token]
           // its vector-ALU shadow: word i / 8 of the next step, slice i % 8
@@ -465,7 +510,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
       // the ones issued after the next stage's loads are the XI loads of the stage after
       // it plus one tile's weight loads (issued in this stage or in the one before).
       {
-        constexpr int YOUNGER = XI + RB * (G128 ? 2 : 3);
+        constexpr int YOUNGER = XI + RB * 2;
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(YOUNGER) : "memory");
       }
       if (!(PF_EXP & 32)) __builtin_amdgcn_s_barrier();
@@ -554,6 +599,8 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
   PrefillArgs a;
   const glowq_unit& u0 = *units[0];
   const int MB = prefill_mb(u0.T);
+  const int tile_blocks = u0.act_dtype == GLOWQ_F16 ? PfShape<ACT_F16>::TILE_BLOCKS
+                                                    : PfShape<ACT_BF16>::TILE_BLOCKS;
   // longest contraction first
   int order[PF_MAX_UNITS];
   for (int i = 0; i < n_units; ++i) order[i] = i;
@@ -603,7 +650,7 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
       pm.rows16 = v.rows16;
       pm.unit = oi;
       pm.wg_start = wg;
-      wg += pu.n_mtiles * ((v.rows16 + 15) / 16);
+      wg += pu.n_mtiles * ((v.rows16 + tile_blocks - 1) / tile_blocks);
     }
   }
   for (int i = n_units; i < PF_MAX_UNITS; ++i) a.unit[i] = a.unit[0];
