@@ -17,18 +17,19 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   w.ctl_bytes = align_up(w.off_counters + (size_t)tblocks * 4, 256);
   // K slices of the projection: decode spreads B over many compute units; prefill
   // already has T / 16 token blocks and only needs enough slices to fill the chip
-  // (a handful of tokens: 8 K parts, one wave per (rank, part), the consumers add the
-  // parts themselves; the parts of one output fill one 64-byte line and consecutive
-  // outputs sit 4 KiB + 64 B apart so that the gather is spread over memory channels)
+  // (a handful of tokens: one wave per (rank, part) and parts of about 2048 channels, so
+  // that a wave has all its loads in flight at once, at most four parts; the consumers
+  // add the parts themselves)
   const bool direct = u.T <= 4;
-  int ksplit = direct ? 8 : is_decode(u.T) ? 32 : (256 + tblocks - 1) / tblocks;
+  int ksplit = direct ? (u.d_in + 2047) / 2048 : is_decode(u.T) ? 32 : (256 + tblocks - 1) / tblocks;
+  if (direct && ksplit > 4) ksplit = 4;
   if (ksplit > 32) ksplit = 32;
   if (ksplit < 1) ksplit = 1;
   int steps = u.d_in / 32;
   int per = (steps + ksplit - 1) / ksplit;
   w.kslice = per * 32;
   w.ksplit = (u.d_in + w.kslice - 1) / w.kslice;
-  w.kstride = direct ? 520 : (w.ksplit + 3) / 4 * 4;
+  w.kstride = (w.ksplit + 3) / 4 * 4;
   w.off_rpart = w.ctl_bytes;
   size_t rpart = (u.r > 0) ? (size_t)w.kstride * u.T * u.r * (direct ? 8 : 4) : 0;
   w.off_r16 = align_up(w.off_rpart + rpart, 256);

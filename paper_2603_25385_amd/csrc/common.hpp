@@ -245,6 +245,30 @@ template <int ACT> __device__ inline uint16_t to_act16(float v) {
   else return __builtin_bit_cast(uint16_t, (__bf16)v);
 }
 
+// LDS reads issued as assembly (the result is pending until an lds_wait that names it)
+__device__ inline void lds_read(u32x4_t& v, uint32_t addr, int imm) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");
+}
+__device__ inline void lds_read32(uint32_t& v, uint32_t addr, int imm) {
+  asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");
+}
+template <int N> __device__ inline void lds_wait(u32x4_t& v) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
+}
+
+// A 16-byte global load whose completion is waited for by hand (vm_wait): the compiler
+// does not see it as a memory operation, so it adds no wait of its own, and the waits
+// it does add for loads it knows never cover these.
+__device__ inline void vm_load(u32x4_t& v, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+}
+template <int N> __device__ inline void vm_wait() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// ties a value to a point behind a wait, so that nothing that uses it moves above
+__device__ inline void after_wait(u32x4_t& v) { asm volatile("" : "+v"(v)); }
+__device__ inline void after_wait32(uint32_t& v) { asm volatile("" : "+v"(v)); }
+
 // Optional stage timestamps (builds with -DGLOWQ_TRACE only): 100 MHz real-time counter
 // values per workgroup and stage, fetched with glowq_debug_trace().
 #ifdef GLOWQ_TRACE

@@ -43,12 +43,12 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArg
   decode_workgroup<ACT, TBK>(a, (int)blockIdx.x - n_prod, lds);
 }
 
-template <int ACT>
+template <int ACT, int TM>
 __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeArgs a, ProjArgs p,
                                                                  int n_prod) {
   __shared__ float lds[DEC_WAVES * 4 * 64];
-  __shared__ __attribute__((aligned(16))) char lds_x[DEC_WAVES * DEC_XWAVE];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_r[DEC_SMALL_T * GLOWQ_MAX_RANK];
+  __shared__ __attribute__((aligned(64))) char lds_x[DEC_WAVES * DecX<TM>::WAVE_BYTES];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_rf[DEC_WAVES * TM * DEC_MAX_PARTS * 64];
   if ((int)blockIdx.x < n_prod) {
     GLOWQ_STAMP(0);
     proj_wave_direct<ACT>(p, (int)blockIdx.x * DEC_WAVES + (int)(threadIdx.x >> 6),
@@ -56,7 +56,7 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeArgs a, P
     GLOWQ_STAMP(1);
     return;
   }
-  decode_workgroup_small<ACT>(a, p, (int)blockIdx.x - n_prod, lds, lds_x, lds_r);
+  decode_workgroup_small<ACT, TM>(a, p, (int)blockIdx.x - n_prod, lds, lds_x, lds_rf);
 }
 
 int fill_decode_args(const glowq_unit& u, const UnitWorkspace& ws, bool restore, DecodeArgs& a) {
@@ -104,8 +104,18 @@ hipError_t launch_decode(const glowq_unit& u, const UnitWorkspace& ws, bool rest
   dim3 grid((unsigned)(n_prod + blocks)), block(DEC_WAVES * 64);
   const bool f16 = (u.act_dtype == GLOWQ_F16);
   if (u.T <= DEC_SMALL_T) {
-    if (f16) k_decode_small<ACT_F16><<<grid, block, 0, st>>>(a, p, n_prod);
-    else k_decode_small<ACT_BF16><<<grid, block, 0, st>>>(a, p, n_prod);
+    // the single-token instance keeps its LDS small enough for four workgroups per
+    // compute unit, so that the whole grid is resident at once
+    if (u.T == 1) {
+      if (f16) k_decode_small<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
+      else k_decode_small<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
+    } else if (u.T == 2) {
+      if (f16) k_decode_small<ACT_F16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
+      else k_decode_small<ACT_BF16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
+    } else {
+      if (f16) k_decode_small<ACT_F16, DEC_SMALL_T><<<grid, block, 0, st>>>(a, p, n_prod);
+      else k_decode_small<ACT_BF16, DEC_SMALL_T><<<grid, block, 0, st>>>(a, p, n_prod);
+    }
   } else if (u.T <= 16) {
     if (f16) k_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
     else k_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod);

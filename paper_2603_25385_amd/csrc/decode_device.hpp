@@ -145,15 +145,33 @@ __device__ inline void decode_stream(const DecodeArgs& a, const ModuleArgs& M, i
 // 128-bit LDS reads (a broadcast for one token).  No workgroup barrier is involved.
 constexpr int DEC_SMALL_T = 4;
 constexpr int DEC_XROW = 1040;                       // bytes per token and chunk (1 KiB + pad)
-constexpr int DEC_XBUF = DEC_SMALL_T * DEC_XROW;     // one chunk buffer
-constexpr int DEC_XWAVE = 2 * DEC_XBUF;              // two chunk buffers per wave
+// one chunk buffer holds TM rows (TM: the most tokens the kernel instance takes; the
+// single-token instance leaves room for four workgroups per compute unit); a wave has two
+__host__ __device__ constexpr int dec_xbuf_bytes(int T) { return (T * DEC_XROW + 63) / 64 * 64; }
 
+
+// X staging and its ordering.  Loads of a wave complete in the order they were issued,
+// so a chunk's X has landed as soon as any load issued after it has: with room for three
+// chunk buffers (TM <= 2) the X of chunk k+1 goes out ahead of the weights of chunk k
+// and needs no wait at all by the time it is read; with two buffers (TM = 4) the X of
+// chunk k goes out ahead of its own weights and is read once their first words are
+// here.  The operand reads are issued as assembly, one tile ahead of their use, behind a
+// register dependency on such a "later" load, so that neither the compiler's scheduler
+// nor its own bookkeeping of LDS-bound loads has a say in the order.
 // `mid` runs once, after the wave's first chunk has been consumed (or right away if the
 // wave has no tiles).
-template <int ACT, bool G128, int NV, class MID>
+template <int TM> struct DecX {
+  static constexpr bool EARLY = TM <= 2;
+  static constexpr int NBUF = EARLY ? 3 : 2;
+  static constexpr int WAVE_BYTES = NBUF * dec_xbuf_bytes(TM);
+};
+
+template <int ACT, bool G128, int NV, int TM, class MID>
 __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs& M, int rb,
                                            int wave, int lane, float4_t (&acc)[1],
                                            char* lds_wave, MID mid) {
+  constexpr bool EARLY = DecX<TM>::EARLY;
+  constexpr int NBUF = DecX<TM>::NBUF;
   const int n = lane & 15, kq = lane >> 4;
   const int ktiles = a.K >> 7;
   const int rw = G128 ? 272 : 288;             // words per tile record
@@ -164,20 +182,26 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
   const int lc = lane >> 4, lp = lane & 15;
   const uint16_t* xsrc = a.X + 128 * wave + 8 * lp;
   // reading: lane (i, kq) -> token min(i, T - 1), piece 4 j + kq
-  const char* xrd = lds_wave + min(n, a.T - 1) * DEC_XROW + kq * 16;
+  constexpr int xbuf = dec_xbuf_bytes(TM);
+  const uint32_t xrd = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave +
+                       (uint32_t)(min(n, a.T - 1) * DEC_XROW + kq * 16);
 
   u32x4_t wA[DEC_CHUNK], wB[DEC_CHUNK];
   uint32_t sA[DEC_CHUNK][2], sB[DEC_CHUNK][2];
 
-  auto load_chunk = [&](int t0, int buf, u32x4_t (&w)[DEC_CHUNK], uint32_t (&s)[DEC_CHUNK][2]) {
-    // X first: loads return in order, and a tile needs its X before anything else
-    const int tx = min(t0 + lc, ntw - 1);
+  auto load_x = [&](int idx) {   // X of chunk idx -> ring buffer idx % NBUF
+    const int tx = min(idx * DEC_CHUNK + lc, ntw - 1);
     const uint16_t* src = xsrc + (size_t)tx * (128 * DEC_WAVES);
+    char* dst = lds_wave + (idx % NBUF) * xbuf;
     for (int tok = 0; tok < a.T; ++tok)
       __builtin_amdgcn_global_load_lds(
           (const __attribute__((address_space(1))) void*)(src + (size_t)tok * a.K),
-          (__attribute__((address_space(3))) void*)(lds_wave + buf * DEC_XBUF + tok * DEC_XROW),
-          16, 0, 0);
+          (__attribute__((address_space(3))) void*)(dst + tok * DEC_XROW), 16, 0, 0);
+  };
+  auto load_chunk = [&](int idx, u32x4_t (&w)[DEC_CHUNK], uint32_t (&s)[DEC_CHUNK][2]) {
+    // X first: a tile needs its X before anything else
+    load_x(EARLY ? idx + 1 : idx);
+    const int t0 = idx * DEC_CHUNK;
 #pragma unroll
     for (int c = 0; c < DEC_CHUNK; ++c) {
       const int t = min(t0 + c, ntw - 1);          // clamped: a duplicate tile is never used
@@ -188,26 +212,43 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
       else s[c][1] = __builtin_nontemporal_load(rec + 272 + n);
     }
   };
-  auto run_chunk = [&](int t0, int buf, const u32x4_t (&w)[DEC_CHUNK],
-                       const uint32_t (&s)[DEC_CHUNK][2]) {
+  uint32_t landed = 0;   // a word of a load issued after the X that is read next
+  auto run_chunk = [&](int idx, const u32x4_t (&w)[DEC_CHUNK], const uint32_t (&s)[DEC_CHUNK][2]) {
+    const int t0 = idx * DEC_CHUNK;
+    const uint32_t w00 = w[0][0];
+    if (!EARLY || idx == 0) landed = w00;
+    uint32_t xc = xrd + (uint32_t)((idx % NBUF) * xbuf);
+    asm volatile("" : "+v"(xc) : "v"(landed));
+    u32x4_t xf[2][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) lds_read(xf[0][j], xc, 64 * j);
 #pragma unroll
     for (int c = 0; c < DEC_CHUNK; ++c) {
-      if (t0 + c < ntw) {
-        const char* xc = xrd + buf * DEC_XBUF + c * 256;
-        decode_tile<ACT, 1, G128, NV>(w[c], s[c][0], s[c][1], [&](int, int j) {
-          return *(const u32x4_t*)(xc + 64 * j); }, acc);
+      if (c + 1 < DEC_CHUNK) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) lds_read(xf[(c + 1) & 1][j], xc, (c + 1) * 256 + 64 * j);
+        asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(xf[c & 1][0]), "+v"(xf[c & 1][1]), "+v"(xf[c & 1][2]),
+                     "+v"(xf[c & 1][3]) : : "memory");
+      } else {
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xf[c & 1][0]), "+v"(xf[c & 1][1]), "+v"(xf[c & 1][2]),
+                     "+v"(xf[c & 1][3]) : : "memory");
       }
+      if (t0 + c < ntw)
+        decode_tile<ACT, 1, G128, NV>(w[c], s[c][0], s[c][1], [&](int, int j) { return xf[c & 1][j]; }, acc);
     }
+    landed = w00;   // the next chunk's X went out before this chunk's weights (EARLY)
   };
 
-  load_chunk(0, 0, wA, sA);
-  for (int t0 = 0; t0 < ntw; t0 += 2 * DEC_CHUNK) {
-    if (t0 + DEC_CHUNK < ntw) load_chunk(t0 + DEC_CHUNK, 1, wB, sB);
-    run_chunk(t0, 0, wA, sA);
-    if (t0 == 0) mid();
-    if (t0 + DEC_CHUNK < ntw) {
-      if (t0 + 2 * DEC_CHUNK < ntw) load_chunk(t0 + 2 * DEC_CHUNK, 0, wA, sA);
-      run_chunk(t0 + DEC_CHUNK, 1, wB, sB);
+  const int nchunks = (ntw + DEC_CHUNK - 1) / DEC_CHUNK;
+  if (EARLY) load_x(0);
+  load_chunk(0, wA, sA);
+  for (int idx = 0; idx < nchunks; idx += 2) {
+    if (idx + 1 < nchunks) load_chunk(idx + 1, wB, sB);
+    run_chunk(idx, wA, sA);
+    if (idx == 0) mid();
+    if (idx + 1 < nchunks) {
+      if (idx + 2 < nchunks) load_chunk(idx + 2, wA, sA);
+      run_chunk(idx + 1, wB, sB);
     }
   }
 }
@@ -249,111 +290,119 @@ __device__ inline u32x4_t load_r16(const uint16_t* p) {
 }
 
 // Direct mode (T <= 4): every (rank, K part) wave of the projection leaves, per token,
-// one 8-byte slot {partial sum, low word of its launch tag}.  The workgroup loads all
-// slots of its unit (all of a thread's loads are in flight together), checks that every
-// slot carries THIS launch's tag, adds the parts in part order and leaves R, rounded to
-// the activation type, in LDS.  All threads of the workgroup take part.
+// one 8-byte slot {partial sum, low word of its launch tag}; slot of (t, part, j) is
+// slots[(t ksplit + part) r + j], so the eight ranks a lane needs for its matrix operand
+// are one 64-byte line per part.  Each wave fetches, for its own correction step only,
+// the slots of its lanes (lane (token n, kq): ranks 32 wave + 8 kq .. + 8), checks that
+// every one carries THIS launch's tag, adds the parts in part order and rounds to the
+// activation type: no LDS, no workgroup barrier.
 //
-// The first attempt uses ordinary (L2-cached) loads and is issued in the middle of the
-// weight stream, so its latency is hidden: the projection waves publish within the first
-// couple of microseconds, long before any weight chunk has been consumed, and one
-// workgroup per XCD pays the miss.  A slot read too early shows an older tag; then, and
-// only then, the retries use device-scope loads, which cannot be served from a stale
-// cached line.  The wait is bounded (the projection waves wait for nothing, so it cannot
-// expire); if it did, ctl->status is set and the correction is left out rather than hang.
-struct GatherR {
-  unsigned long long v[8];
-  const unsigned long long* q;
-  int outputs, groups, g, e, z0, z1;
-  bool active, issued;
+// The first attempt uses ordinary (L2-cached) loads and is issued during the weight
+// stream, so its latency is hidden: the projection waves publish within the first couple
+// of microseconds.  A slot read too early shows an older tag; then, and only then, the
+// retries use device-scope loads, which cannot be served from a stale cached line.  The
+// wait is bounded (the projection waves wait for nothing, so it cannot expire); if it
+// did, ctl->status is set and the correction is left out rather than hang.
+constexpr int DEC_MAX_PARTS = 4;   // K parts of the direct projection (see plan_unit_workspace)
+struct RFetch {
+  u32x4_t v[DEC_MAX_PARTS][4];     // per part: 8 slots = 64 bytes
+  const unsigned long long* q;     // this lane's first slot of part 0
+  int part_stride;                 // slots between parts
+  bool on;                         // this lane contributes ranks of a real token
 };
 
-__device__ inline void gather_r_plan(const DecodeArgs& a, const ProjArgs& p, GatherR& st) {
-  st.outputs = a.T * a.r;                               // <= 512
-  st.groups = 1;
-  while (st.groups * 2 * st.outputs <= DEC_WAVES * 64 && st.groups * 2 <= p.ksplit)
-    st.groups *= 2;
-  st.issued = false;
+__device__ inline void r_fetch_plan(const DecodeArgs& a, const ProjArgs& p, int j0c, bool lane_on,
+                                    int lane, RFetch& f) {
+  const int n = lane & 15;
+  f.on = lane_on && n < a.T;
+  f.part_stride = a.r;
+  f.q = (const unsigned long long*)p.Rpart + (size_t)(f.on ? n : 0) * p.ksplit * a.r + j0c;
 }
-
-__device__ inline void gather_r_slice(const ProjArgs& p, GatherR& st, int idx) {
-  const int spg = (p.ksplit + st.groups - 1) / st.groups;   // parts per group
-  st.g = idx / st.outputs;
-  st.e = idx - st.g * st.outputs;
-  st.active = st.g < st.groups;
-  st.q = (const unsigned long long*)p.Rpart + (size_t)(st.active ? st.e : 0) * p.kstride;
-  st.z0 = st.active ? st.g * spg : 0;
-  st.z1 = st.active ? min(p.ksplit, st.z0 + spg) : 0;
+// First attempt: the wave's 32 ranks of every (token, part), 256 bytes each, go straight
+// into its rows of LDS (a load the compiler accounts for exactly, issued in the middle of
+// the weight stream, no registers held).  Lanes past rank r load nothing.
+__device__ inline void r_fetch_issue(const DecodeArgs& a, const ProjArgs& p, int wave, int lane,
+                                     uint32_t* lds_rf_wave) {
+  const bool in = 32 * wave + (lane >> 1) < a.r;
+  const uint32_t* src = (const uint32_t*)p.Rpart + (size_t)64 * wave + lane;
+  for (int t = 0; t < a.T; ++t)
+    for (int part = 0; part < p.ksplit; ++part)
+      if (in)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(src + (size_t)(t * p.ksplit + part) * a.r * 2),
+            (__attribute__((address_space(3))) void*)(lds_rf_wave + (t * DEC_MAX_PARTS + part) * 64),
+            4, 0, 0);
 }
-
-// issue the first (cached) attempt for this thread's first eight parts
-__device__ inline void gather_r_issue(const DecodeArgs& a, const ProjArgs& p, GatherR& st) {
-  if (!a.restore) return;
-  gather_r_slice(p, st, threadIdx.x);
+__device__ inline void r_fetch_take(const DecodeArgs& a, const ProjArgs& p, int lane,
+                                    const uint32_t* lds_rf_wave, RFetch& f) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the loads above have landed
+  const int n = lane & 15, kq = lane >> 4;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    st.v[i] = 0ull;
-    if (st.z0 < st.z1)
-      st.v[i] = __hip_atomic_load(st.q + min(st.z0 + i, st.z1 - 1), __ATOMIC_RELAXED,
-                                  __HIP_MEMORY_SCOPE_WORKGROUP);
-  }
-  st.issued = true;
+  for (int part = 0; part < DEC_MAX_PARTS; ++part)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f.v[part][i] = u32x4_t{0u, 0u, 0u, 0u};
+#if defined(GLOWQ_FORCE_RETRY) && GLOWQ_FORCE_RETRY == 2
+      if (false)
+#else
+      if (f.on && part < p.ksplit)
+#endif
+        f.v[part][i] = *(const u32x4_t*)(lds_rf_wave + (n * DEC_MAX_PARTS + part) * 64 + 16 * kq + 4 * i);
+    }
 }
-
-// lds_f: 512 floats of scratch; lds_r: T * r 16-bit values
+// returns false if the bounded wait expired (status recorded); rf: the lane's operand
 template <int ACT>
-__device__ inline bool gather_r_finish(const DecodeArgs& a, const ProjArgs& p, GatherR& st,
-                                       float* lds_f, uint16_t* lds_r) {
-  const int tid = threadIdx.x;
+__device__ inline bool r_fetch_finish(const ProjArgs& p, RFetch& f, u32x4_t& rf) {
   const uint32_t tag = (uint32_t)(launch_tag() & 0xffffffffull);
-  const int passes = (st.outputs + DEC_WAVES * 64 - 1) / (DEC_WAVES * 64);   // 2 only if groups == 1
-  for (int pass = 0; pass < passes; ++pass) {
-    gather_r_slice(p, st, tid + pass * DEC_WAVES * 64);
-    const bool use_prefetch = st.issued && pass == 0;
-    float s = 0.f;
-    bool done = false;
-    for (int spin = 0; spin < (1 << 14); ++spin) {
-      bool ok = true;
-      s = 0.f;
-      for (int zb = st.z0; zb < st.z1; zb += 8) {
-        unsigned long long v[8];
+  float s[8];
+  bool done = false;
+  for (int spin = 0; spin < (1 << 14); ++spin) {
+    bool ok = true;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const unsigned long long* qi = st.q + min(zb + i, st.z1 - 1);
-          if (spin == 0 && use_prefetch && zb == st.z0) v[i] = st.v[i];
-          else if (spin == 0)
-            v[i] = __hip_atomic_load(qi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          else v[i] = __hip_atomic_load(qi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+    for (int e = 0; e < 8; ++e) s[e] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          if (zb + i < st.z1) {
-            ok = ok && ((uint32_t)(v[i] >> 32) == tag);
-            s += __builtin_bit_cast(float, (uint32_t)v[i]);
-          }
+    for (int part = 0; part < DEC_MAX_PARTS; ++part) {
+      if (part < p.ksplit) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const u32x4_t q = f.v[part][i];
+          const uint32_t v0 = q[0], t0 = q[1], v1 = q[2], t1 = q[3];   // (bit_cast of a vector
+          ok = ok && (t0 == tag) && (t1 == tag);                       //  element reads element 0)
+          s[2 * i] += __builtin_bit_cast(float, v0);
+          s[2 * i + 1] += __builtin_bit_cast(float, v1);
         }
       }
-      if (__syncthreads_and(ok ? 1 : 0)) { done = true; break; }
-      __builtin_amdgcn_s_sleep(32);
     }
-    if (!done) {
-      if (tid == 0) atomicOr(&p.ctl->status, 1u);
-      return false;
+    if (!f.on) ok = true;
+    if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) {
+      done = true;
+#ifdef GLOWQ_TRACE
+      if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace[blockIdx.x][5] = (unsigned long long)(spin + 1);
+#endif
+      break;
     }
-    if (st.active) {
-      if (st.groups == 1) lds_r[st.e] = to_act16<ACT>(s);
-      else lds_f[st.g * st.outputs + st.e] = s;
+    __builtin_amdgcn_s_sleep(32);
+    // again, past every cache that may hold a stale copy
+#pragma unroll
+    for (int part = 0; part < DEC_MAX_PARTS; ++part) {
+      if (f.on && part < p.ksplit) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned long long* q = f.q + (size_t)part * f.part_stride + 2 * i;
+          const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          f.v[part][i] = u32x4_t{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+        }
+      }
     }
   }
-  __syncthreads();
-  if (st.groups > 1) {
-    if (tid < st.outputs) {
-      float s = 0.f;
-      for (int g = 0; g < st.groups; ++g) s += lds_f[g * st.outputs + tid];
-      lds_r[tid] = to_act16<ACT>(s);
-    }
-    __syncthreads();
+  if (!done) {
+    if ((threadIdx.x & 63) == 0) atomicOr(&p.ctl->status, 1u);
+    return false;
   }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    rf[i] = f.on ? ((uint32_t)to_act16<ACT>(s[2 * i]) | ((uint32_t)to_act16<ACT>(s[2 * i + 1]) << 16)) : 0u;
   return true;
 }
 
@@ -450,11 +499,11 @@ __device__ inline void decode_workgroup(const DecodeArgs& a, int blk, float* lds
   decode_reduce_store<ACT, TBK>(a, M, rb, wave, lane, acc, lds);
 }
 
-// T <= 4.  lds: DEC_WAVES * 256 floats for the fold; lds_x: DEC_WAVES * DEC_XWAVE bytes;
-// lds_r: DEC_SMALL_T * GLOWQ_MAX_RANK 16-bit values.
-template <int ACT>
+// T <= 4.  lds: DEC_WAVES * 256 floats for the fold; lds_x: DEC_WAVES * DecX<TM>::WAVE_BYTES;
+// lds_rf: DEC_WAVES * TM * DEC_MAX_PARTS rows of 64 words.
+template <int ACT, int TM>
 __device__ inline void decode_workgroup_small(const DecodeArgs& a, const ProjArgs& p, int blk,
-                                              float* lds, char* lds_x, uint16_t* lds_r) {
+                                              float* lds, char* lds_x, uint32_t* lds_rf) {
   const ModuleArgs& M = find_module(a, blk);
   const int rb = blk - M.blk_start;
   const int lane = threadIdx.x & 63;
@@ -470,26 +519,27 @@ __device__ inline void decode_workgroup_small(const DecodeArgs& a, const ProjArg
   }
 #endif
   const CorrFrag cf = correction_prefetch(a, M, rb, wave, lane);
-  GatherR gr;
-  gather_r_plan(a, p, gr);
-  auto mid = [&]() { gather_r_issue(a, p, gr); };
-  char* lds_wave = lds_x + wave * DEC_XWAVE;
+  RFetch rfetch;
+  r_fetch_plan(a, p, cf.j0c, a.restore && cf.active && cf.ok, lane, rfetch);
+  uint32_t* lds_rf_wave = lds_rf + wave * (TM * DEC_MAX_PARTS * 64);
+#if defined(GLOWQ_FORCE_RETRY) && GLOWQ_FORCE_RETRY == 1
+  auto mid = [&]() {};
+#else
+  auto mid = [&]() { if (a.restore && cf.active) r_fetch_issue(a, p, wave, lane, lds_rf_wave); };
+#endif
+  char* lds_wave = lds_x + wave * DecX<TM>::WAVE_BYTES;
   if (a.G == 128) {
-    if (a.T == 1) decode_stream_small<ACT, true, 1>(a, M, rb, wave, lane, acc, lds_wave, mid);
-    else decode_stream_small<ACT, true, 4>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    if constexpr (TM == 1) decode_stream_small<ACT, true, 1, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    else decode_stream_small<ACT, true, 4, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);
   } else {
-    decode_stream_small<ACT, false, 4>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    decode_stream_small<ACT, false, 4, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);
   }
   GLOWQ_STAMP(1);
-  if (a.restore) {
-    const bool got = gather_r_finish<ACT>(a, p, gr, lds, lds_r);
+  if (a.restore && cf.active) {
+    u32x4_t rf;
+    r_fetch_take(a, p, lane, lds_rf_wave, rfetch);
+    if (r_fetch_finish<ACT>(p, rfetch, rf)) acc[0] = mfma16<ACT>(rf, cf.af, acc[0]);
     GLOWQ_STAMP(3);
-    if (got && cf.active) {
-      const int tok = min(lane & 15, a.T - 1);
-      u32x4_t rf = *(const u32x4_t*)(lds_r + tok * a.r + cf.j0c);
-      if (!cf.ok) rf = u32x4_t{0u, 0u, 0u, 0u};
-      acc[0] = mfma16<ACT>(rf, cf.af, acc[0]);
-    }
   }
   decode_reduce_store<ACT, 1>(a, M, rb, wave, lane, acc, lds);
   GLOWQ_STAMP(4);

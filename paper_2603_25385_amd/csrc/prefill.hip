@@ -86,29 +86,6 @@ template <typename T> __device__ inline T* uniform_ptr(T* p) {
   return (T*)(((unsigned long long)hi << 32) | lo);
 }
 
-__device__ inline void lds_read(u32x4_t& v, uint32_t addr, int imm) {
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");
-}
-__device__ inline void lds_read32(uint32_t& v, uint32_t addr, int imm) {
-  asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");
-}
-template <int N> __device__ inline void lds_wait(u32x4_t& v) {
-  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(v) : "n"(N) : "memory");
-}
-
-// A 16-byte global load whose completion is waited for by hand (vm_wait): the compiler
-// does not see it as a memory operation, so it adds no wait of its own, and the waits
-// it does add for loads it knows never cover these.
-__device__ inline void vm_load(u32x4_t& v, const void* p) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
-}
-template <int N> __device__ inline void vm_wait() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-// ties a value to a point behind a wait, so that nothing that uses it moves above
-__device__ inline void after_wait(u32x4_t& v) { asm volatile("" : "+v"(v)); }
-__device__ inline void after_wait32(uint32_t& v) { asm volatile("" : "+v"(v)); }
-
 // Projection tile of the prefill launch: R[tile] = X[tile] B^T  (paper Eq. 8), MT tokens x
 // all r ranks over the whole contraction, rounded once to the activation type and
 // stored in the workspace; then the tile's flag is set to this launch's tag.  These

@@ -127,12 +127,12 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
 
 // Projection for a handful of tokens (T <= 4), built for the shortest dependency chain:
 // one WAVE computes, for one rank j and one of `ksplit` K parts, the T partial sums
-// sum_k X[t][k] B[j][k] -- a contiguous read of B, fp32 accumulation, a butterfly
-// reduction -- and publishes each as ONE 8-byte device-scope store {fp32 bits, low word
-// of the launch tag}.  A slot therefore validates itself: no fence, no flag, no ordering
-// between stores, and the wave never waits for anything.  The consumers add the parts
-// (gather_r_direct).  Slot of (t, j, part): slots[(t r + j) kstride + part]; kstride
-// spreads the outputs over memory channels.
+// sum_k X[t][k] B[j][k] -- contiguous reads of B and X, all of a batch in flight
+// together, fp32 accumulation, a butterfly reduction -- and publishes each as ONE 8-byte
+// device-scope store {fp32 bits, low word of the launch tag}.  A slot therefore
+// validates itself: no fence, no flag, no ordering between stores, and the wave never
+// waits for anything.  The consumers add the parts (r_fetch_finish).  Slot of
+// (t, part, j): slots[(t ksplit + part) r + j].
 template <int ACT>
 __device__ inline void proj_wave_direct(const ProjArgs& a, int wave_global, int lane) {
   const int rank = wave_global % a.r, part = wave_global / a.r;   // a workgroup shares a part
@@ -141,29 +141,43 @@ __device__ inline void proj_wave_direct(const ProjArgs& a, int wave_global, int 
   const int k_end = min(a.K, k_begin + a.kslice);
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   const uint16_t* brow = a.B + (size_t)rank * a.K;
-  for (int k = k_begin + 8 * lane; k < k_end; k += 512) {
-    const u32x4_t bv = *(const u32x4_t*)(brow + k);
+  constexpr int BATCH = 4;   // 512-channel steps whose loads are in flight together
+  for (int k0 = k_begin + 8 * lane; k0 < k_end; k0 += 512 * BATCH) {
+    u32x4_t bv[BATCH], xv[4][BATCH];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      if (t < a.T) {
-        const u32x4_t xv = *(const u32x4_t*)(a.X + (size_t)t * a.K + k);
+    for (int it = 0; it < BATCH; ++it) {
+      const int k = k0 + 512 * it;
+      const bool in = k < k_end;
+      const int kc = in ? k : k0;                     // clamped: loaded again, not used
+      bv[it] = *(const u32x4_t*)(brow + kc);
+      if (!in) bv[it] = u32x4_t{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const uint32_t bw = bv[i], xw = xv[i];
-          float b0, b1, x0, x1;
-          if constexpr (ACT == ACT_F16) {
-            b0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(bw & 0xffffu));
-            b1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(bw >> 16));
-            x0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(xw & 0xffffu));
-            x1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(xw >> 16));
-          } else {
-            b0 = __builtin_bit_cast(float, bw << 16);
-            b1 = __builtin_bit_cast(float, bw & 0xffff0000u);
-            x0 = __builtin_bit_cast(float, xw << 16);
-            x1 = __builtin_bit_cast(float, xw & 0xffff0000u);
+      for (int t = 0; t < 4; ++t)
+        if (t < a.T) xv[t][it] = *(const u32x4_t*)(a.X + (size_t)t * a.K + kc);
+    }
+#pragma unroll
+    for (int it = 0; it < BATCH; ++it) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        if (t < a.T) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uint32_t bw = bv[it][i], xw = xv[t][it][i];
+            float b0, b1, x0, x1;
+            if constexpr (ACT == ACT_F16) {
+              b0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(bw & 0xffffu));
+              b1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(bw >> 16));
+              x0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(xw & 0xffffu));
+              x1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(xw >> 16));
+            } else {
+              b0 = __builtin_bit_cast(float, bw << 16);
+              b1 = __builtin_bit_cast(float, bw & 0xffff0000u);
+              x0 = __builtin_bit_cast(float, xw << 16);
+              x1 = __builtin_bit_cast(float, xw & 0xffff0000u);
+            }
+            acc[t] = __builtin_fmaf(b0, x0, acc[t]);
+            acc[t] = __builtin_fmaf(b1, x1, acc[t]);
           }
-          acc[t] = __builtin_fmaf(b0, x0, acc[t]);
-          acc[t] = __builtin_fmaf(b1, x1, acc[t]);
         }
       }
     }
@@ -177,7 +191,7 @@ __device__ inline void proj_wave_direct(const ProjArgs& a, int wave_global, int 
 #pragma unroll
       for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
       if (lane == 0)
-        __hip_atomic_store(&slots[((size_t)t * a.r + rank) * a.kstride + part],
+        __hip_atomic_store(&slots[((size_t)t * a.ksplit + part) * a.r + rank],
                            tag_hi | (unsigned long long)__builtin_bit_cast(uint32_t, s),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
