@@ -91,12 +91,22 @@ static glowq_status forward_all(const glowq_unit* units, int n_units, const uint
   while (i < n_units) {
     const glowq_unit& u = units[i];
     if (is_decode(u.T)) {
-      UnitWorkspace ws = plan_unit_workspace(u, workspace + off);
-      const bool corr = (!mask || mask[i]) && u.r > 0;
-      hipError_t e = launch_decode(u, ws, corr, st);
+      // consecutive few-token units of one kind share a launch
+      const glowq_unit* dbatch[8];
+      UnitWorkspace dws[8];
+      bool dcorr[8];
+      int nd = 0;
+      while (i < n_units && nd < decode_max_batch() && nd < 8 && is_decode(units[i].T) &&
+             (nd == 0 || decode_batch_compatible(*dbatch[0], units[i]))) {
+        dbatch[nd] = &units[i];
+        dws[nd] = plan_unit_workspace(units[i], workspace + off);
+        dcorr[nd] = (!mask || mask[i]) && units[i].r > 0;
+        off += dws[nd].bytes;
+        ++nd;
+        ++i;
+      }
+      hipError_t e = launch_decode_multi(dbatch, dws, dcorr, nd, st);
       if (e != hipSuccess) return hip_status(e);
-      off += ws.bytes;
-      ++i;
       continue;
     }
     const glowq_unit* batch[8];

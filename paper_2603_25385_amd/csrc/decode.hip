@@ -43,20 +43,37 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArg
   decode_workgroup<ACT, TBK>(a, (int)blockIdx.x - n_prod, lds);
 }
 
+// Up to DEC_MAX_BATCH units of the same kind (activation type, token class) in one
+// launch: the grid is the concatenation of the units' [projection waves][row blocks].
+constexpr int DEC_MAX_BATCH = 8;
+struct DecodeBatch {
+  DecodeArgs a[DEC_MAX_BATCH];
+  ProjArgs p[DEC_MAX_BATCH];
+  int n_prod[DEC_MAX_BATCH];
+  int wg_start[DEC_MAX_BATCH];
+  int n;
+};
+
 template <int ACT, int TM>
-__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeArgs a, ProjArgs p,
-                                                                 int n_prod) {
+__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeBatch b) {
   __shared__ float lds[DEC_WAVES * 4 * 64];
   __shared__ __attribute__((aligned(64))) char lds_x[DEC_WAVES * DecX<TM>::WAVE_BYTES];
   __shared__ __attribute__((aligned(16))) uint32_t lds_rf[DEC_WAVES * TM * DEC_MAX_PARTS * 64];
-  if ((int)blockIdx.x < n_prod) {
+  int ui = 0;
+#pragma unroll
+  for (int i = 1; i < DEC_MAX_BATCH; ++i)
+    if (i < b.n && (int)blockIdx.x >= b.wg_start[i]) ui = i;
+  const DecodeArgs& a = b.a[ui];
+  const ProjArgs& p = b.p[ui];
+  const int local = (int)blockIdx.x - b.wg_start[ui];
+  const int n_prod = b.n_prod[ui];
+  if (local < n_prod) {
     GLOWQ_STAMP(0);
-    proj_wave_direct<ACT>(p, (int)blockIdx.x * DEC_WAVES + (int)(threadIdx.x >> 6),
-                          (int)(threadIdx.x & 63));
+    proj_wave_direct<ACT>(p, local * DEC_WAVES + (int)(threadIdx.x >> 6), (int)(threadIdx.x & 63));
     GLOWQ_STAMP(1);
     return;
   }
-  decode_workgroup_small<ACT, TM>(a, p, (int)blockIdx.x - n_prod, lds, lds_x, lds_rf);
+  decode_workgroup_small<ACT, TM>(a, p, local - n_prod, lds, lds_x, lds_rf);
 }
 
 int fill_decode_args(const glowq_unit& u, const UnitWorkspace& ws, bool restore, DecodeArgs& a) {
@@ -86,44 +103,90 @@ int fill_decode_args(const glowq_unit& u, const UnitWorkspace& ws, bool restore,
   return blk;
 }
 
-hipError_t launch_decode(const glowq_unit& u, const UnitWorkspace& ws, bool restore,
-                         hipStream_t st) {
-  DecodeArgs a;
-  const int blocks = fill_decode_args(u, ws, restore, a);
-  ProjArgs p = {};
-  int n_prod = 0;
-  a.ctl = (Control*)ws.base;
-  a.in_launch_proj = 0;
-  if (restore) {
-    p = make_proj_args(u, ws, nullptr, true);
-    const int tblocks = (u.T + 15) / 16;
-    if (u.T <= DEC_SMALL_T) n_prod = (u.r * ws.ksplit + DEC_WAVES - 1) / DEC_WAVES;   // one wave per (rank, part)
-    else n_prod = tblocks * ws.ksplit;
-    a.in_launch_proj = 1;
-  }
-  dim3 grid((unsigned)(n_prod + blocks)), block(DEC_WAVES * 64);
-  const bool f16 = (u.act_dtype == GLOWQ_F16);
-  if (u.T <= DEC_SMALL_T) {
-    // the single-token instance keeps its LDS small enough for four workgroups per
-    // compute unit, so that the whole grid is resident at once
-    if (u.T == 1) {
-      if (f16) k_decode_small<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
-      else k_decode_small<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
-    } else if (u.T == 2) {
-      if (f16) k_decode_small<ACT_F16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
-      else k_decode_small<ACT_BF16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
-    } else {
-      if (f16) k_decode_small<ACT_F16, DEC_SMALL_T><<<grid, block, 0, st>>>(a, p, n_prod);
-      else k_decode_small<ACT_BF16, DEC_SMALL_T><<<grid, block, 0, st>>>(a, p, n_prod);
+static int decode_small_class(int T) { return T == 1 ? 1 : T == 2 ? 2 : DEC_SMALL_T; }
+
+bool decode_batch_compatible(const glowq_unit& a, const glowq_unit& b) {
+  return a.T <= DEC_SMALL_T && b.T <= DEC_SMALL_T && a.act_dtype == b.act_dtype &&
+         decode_small_class(a.T) == decode_small_class(b.T);
+}
+int decode_max_batch() { return DEC_MAX_BATCH; }
+
+// units[i] uses workspace slice ws[i]; all of them pass decode_batch_compatible with
+// units[0] (or n == 1, any decode-sized unit).
+hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspace* ws,
+                               const bool* restore, int n, hipStream_t st) {
+  const glowq_unit& u0 = *units[0];
+  const bool f16 = (u0.act_dtype == GLOWQ_F16);
+  dim3 block(DEC_WAVES * 64);
+  if (u0.T <= DEC_SMALL_T) {
+    DecodeBatch b;
+    int wg = 0;
+    for (int i = 0; i < n; ++i) {
+      const glowq_unit& u = *units[i];
+      const int blocks = fill_decode_args(u, ws[i], restore[i], b.a[i]);
+      b.p[i] = ProjArgs{};
+      b.n_prod[i] = 0;
+      b.a[i].ctl = (Control*)ws[i].base;
+      b.a[i].in_launch_proj = 0;
+      if (restore[i]) {
+        b.p[i] = make_proj_args(u, ws[i], nullptr, true);
+        b.n_prod[i] = (u.r * ws[i].ksplit + DEC_WAVES - 1) / DEC_WAVES;   // one wave per (rank, part)
+        b.a[i].in_launch_proj = 1;
+      }
+      b.wg_start[i] = wg;
+      wg += b.n_prod[i] + blocks;
     }
-  } else if (u.T <= 16) {
-    if (f16) k_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
-    else k_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
-  } else {
-    if (f16) k_decode<ACT_F16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
-    else k_decode<ACT_BF16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
+    for (int i = n; i < DEC_MAX_BATCH; ++i) {
+      b.a[i] = b.a[0];
+      b.p[i] = b.p[0];
+      b.n_prod[i] = 0;
+      b.wg_start[i] = wg;
+    }
+    b.n = n;
+    dim3 grid((unsigned)wg);
+    // the one- and two-token instances keep their LDS small enough for four workgroups
+    // per compute unit, so that a unit's whole grid is resident at once
+    switch (decode_small_class(u0.T)) {
+      case 1:
+        if (f16) k_decode_small<ACT_F16, 1><<<grid, block, 0, st>>>(b);
+        else k_decode_small<ACT_BF16, 1><<<grid, block, 0, st>>>(b);
+        break;
+      case 2:
+        if (f16) k_decode_small<ACT_F16, 2><<<grid, block, 0, st>>>(b);
+        else k_decode_small<ACT_BF16, 2><<<grid, block, 0, st>>>(b);
+        break;
+      default:
+        if (f16) k_decode_small<ACT_F16, DEC_SMALL_T><<<grid, block, 0, st>>>(b);
+        else k_decode_small<ACT_BF16, DEC_SMALL_T><<<grid, block, 0, st>>>(b);
+    }
+    return hipGetLastError();
   }
-  return hipGetLastError();
+  // 4 < T <= 32: one unit per launch
+  for (int i = 0; i < n; ++i) {
+    const glowq_unit& u = *units[i];
+    DecodeArgs a;
+    const int blocks = fill_decode_args(u, ws[i], restore[i], a);
+    ProjArgs p = {};
+    int n_prod = 0;
+    a.ctl = (Control*)ws[i].base;
+    a.in_launch_proj = 0;
+    if (restore[i]) {
+      p = make_proj_args(u, ws[i], nullptr, true);
+      n_prod = ((u.T + 15) / 16) * ws[i].ksplit;
+      a.in_launch_proj = 1;
+    }
+    dim3 grid((unsigned)(n_prod + blocks));
+    if (u.T <= 16) {
+      if (f16) k_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
+      else k_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
+    } else {
+      if (f16) k_decode<ACT_F16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
+      else k_decode<ACT_BF16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace glowq

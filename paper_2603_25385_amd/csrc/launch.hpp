@@ -41,8 +41,10 @@ hipError_t launch_proj(const glowq_unit& u, const UnitWorkspace& ws, float* R32,
                        hipStream_t st);
 // T <= 32: streaming pass over the prepared weights; when restore, the projection runs
 // in the first workgroups of the same launch
-hipError_t launch_decode(const glowq_unit& u, const UnitWorkspace& ws, bool restore,
-                         hipStream_t st);
+bool decode_batch_compatible(const glowq_unit& a, const glowq_unit& b);
+int decode_max_batch();
+hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspace* ws,
+                               const bool* restore, int n, hipStream_t st);
 // T > 32: tiled matrix-core GEMM, correction folded in as an extra K slab.  One launch
 // covers several compatible units (same types, group size and token-tile size).
 bool prefill_compatible(const glowq_unit& a, const glowq_unit& b);
