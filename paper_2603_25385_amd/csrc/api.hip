@@ -21,7 +21,7 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   // that a wave has all its loads in flight at once, at most four parts; the consumers
   // add the parts themselves)
   const bool direct = u.T <= 4;
-  int ksplit = direct ? (u.d_in + 2047) / 2048 : is_decode(u.T) ? 32 : (256 + tblocks - 1) / tblocks;
+  int ksplit = direct ? (u.d_in + 2047) / 2048 : is_decode(u.T) ? 8 : (256 + tblocks - 1) / tblocks;
   if (direct && ksplit > 4) ksplit = 4;
   if (ksplit > 32) ksplit = 32;
   if (ksplit < 1) ksplit = 1;
@@ -31,7 +31,7 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   w.ksplit = (u.d_in + w.kslice - 1) / w.kslice;
   w.kstride = (w.ksplit + 3) / 4 * 4;
   w.off_rpart = w.ctl_bytes;
-  size_t rpart = (u.r > 0) ? (size_t)w.kstride * u.T * u.r * (direct ? 8 : 4) : 0;
+  size_t rpart = (u.r > 0) ? (size_t)w.kstride * u.T * u.r * (is_decode(u.T) ? 8 : 4) : 0;
   w.off_r16 = align_up(w.off_rpart + rpart, 256);
   size_t r16 = (u.r > 0) ? (size_t)u.T * u.r * 2 : 0;
   w.bytes = align_up(w.off_r16 + r16, 256);

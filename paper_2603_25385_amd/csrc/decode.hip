@@ -32,15 +32,16 @@ namespace glowq {
 
 static_assert(GLOWQ_MAX_RANK <= DEC_WAVES * 32, "one 32-rank correction step per wave");
 
-// Grid: [n_prod projection workgroups][one workgroup per 16-row block].
+// Grid: [n_prod projection workgroups][one workgroup per DEC_RG 16-row blocks].
 template <int ACT, int TBK>
-__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArgs p, int n_prod) {
+__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArgs p, int n_prod,
+                                                          int n_blocks) {
   __shared__ float lds[DEC_WAVES * TBK * 4 * 64];
   if ((int)blockIdx.x < n_prod) {
-    proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds, PROJ_TAG);
+    proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds, PROJ_SLOTS);
     return;
   }
-  decode_workgroup<ACT, TBK>(a, (int)blockIdx.x - n_prod, lds);
+  decode_workgroup<ACT, TBK>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds);
 }
 
 // Up to DEC_MAX_BATCH units of the same kind (activation type, token class) in one
@@ -175,13 +176,13 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
       n_prod = ((u.T + 15) / 16) * ws[i].ksplit;
       a.in_launch_proj = 1;
     }
-    dim3 grid((unsigned)(n_prod + blocks));
+    dim3 grid((unsigned)(n_prod + (blocks + DEC_RG - 1) / DEC_RG));
     if (u.T <= 16) {
-      if (f16) k_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
-      else k_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod);
+      if (f16) k_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
+      else k_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
     } else {
-      if (f16) k_decode<ACT_F16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
-      else k_decode<ACT_BF16, 2><<<grid, block, 0, st>>>(a, p, n_prod);
+      if (f16) k_decode<ACT_F16, 2><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
+      else k_decode<ACT_BF16, 2><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

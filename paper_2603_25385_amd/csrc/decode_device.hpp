@@ -150,6 +150,75 @@ constexpr int DEC_XROW = 1040;                       // bytes per token and chun
 __host__ __device__ constexpr int dec_xbuf_bytes(int T) { return (T * DEC_XROW + 63) / 64 * 64; }
 
 
+// 4 < T <= 32: a workgroup takes DEC_RG consecutive 16-row blocks of the unit (they may
+// belong to different modules) and runs them against the same X fragments, held in
+// registers: X is read once per workgroup instead of once per row block.  Two tiles per
+// register buffer, two buffers in flight.
+constexpr int DEC_RG = 3;
+constexpr int DEC_RCH = 2;
+
+template <int ACT, int TBK, bool G128>
+__device__ inline void decode_stream_rows(const DecodeArgs& a, const uint32_t* const (&recb)[DEC_RG],
+                                          int wave, int lane, float4_t (&acc)[DEC_RG][TBK]) {
+  const int n = lane & 15, kq = lane >> 4;
+  const int ktiles = a.K >> 7;
+  const int rw = G128 ? 272 : 288;             // words per tile record
+  // this wave's tiles: kb = wave + DEC_WAVES * t, t = 0 .. ntw - 1
+  const int ntw = (ktiles - wave + DEC_WAVES - 1) / DEC_WAVES;
+  if (ntw <= 0) return;
+  // tokens past T read the last valid token: their rows of D are never stored
+  const uint16_t* xrow[TBK];
+#pragma unroll
+  for (int tb = 0; tb < TBK; ++tb)
+    xrow[tb] = a.X + (size_t)min(16 * tb + n, a.T - 1) * a.K + 8 * kq + 128 * wave;
+
+  struct Buf {
+    u32x4_t x[DEC_RCH][TBK][4];
+    u32x4_t w[DEC_RCH][DEC_RG];
+    uint32_t s[DEC_RCH][DEC_RG][2];
+  };
+  Buf A, B;
+  auto load = [&](int t0, Buf& b) {
+#pragma unroll
+    for (int c = 0; c < DEC_RCH; ++c) {
+      const int t = min(t0 + c, ntw - 1);          // clamped: a duplicate tile is never used
+#pragma unroll
+      for (int tb = 0; tb < TBK; ++tb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          b.x[c][tb][j] = *(const u32x4_t*)(xrow[tb] + (size_t)t * (128 * DEC_WAVES) + 32 * j);
+#pragma unroll
+      for (int g = 0; g < DEC_RG; ++g) {
+        const uint32_t* rec = recb[g] + (size_t)t * (DEC_WAVES * rw);
+        b.w[c][g] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
+        b.s[c][g][0] = __builtin_nontemporal_load(rec + 256 + n);
+        if constexpr (G128) b.s[c][g][1] = b.s[c][g][0];
+        else b.s[c][g][1] = __builtin_nontemporal_load(rec + 272 + n);
+      }
+    }
+  };
+  auto run = [&](int t0, const Buf& b) {
+#pragma unroll
+    for (int c = 0; c < DEC_RCH; ++c) {
+      if (t0 + c < ntw) {
+#pragma unroll
+        for (int g = 0; g < DEC_RG; ++g)
+          decode_tile<ACT, TBK, G128>(b.w[c][g], b.s[c][g][0], b.s[c][g][1],
+                                      [&](int tb, int j) { return b.x[c][tb][j]; }, acc[g]);
+      }
+    }
+  };
+  load(0, A);
+  for (int t0 = 0; t0 < ntw; t0 += 2 * DEC_RCH) {
+    if (t0 + DEC_RCH < ntw) load(t0 + DEC_RCH, B);
+    run(t0, A);
+    if (t0 + DEC_RCH < ntw) {
+      if (t0 + 2 * DEC_RCH < ntw) load(t0 + 2 * DEC_RCH, A);
+      run(t0 + DEC_RCH, B);
+    }
+  }
+}
+
 // X staging and its ordering.  Loads of a wave complete in the order they were issued,
 // so a chunk's X has landed as soon as any load issued after it has: with room for three
 // chunk buffers (TM <= 2) the X of chunk k+1 goes out ahead of the weights of chunk k
@@ -431,20 +500,68 @@ __device__ inline CorrFrag correction_prefetch(const DecodeArgs& a, const Module
   return c;
 }
 
-// Correction R A_i^T as r more channels of the contraction.
+// Correction R A_i^T as r more channels of the contraction (4 < T <= 32).  R comes from
+// the projection workgroups of the same launch as self-validating slots (PROJ_SLOTS):
+// a lane reads the slots of its own token and eight ranks, every K slice, with
+// device-scope loads, checks the tags and adds the slices in order.  The projection
+// workgroups lead the grid and wait for nothing; the wait is bounded all the same, and a
+// wave that gives up records it in ctl->status and leaves the correction out.
+// R fragments of this wave's correction step for every token block: fetched once per
+// workgroup (all row blocks of the group use the same ones).  Returns false if the
+// bounded wait expired.
 template <int ACT, int TBK>
-__device__ inline void decode_correction(const DecodeArgs& a, const CorrFrag& c, int lane,
-                                         float4_t (&acc)[TBK]) {
-  if (!c.active) return;
-  if (!wait_r_ready(a)) return;
+__device__ inline bool fetch_r_slots(const DecodeArgs& a, const ProjArgs& p, bool active, bool lane_ok,
+                                     int j0c, int lane, u32x4_t (&rf)[TBK]) {
+#pragma unroll
+  for (int tb = 0; tb < TBK; ++tb) rf[tb] = u32x4_t{0u, 0u, 0u, 0u};
+  if (!active) return true;
   const int n = lane & 15;
+  const uint32_t tag = (uint32_t)(launch_tag() & 0xffffffffull);
 #pragma unroll
   for (int tb = 0; tb < TBK; ++tb) {
-    const int tok = min(16 * tb + n, a.T - 1);
-    u32x4_t rf = load_r16(a.R16 + (size_t)tok * a.r + c.j0c);
-    if (!c.ok) rf = u32x4_t{0u, 0u, 0u, 0u};
-    acc[tb] = mfma16<ACT>(rf, c.af, acc[tb]);
+    const int tok = 16 * tb + n;
+    const bool on = lane_ok && tok < a.T;
+    const unsigned long long* q =
+        (const unsigned long long*)p.Rpart + (size_t)(on ? tok : 0) * p.ksplit * a.r + j0c;
+    float s[8];
+    bool done = false;
+    for (int spin = 0; spin < (1 << 14); ++spin) {
+      bool ok = true;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s[e] = 0.f;
+      for (int part0 = 0; part0 < p.ksplit; part0 += 4) {     // 32 loads in flight per lane
+        unsigned long long v[4][8];
+#pragma unroll
+        for (int pp = 0; pp < 4; ++pp)
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            v[pp][e] = (on && part0 + pp < p.ksplit)
+                           ? __hip_atomic_load(q + (size_t)(part0 + pp) * a.r + e, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT)
+                           : 0ull;
+#pragma unroll
+        for (int pp = 0; pp < 4; ++pp)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            if (part0 + pp < p.ksplit) {
+              ok = ok && ((uint32_t)(v[pp][e] >> 32) == tag);
+              s[e] += __builtin_bit_cast(float, (uint32_t)v[pp][e]);
+            }
+          }
+      }
+      if (!on) ok = true;
+      if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) { done = true; break; }
+      __builtin_amdgcn_s_sleep(32);
+    }
+    if (!done) {
+      if (lane == 0) atomicOr(&a.ctl->status, 1u);
+      return false;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      rf[tb][i] = on ? ((uint32_t)to_act16<ACT>(s[2 * i]) | ((uint32_t)to_act16<ACT>(s[2 * i + 1]) << 16)) : 0u;
   }
+  return true;
 }
 
 // lds: DEC_WAVES * TBK * 256 floats
@@ -481,22 +598,48 @@ __device__ inline const ModuleArgs& find_module(const DecodeArgs& a, int blk) {
   return a.mod[mi];
 }
 
+// grp: index of the workgroup's group of DEC_RG row blocks; n_blocks: row blocks of the unit
 template <int ACT, int TBK>
-__device__ inline void decode_workgroup(const DecodeArgs& a, int blk, float* lds) {
-  const ModuleArgs& M = find_module(a, blk);
-  const int rb = blk - M.blk_start;
+__device__ inline void decode_workgroup(const DecodeArgs& a, const ProjArgs& p, int grp, int n_blocks,
+                                        float* lds) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ktiles = a.K >> 7;
+  const int rw = a.G == 128 ? 272 : 288;
 
-  float4_t acc[TBK];
+  float4_t acc[DEC_RG][TBK];
+  const uint32_t* recb[DEC_RG];
+  CorrFrag cf[DEC_RG];
 #pragma unroll
-  for (int tb = 0; tb < TBK; ++tb) acc[tb] = float4_t{0.f, 0.f, 0.f, 0.f};
-
-  const CorrFrag cf = correction_prefetch(a, M, rb, wave, lane);
-  if (a.G == 128) decode_stream<ACT, TBK, true>(a, M, rb, wave, lane, acc);
-  else decode_stream<ACT, TBK, false>(a, M, rb, wave, lane, acc);
-  decode_correction<ACT, TBK>(a, cf, lane, acc);
-  decode_reduce_store<ACT, TBK>(a, M, rb, wave, lane, acc, lds);
+  for (int g = 0; g < DEC_RG; ++g) {
+#pragma unroll
+    for (int tb = 0; tb < TBK; ++tb) acc[g][tb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    // a group past the unit's last block repeats it (computed, not stored)
+    const int blk = min(grp * DEC_RG + g, n_blocks - 1);
+    const ModuleArgs& M = find_module(a, blk);
+    const int rb = blk - M.blk_start;
+    recb[g] = M.rec + ((size_t)rb * ktiles + wave) * rw;
+    cf[g] = correction_prefetch(a, M, rb, wave, lane);
+  }
+  GLOWQ_STAMP(0);
+  if (a.G == 128) decode_stream_rows<ACT, TBK, true>(a, recb, wave, lane, acc);
+  else decode_stream_rows<ACT, TBK, false>(a, recb, wave, lane, acc);
+  GLOWQ_STAMP(1);
+  u32x4_t rf[TBK];
+  const bool have_r = fetch_r_slots<ACT, TBK>(a, p, cf[0].active, cf[0].ok, cf[0].j0c, lane, rf);
+#pragma unroll
+  for (int g = 0; g < DEC_RG; ++g) {
+    const int blk = grp * DEC_RG + g;
+    if (blk >= n_blocks) break;                    // uniform
+    const ModuleArgs& M = find_module(a, blk);
+    if (cf[g].active && have_r) {
+#pragma unroll
+      for (int tb = 0; tb < TBK; ++tb) acc[g][tb] = mfma16<ACT>(rf[tb], cf[g].af, acc[g][tb]);
+    }
+    if (g > 0) __syncthreads();                    // the fold area is free again
+    decode_reduce_store<ACT, TBK>(a, M, blk - M.blk_start, wave, lane, acc[g], lds);
+  }
+  GLOWQ_STAMP(4);
 }
 
 // T <= 4.  lds: DEC_WAVES * 256 floats for the fold; lds_x: DEC_WAVES * DecX<TM>::WAVE_BYTES;

@@ -27,7 +27,11 @@ struct ProjArgs {
 // mode PROJ_ALONE : stand-alone kernel; the last slice of a token block reduces it.
 // mode PROJ_TAG   : same, and the workgroup that completes the last token block then
 //                   publishes the launch tag (consumers in the same launch wait for it).
-enum { PROJ_ALONE = 0, PROJ_TAG = 1 };
+// mode PROJ_SLOTS : no reduction here: every partial sum is published as one 8-byte
+//                   device-scope store {fp32 bits, low word of the launch tag}, slot
+//                   (t, kz, j) = slots[(t ksplit + kz) r + j], and the consumers add the
+//                   slices (no fence, no counter, nothing to wait for).
+enum { PROJ_ALONE = 0, PROJ_TAG = 1, PROJ_SLOTS = 2 };
 
 template <int ACT>
 __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* lds, int mode) {
@@ -48,16 +52,31 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
   const int k_begin = kz * a.kslice;
   const int k_end = min(a.K, k_begin + a.kslice);
   const uint16_t* xrow = a.X + (size_t)tok * a.K + 8 * kq;
-  for (int k = k_begin + wave * 32; k < k_end; k += nw * 32) {
-    const u32x4_t xf = *(const u32x4_t*)(xrow + k);
+  // steps of 32 channels, interleaved over the waves; the loads of PB steps are in
+  // flight together (a step past the end re-reads the first one and multiplies by zero)
+  constexpr int PB = 4;
+  for (int k0 = k_begin + wave * 32; k0 < k_end; k0 += PB * nw * 32) {
+    u32x4_t xf[PB], bf[PB][8];
 #pragma unroll
-    for (int nb = 0; nb < 8; ++nb) {
-      if (nb < nbs) {
-        const int rank = min(nb * 16 + i, a.r - 1);
-        const u32x4_t bf = *(const u32x4_t*)(a.B + (size_t)rank * a.K + k + 8 * kq);
-        acc[nb] = mfma16<ACT>(xf, bf, acc[nb]);   // D[token][rank]
+    for (int s = 0; s < PB; ++s) {
+      const int k = k0 + s * nw * 32;
+      const bool in = k < k_end;
+      const int kc = in ? k : k0;
+      xf[s] = *(const u32x4_t*)(xrow + kc);
+      if (!in) xf[s] = u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) {
+        if (nb < nbs) {
+          const int rank = min(nb * 16 + i, a.r - 1);
+          bf[s][nb] = *(const u32x4_t*)(a.B + (size_t)rank * a.K + kc + 8 * kq);
+        }
       }
     }
+#pragma unroll
+    for (int s = 0; s < PB; ++s)
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb)
+        if (nb < nbs) acc[nb] = mfma16<ACT>(xf[s], bf[s][nb], acc[nb]);   // D[token][rank]
   }
 
   GLOWQ_STAMP(1);
@@ -74,12 +93,22 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
         for (int w = 0; w < nw; ++w) s += lds[(w * 4 + v) * 64 + ln];
         const int t = tb * 16 + 4 * (ln >> 4) + v;
         const int rank = nb * 16 + (ln & 15);
-        if (t < a.T && rank < a.r) a.Rpart[((size_t)t * a.r + rank) * a.kstride + kz] = s;
+        if (t < a.T && rank < a.r) {
+          if (mode == PROJ_SLOTS) {
+            const unsigned long long tag_hi = (launch_tag() & 0xffffffffull) << 32;
+            __hip_atomic_store((unsigned long long*)a.Rpart + ((size_t)t * a.ksplit + kz) * a.r + rank,
+                               tag_hi | (unsigned long long)__builtin_bit_cast(uint32_t, s),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          } else {
+            a.Rpart[((size_t)t * a.r + rank) * a.kstride + kz] = s;
+          }
+        }
       }
       __syncthreads();
     }
   }
   GLOWQ_STAMP(2);
+  if (mode == PROJ_SLOTS) return;
 
   // the last slice to arrive for this token block adds the partial sums in slice order
   __threadfence();
