@@ -107,12 +107,12 @@ glowq_status glowq_prepare_weights(const uint32_t* wq, const uint16_t* scales,
                                    int32_t group_size, void* w_prepared, void* stream);
 
 /* ---- workspace ------------------------------------------------------------
- * Scratch for a call over `n_units` units (R in 16 bit, fp32 partial sums of the
- * projection, a few control words).  glowq_workspace_init clears it; it must be
- * called once before the first forward call that uses the buffer.  After that one
+ * Scratch for a call over `n_units` units (R in 16 bit, partial sums of the
+ * projection, a few control and flag words).  glowq_workspace_init clears it; it must
+ * be called once before the first forward call that uses the buffer.  After that one
  * buffer can serve any number of consecutive calls on one stream, eager or replayed
  * from a captured graph: a launch recognises its own projection by a tag that is
- * unique per kernel launch, and every call leaves the arrival counters at zero.  Calls
+ * unique per kernel launch, so nothing in the buffer ever has to be reset.  Calls
  * that may overlap in time need separate workspaces.  Word 3 of a unit's slice (byte
  * offset 12) is a status word: nonzero means a bounded in-kernel wait expired and the
  * correction of that unit was left out; it cannot happen unless workgroups of a launch

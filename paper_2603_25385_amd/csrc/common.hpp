@@ -285,9 +285,9 @@ static __device__ unsigned long long g_trace[8192][8];   // one copy per transla
 
 // Control words at the head of a unit's workspace slice.
 struct Control {
-  unsigned long long r_tag;  // launch tag of the launch whose R is complete in the workspace
-  uint32_t blocks_done;      // token blocks of the projection finished in the running launch
-  uint32_t status;           // nonzero: a bounded wait expired (cannot happen: see wait_r_ready)
+  unsigned long long reserved0;
+  uint32_t reserved1;
+  uint32_t status;           // nonzero: a bounded wait expired (cannot happen: producers wait for nothing)
   uint32_t pad[12];
 };
 

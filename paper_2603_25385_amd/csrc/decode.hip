@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArg
                                                           int n_blocks) {
   __shared__ float lds[DEC_WAVES * TBK * 4 * 64];
   if ((int)blockIdx.x < n_prod) {
-    proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds, PROJ_SLOTS);
+    proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds);
     return;
   }
   decode_workgroup<ACT, TBK>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds);

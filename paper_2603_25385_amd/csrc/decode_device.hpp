@@ -322,42 +322,6 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
   }
 }
 
-// Single-launch mode: a wave that is about to read R polls the tag that the last
-// projection workgroup stores, with release semantics, once R is complete.  The tag is
-// unique to the launch, so nothing has to be reset afterwards and a value left by an
-// earlier launch can never be mistaken for this one's.  The projection workgroups have
-// the lowest indices of the grid and never wait for anything, so the poll ends as soon
-// as they have run; the loop is bounded all the same, and a wave that gives up records
-// it in ctl->status and leaves the correction out rather than hang.
-__device__ inline bool wait_r_ready(const DecodeArgs& a) {
-  if (!a.in_launch_proj) return true;
-  const unsigned long long tag = launch_tag();
-  bool ok = false;
-  for (int spin = 0; spin < (1 << 20); ++spin) {
-    const unsigned long long v = __hip_atomic_load(&a.ctl->r_tag, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-    if (v == tag) { ok = true; break; }
-    __builtin_amdgcn_s_sleep(8);
-  }
-  // No cache invalidation here (it would hit every wave of the grid): R is read with
-  // device-coherent loads instead, see load_r16().  The compiler must not hoist them.
-  __atomic_signal_fence(__ATOMIC_SEQ_CST);
-  if (!ok && (threadIdx.x & 63) == 0) atomicOr(&a.ctl->status, 1u);
-  return ok;
-}
-
-// Eight 16-bit values of R read with device-scope loads: they bypass whatever this
-// compute unit or this XCD's L2 may still hold for the address from an earlier call.
-__device__ inline u32x4_t load_r16(const uint16_t* p) {
-  const uint32_t* q = (const uint32_t*)p;
-  u32x4_t v;
-  v[0] = __hip_atomic_load(q + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  v[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  v[2] = __hip_atomic_load(q + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  v[3] = __hip_atomic_load(q + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return v;
-}
-
 // Direct mode (T <= 4): every (rank, K part) wave of the projection leaves, per token,
 // one 8-byte slot {partial sum, low word of its launch tag}; slot of (t, part, j) is
 // slots[(t ksplit + part) r + j], so the eight ranks a lane needs for its matrix operand
@@ -411,11 +375,7 @@ __device__ inline void r_fetch_take(const DecodeArgs& a, const ProjArgs& p, int 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       f.v[part][i] = u32x4_t{0u, 0u, 0u, 0u};
-#if defined(GLOWQ_FORCE_RETRY) && GLOWQ_FORCE_RETRY == 2
-      if (false)
-#else
       if (f.on && part < p.ksplit)
-#endif
         f.v[part][i] = *(const u32x4_t*)(lds_rf_wave + (n * DEC_MAX_PARTS + part) * 64 + 16 * kq + 4 * i);
     }
 }
@@ -665,11 +625,7 @@ __device__ inline void decode_workgroup_small(const DecodeArgs& a, const ProjArg
   RFetch rfetch;
   r_fetch_plan(a, p, cf.j0c, a.restore && cf.active && cf.ok, lane, rfetch);
   uint32_t* lds_rf_wave = lds_rf + wave * (TM * DEC_MAX_PARTS * 64);
-#if defined(GLOWQ_FORCE_RETRY) && GLOWQ_FORCE_RETRY == 1
-  auto mid = [&]() {};
-#else
   auto mid = [&]() { if (a.restore && cf.active) r_fetch_issue(a, p, wave, lane, lds_rf_wave); };
-#endif
   char* lds_wave = lds_x + wave * DecX<TM>::WAVE_BYTES;
   if (a.G == 128) {
     if constexpr (TM == 1) decode_stream_small<ACT, true, 1, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);

@@ -1,27 +1,22 @@
 // Prefill path (T > 32 tokens): Y_i = X dequant(W_q,i)^T + R A_i^T  (paper Eq. 9)
-// as a tiled matrix-core GEMM with the correction folded in as r extra channels.
+// as a tiled matrix-core GEMM with the correction folded in as r extra channels, and
+// R = X B^T (paper Eq. 8) computed by the leading tiles of the same launch.
 //
-// Workgroup tile: (16 MB) tokens x 256 rows (MB = 8: 128 tokens), four waves, each wave
-// 64 rows x all tokens of the tile; 128 accumulator registers per lane leave room for
-// two workgroups per compute unit, so one wave's dequantisation overlaps another's
-// matrix work.  The packed weights never pass through LDS: a wave fetches its 16-row x
-// 128-channel tiles with one contiguous 1 KiB load each, already in operand order,
-// dequantises a word into eight 16-bit values in registers (one rounding, the stored
-// weight exactly) and feeds them to the matrix core as the A operand of a 16x16x32
-// instruction; because every wave covers all tokens of the tile, each weight is
-// dequantised once per workgroup.  X is staged through LDS in 64-channel stages, double
-// buffered; the 16-byte chunks of a row are XOR-swizzled by the row index so that the
-// 128-bit operand reads are conflict free without padding.  One barrier per stage, and
-// it waits for LDS traffic only: the weight loads of the next tile stay in flight
-// across it.  D is [row][token], so a
-// lane ends up with four consecutive rows of one token and stores them with one 8- or
-// 16-byte write.
+// Workgroup tile: (16 MB) tokens x 256 rows (192 for bfloat16), four waves, each wave
+// 64 (48) rows x all tokens of the tile; at most 256 registers per lane, so two
+// workgroups share a compute unit and one's barrier or memory wait leaves the matrix
+// cores to the other.  Because every wave covers all tokens of the tile, each weight is
+// dequantised once per workgroup (in registers: one rounding, the stored weight exactly)
+// and becomes the A operand of a 16x16x32 instruction.  Everything that moves is a
+// direct global->LDS load: X in 64-channel stages into a ring of three (the 16-byte
+// chunks of a row XOR-swizzled by the row index on the global-address side, so that the
+// 128-bit operand reads are conflict free without padding), the tile records of the next
+// tile into a per-wave stage.  The operand reads, the waits and the one barrier per
+// stage are placed by hand (see the kernel).  D is [row][token], so a lane ends up with
+// four consecutive rows of one token and stores them with one 8- or 16-byte write.
 #include "common.hpp"
 #include "launch.hpp"
 
-#ifndef PF_EXP
-#define PF_EXP 0
-#endif
 namespace glowq {
 
 // Two waves per SIMD either way: binary16 runs two workgroups of four waves per compute
@@ -73,10 +68,6 @@ struct PrefillArgs {
   int out_f32;
 };
 
-// s_waitcnt lgkmcnt(0) only (LDS traffic of this wave has completed); vector-memory
-// loads stay in flight.  gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] |
-// vmcnt[5:4] at [15:14].
-__device__ inline void wait_lds_only() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // a pointer that is the same in every lane, moved to scalar registers
 template <typename T> __device__ inline T* uniform_ptr(T* p) {
@@ -404,9 +395,8 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   // slices of one matrix instruction each (32 per step, fenced so that the compiler
   // keeps them apart): behind product (b, mb) of step j rides one slice of the
   // dequantisation of the operand words of step j+1; the LDS reads of the X fragments
-  // run two token blocks ahead; global loads run two stages (X) and one tile (W) ahead
-  // and are spread over the first slices of a stage, the LDS writes of the next
-  // stage's X over the later ones.
+  // run XD token blocks ahead; the direct loads run two stages (X) and one tile (W)
+  // ahead and sit in the first slices of a stage.
   int slot_cur = 0, slot_next2 = 2;   // ring slots of the stage being read and of stage+2
   for (int kt = 0; kt < ktiles; ++kt) {
 #ifdef GLOWQ_TRACE
@@ -470,14 +460,14 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
           {
             constexpr int NS = RB * MB;
             constexpr int NO = DequantLockstep<ACT, RB>::N_OPS;
-            if (i < RB && new_group && !(PF_EXP & 4)) g[i].set(szcur[i][G128 ? 0 : (jn >> 1)]);
+            if (i < RB && new_group) g[i].set(szcur[i][G128 ? 0 : (jn >> 1)]);
             // the first RB slots carry the group constants when a new group starts; the
             // recipe's instructions are spread evenly over the slots after them
             const int lo = i < RB ? 0 : ((i - RB) * NO) / (NS - RB);
             const int hi = i < RB ? 0 : ((i - RB + 1) * NO) / (NS - RB);
 #pragma unroll
             for (int o = lo; o < hi; ++o)
-              if (!(PF_EXP & 4)) dq.op(o, wcur, jn, g, wn);
+              dq.op(o, wcur, jn, g, wn);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -490,7 +480,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
         constexpr int YOUNGER = XI + RB * 2;
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(YOUNGER) : "memory");
       }
-      if (!(PF_EXP & 32)) __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();
       slot_cur = slot_cur == NBUF - 1 ? 0 : slot_cur + 1;
       slot_next2 = slot_next2 == NBUF - 1 ? 0 : slot_next2 + 1;
     }

@@ -13,29 +13,22 @@ struct ProjArgs {
   int ksplit;          // K slices
   int kslice;          // channels per slice, multiple of 32
   int kstride;         // ksplit rounded up to a multiple of 4
-  float* Rpart;        // fp32 [T][r][kstride]: the slices of one output are contiguous
-                       // (direct mode: 8-byte slots {fp32 bits, launch tag} instead)
+  float* Rpart;        // stand-alone projection: fp32 [slice][T][r]; in-launch projection
+                       // of the decode kernels: 8-byte slots {fp32 bits, launch tag}
   float* R32;          // optional fp32 [T][r]
   uint16_t* R16;       // optional act dtype [T][r]
   Control* ctl;
-  uint32_t* counters;  // one per 16-token block, zero between launches
-  int tblocks;         // 16-token blocks in the launch (single-launch mode)
+  uint32_t* counters;  // one word per 16-token block (ready flags of the prefill tiles)
+  int tblocks;         // 16-token blocks of the unit
 };
 
 // One workgroup = (16-token block tb, K slice kz); any whole number of waves.
 // lds: blockDim.x / 64 * 256 floats.
-// mode PROJ_ALONE : stand-alone kernel; the last slice of a token block reduces it.
-// mode PROJ_TAG   : same, and the workgroup that completes the last token block then
-//                   publishes the launch tag (consumers in the same launch wait for it).
-// mode PROJ_SLOTS : no reduction here: every partial sum is published as one 8-byte
-//                   device-scope store {fp32 bits, low word of the launch tag}, slot
-//                   (t, kz, j) = slots[(t ksplit + kz) r + j], and the consumers add the
-//                   slices (no fence, no counter, nothing to wait for).
-enum { PROJ_ALONE = 0, PROJ_TAG = 1, PROJ_SLOTS = 2 };
-
+// No reduction here: every partial sum is published as one 8-byte device-scope store
+// {fp32 bits, low word of the launch tag}, slot (t, kz, j) = slots[(t ksplit + kz) r + j],
+// and the consumers add the slices (no fence, no counter, nothing to wait for).
 template <int ACT>
-__device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* lds, int mode) {
-  __shared__ uint32_t s_prev;
+__device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* lds) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
   const int nbs = (a.r + 15) >> 4;
   const int i = lane & 15, kq = lane >> 4;
@@ -94,64 +87,16 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
         const int t = tb * 16 + 4 * (ln >> 4) + v;
         const int rank = nb * 16 + (ln & 15);
         if (t < a.T && rank < a.r) {
-          if (mode == PROJ_SLOTS) {
-            const unsigned long long tag_hi = (launch_tag() & 0xffffffffull) << 32;
-            __hip_atomic_store((unsigned long long*)a.Rpart + ((size_t)t * a.ksplit + kz) * a.r + rank,
-                               tag_hi | (unsigned long long)__builtin_bit_cast(uint32_t, s),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          } else {
-            a.Rpart[((size_t)t * a.r + rank) * a.kstride + kz] = s;
-          }
+          const unsigned long long tag_hi = (launch_tag() & 0xffffffffull) << 32;
+          __hip_atomic_store((unsigned long long*)a.Rpart + ((size_t)t * a.ksplit + kz) * a.r + rank,
+                             tag_hi | (unsigned long long)__builtin_bit_cast(uint32_t, s),
+                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
       __syncthreads();
     }
   }
   GLOWQ_STAMP(2);
-  if (mode == PROJ_SLOTS) return;
-
-  // the last slice to arrive for this token block adds the partial sums in slice order
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) s_prev = atomicAdd(&a.counters[tb], 1u);
-  __syncthreads();
-  GLOWQ_STAMP(3);
-  if (s_prev != (uint32_t)(a.ksplit - 1)) return;
-  __threadfence();
-  GLOWQ_STAMP(4);
-  for (int e = tid; e < 16 * a.r; e += blockDim.x) {
-    const int t = tb * 16 + e / a.r, rank = e % a.r;
-    if (t < a.T) {
-      const float4_t* p = (const float4_t*)(a.Rpart + ((size_t)t * a.r + rank) * a.kstride);
-      float s = 0.f;
-#pragma unroll 4
-      for (int z = 0; z < a.ksplit; z += 4) {     // independent 16-byte loads, slice order
-        const float4_t v = p[z >> 2];
-        s += v[0];
-        if (z + 1 < a.ksplit) s += v[1];
-        if (z + 2 < a.ksplit) s += v[2];
-        if (z + 3 < a.ksplit) s += v[3];
-      }
-      if (a.R32) a.R32[(size_t)t * a.r + rank] = s;
-      if (a.R16) a.R16[(size_t)t * a.r + rank] = to_act16<ACT>(s);
-    }
-  }
-  GLOWQ_STAMP(5);
-  if (tid == 0) a.counters[tb] = 0u;
-  if (mode == PROJ_TAG) {
-    // single-launch mode: the workgroup that completes the last token block publishes
-    // this launch's tag; consumers of the same launch wait for exactly that value
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      const uint32_t done = atomicAdd(&a.ctl->blocks_done, 1u);
-      if (done == (uint32_t)(a.tblocks - 1)) {
-        a.ctl->blocks_done = 0u;
-        __hip_atomic_store(&a.ctl->r_tag, launch_tag(), __ATOMIC_RELEASE,
-                           __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
-  }
 }
 
 // Projection for a handful of tokens (T <= 4), built for the shortest dependency chain:
