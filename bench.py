@@ -265,9 +265,15 @@ def cpu_baseline(unit, shape, T, r, Gs, decode):
                 for o in shape.d_outs]
         sampled = int(sum(len(x) for x in rows))
     naive.load()
-    t0 = time.perf_counter()
-    naive.group_forward(unit, True, rows=rows)
-    dt = time.perf_counter() - t0
+    naive.group_forward(unit, True, rows=rows)          # first touch of the operands
+    # repeat the same sample until about ten seconds of CPU work have been timed
+    reps, total = 0, 0.0
+    while total < 10.0 and reps < 400:
+        t0 = time.perf_counter()
+        naive.group_forward(unit, True, rows=rows)
+        total += time.perf_counter() - t0
+        reps += 1
+    dt = total / reps
     K = shape.d_in
     by = sampled * K // 2 + sampled * (K // Gs) * 4 + sampled * r * 2 + r * K * 2 + T * K * 2 \
         + T * sampled * 2
@@ -277,9 +283,9 @@ def cpu_baseline(unit, shape, T, r, Gs, decode):
     else:
         val, unit_s = fl / dt / 1e12, "TFLOP/s"
     return {"value": val, "unit": unit_s, "cores": naive.max_threads(), "kind": "oracle",
-            "seconds": dt,
+            "seconds": total,
             "sample": f"unit 0 ({shape.name}), {T} token(s), {sampled} of {shape.rows} output rows, "
-                      "naive C loops in float64 with OpenMP"}
+                      f"{reps} repetitions, naive C loops in float64 with OpenMP"}
 
 
 if __name__ == "__main__":
