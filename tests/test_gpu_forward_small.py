@@ -32,9 +32,10 @@ def test_tiny_workload(T):
 
 
 @pytest.mark.parametrize("act", ["f16", "bf16"])
-@pytest.mark.parametrize("T", [3, 70, 257])
+@pytest.mark.parametrize("T", [3, 9, 20, 70, 257])
 def test_ragged_group(act, T):
-    # rows not a multiple of 32, three module sizes, two quantisation groups
+    # rows not a multiple of 32, three module sizes, two quantisation groups; 26 row blocks:
+    # the three-block groups of the 4 < T <= 32 path straddle the modules and end ragged
     shape = UnitShape("g", 384, (40, 264, 96))
     u = recipe_unit(O, 1, 0, T, r=24, shape=shape, act=act, G=128)
     ys, _, _ = run_group(u, True, ldy_pad=8)
@@ -44,7 +45,7 @@ def test_ragged_group(act, T):
 
 
 @pytest.mark.parametrize("r", [8, 16, 32, 64, 128])
-@pytest.mark.parametrize("T", [2, 48])
+@pytest.mark.parametrize("T", [2, 12, 48])
 def test_every_rank(r, T):
     shape = UnitShape("g", 256, (128, 64))
     u = recipe_unit(O, 1, 0, T, r=r, shape=shape, G=64)
@@ -107,6 +108,26 @@ def test_block_forward_with_mask():
     dus = [DeviceUnit(u) for u in units]
     ws = Workspace([d.desc for d in dus])
     for _ in range(2):                  # twice through the same workspace
+        for d in dus:
+            d.clear()
+        G.glowq_block_forward([d.desc for d in dus], bytes(mask), ws.ptr, ws.bytes, stream())
+        for d, u, f in zip(dus, units, mask):
+            _check(d.outputs(), O.group_forward(u, bool(f)), TOL)
+        ws.assert_idle()
+
+
+def test_block_forward_mixed_token_counts():
+    """Thirteen few-token units of different token classes and gating in one call: the
+    decode launches batch up to eight compatible units and must split at every change
+    of class; every unit's result is the single-unit result."""
+    Ts = [1, 1, 2, 1, 1, 1, 1, 1, 1, 1, 4, 9, 1]
+    mask = [1, 0, 1, 1, 1, 0, 1, 1, 1, 1, 1, 1, 0]
+    shapes = [UnitShape("a", 256, (64, 32)), UnitShape("b", 128, (48,)), UnitShape("c", 384, (16, 16, 16))]
+    units = [recipe_unit(O, 1, 0, T, seed=10 + i, shape=shapes[i % 3], r=16, G=64)
+             for i, T in enumerate(Ts)]
+    dus = [DeviceUnit(u) for u in units]
+    ws = Workspace([d.desc for d in dus])
+    for _ in range(2):
         for d in dus:
             d.clear()
         G.glowq_block_forward([d.desc for d in dus], bytes(mask), ws.ptr, ws.bytes, stream())
