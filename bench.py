@@ -28,6 +28,9 @@ MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 / bf16 matrix throughput
 # name -> (config id, T, bound)
 WORKLOADS = {
     "cfg2_T1": (2, 1, "hbm"),
+    "cfg2_T2": (2, 2, "hbm"),
+    "cfg2_T4": (2, 4, "hbm"),
+    "cfg2_T8": (2, 8, "hbm"),
     "cfg2_T16": (2, 16, "hbm"),
     "cfg3": (3, 2048, "mfma"),
     "cfg4": (4, 512, "mfma"),
