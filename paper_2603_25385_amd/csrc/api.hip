@@ -14,7 +14,8 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   w.base = base;
   const int tblocks = (u.T + 15) / 16;
   w.off_counters = sizeof(Control);
-  w.ctl_bytes = align_up(w.off_counters + (size_t)tblocks * 4, 256);
+  // (one word more than blocks: the arrival counter of a last tile of a single block)
+  w.ctl_bytes = align_up(w.off_counters + (size_t)(tblocks + 1) * 4, 256);
   // K slices of the projection: decode spreads B over many compute units; prefill
   // already has T / 16 token blocks and only needs enough slices to fill the chip
   // (a handful of tokens: one wave per (rank, part) and parts of about 2048 channels, so
@@ -30,8 +31,17 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   w.kslice = per * 32;
   w.ksplit = (u.d_in + w.kslice - 1) / w.kslice;
   w.kstride = (w.ksplit + 3) / 4 * 4;
+  // T > 32: the projection tiles that lead the GEMM launch take parts of about 2048
+  // channels (at most 8), so that the longest contraction's R is ready as early as the
+  // shortest one's
+  const int stages = u.d_in / 64;
+  int parts = (u.d_in + 2047) / 2048;
+  if (parts > 8) parts = 8;
+  w.pf_part_stages = (stages + parts - 1) / parts;
+  w.pf_parts = (stages + w.pf_part_stages - 1) / w.pf_part_stages;
   w.off_rpart = w.ctl_bytes;
-  size_t rpart = (u.r > 0) ? (size_t)w.kstride * u.T * u.r * (is_decode(u.T) ? 8 : 4) : 0;
+  const int slabs = is_decode(u.T) ? w.kstride : (w.kstride > w.pf_parts ? w.kstride : w.pf_parts);
+  size_t rpart = (u.r > 0) ? (size_t)slabs * u.T * u.r * (is_decode(u.T) ? 8 : 4) : 0;
   w.off_r16 = align_up(w.off_rpart + rpart, 256);
   size_t r16 = (u.r > 0) ? (size_t)u.T * u.r * 2 : 0;
   w.bytes = align_up(w.off_r16 + r16, 256);

@@ -17,6 +17,8 @@ struct UnitWorkspace {
   int ksplit;         // K slices of the projection
   int kslice;         // channels per slice (multiple of 32)
   int kstride;        // elements between the slice arrays of two outputs in the partial-sum area
+  int pf_parts;       // T > 32: K parts of a projection tile inside the GEMM launch
+  int pf_part_stages; // 64-channel stages per such part
 };
 
 // decode path = one pass over the weights with all tokens in one matrix-core tile

@@ -44,7 +44,11 @@ struct PfUnit {
   const uint16_t* X;
   const uint16_t* B;       // shared right factor [r][K]
   uint16_t* R16;           // R = X B^T rounded to the activation type, [T][r], in the workspace
-  uint32_t* flags;         // one word per 16-token block; word MB*mt is token tile mt's ready flag
+  float* Rpart;            // fp32 [parts][T][r]: the K parts' partial sums (parts > 1 only)
+  uint32_t* flags;         // one word per 16-token block; word MB*mt is token tile mt's ready
+                           // flag, word MB*mt + 1 counts the K parts of that tile that are done
+  int parts;               // K parts of a projection tile (one workgroup each)
+  int part_stages;         // 64-channel stages per part
   uint32_t* status;        // the unit's status word (see Control)
   int T, K, r, restore, n_mtiles;
   int proj_start;          // first workgroup of this unit's projection tiles in the grid
@@ -78,10 +82,14 @@ template <typename T> __device__ inline T* uniform_ptr(T* p) {
 }
 
 // Projection tile of the prefill launch: R[tile] = X[tile] B^T  (paper Eq. 8), MT tokens x
-// all r ranks over the whole contraction, rounded once to the activation type and
-// stored in the workspace; then the tile's flag is set to this launch's tag.  These
-// tiles are the first workgroups of the grid, so they are running before any tile that
-// needs their result has started, and they wait for nothing.
+// all r ranks, rounded once to the activation type and stored in the workspace; then the
+// tile's flag is set to this launch's tag.  These tiles are the first workgroups of the
+// grid, so they are running before any tile that needs their result has started, and
+// they wait for nothing.  A long contraction is cut into K parts, one workgroup each, so
+// that R is ready well before the main tiles of the same unit reach their correction:
+// every part leaves its fp32 partial tile in the workspace and counts itself in; the
+// part that finds all others counted adds the partial tiles in part order (so the sum
+// does not depend on which one that is), rounds, stores and sets the flag.
 // X takes the same path as in the main tiles (LDS ring, swizzled rows); the rows of B
 // are read straight into operand registers, one stage ahead.
 template <int ACT, int MB>
@@ -96,11 +104,14 @@ __device__ inline void proj_tile(const PrefillArgs& a, uint16_t* xs) {
   for (int i = 0; i < PF_MAX_UNITS; ++i)
     if (i < a.n_units && a.unit[i].proj_start >= 0 && (int)blockIdx.x >= a.unit[i].proj_start) ui = i;
   const PfUnit& U = a.unit[ui];
-  const int mt = (int)blockIdx.x - U.proj_start;
+  const int local = (int)blockIdx.x - U.proj_start;
+  const int mt = local / U.parts, part = local - mt * U.parts;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, kq = lane >> 4;
   const int nstages = U.K >> 6;
+  const int s_begin = part * U.part_stages;                    // < nstages (host)
+  const int s_end = min(nstages, s_begin + U.part_stages);
   const int tok0 = mt * MT;
 
   const uint16_t* xsrc[XI];
@@ -142,10 +153,10 @@ __device__ inline void proj_tile(const PrefillArgs& a, uint16_t* xs) {
     for (int mb = 0; mb < MB; ++mb) acc[b][mb] = float4_t{0.f, 0.f, 0.f, 0.f};
 
 #pragma unroll
-  for (int i = 0; i < XI; ++i) dma_x(0, 0, i);
+  for (int i = 0; i < XI; ++i) dma_x(s_begin, 0, i);
 #pragma unroll
-  for (int i = 0; i < XI; ++i) dma_x(1, 1, i);
-  load_b(0);
+  for (int i = 0; i < XI; ++i) dma_x(s_begin + 1, 1, i);
+  load_b(s_begin);
   vm_wait<0>();
 #pragma unroll
   for (int b = 0; b < RBP; ++b)
@@ -154,7 +165,7 @@ __device__ inline void proj_tile(const PrefillArgs& a, uint16_t* xs) {
   __builtin_amdgcn_s_barrier();
 
   int slot_cur = 0, slot_next2 = 2;
-  for (int stage = 0; stage < nstages; ++stage) {
+  for (int stage = s_begin; stage < s_end; ++stage) {
     const uint32_t xa[2] = {rd_lane[0] + (uint32_t)slot_cur * STAGE_BYTES,
                             rd_lane[1] + (uint32_t)slot_cur * STAGE_BYTES};
     u32x4_t xq[3];
@@ -189,6 +200,52 @@ __device__ inline void proj_tile(const PrefillArgs& a, uint16_t* xs) {
   vm_wait<0>();   // nothing may still be on its way into LDS when the workgroup ends
 
   // lane holds token (mb, n) and ranks 16 blk + 4 kq + {0..3}
+  if (U.parts > 1) {
+    float* mine = U.Rpart + (size_t)part * U.T * U.r;
+#pragma unroll
+    for (int b = 0; b < RBP; ++b) {
+      const int rank0 = (wave * RBP + b) * 16 + 4 * kq;
+      if (rank0 >= U.r) continue;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int tok = tok0 + mb * 16 + n;
+        if (tok < U.T) *(float4_t*)(mine + (size_t)tok * U.r + rank0) = acc[b][mb];
+      }
+    }
+    // count this part in (after its stores are visible device-wide); all but the last
+    // one to arrive are done
+    __threadfence();
+    __syncthreads();
+    uint32_t* lds_word = (uint32_t*)xs;      // the X ring is idle from here on
+    if (tid == 0)
+      *lds_word = __hip_atomic_fetch_add(U.flags + MB * mt + 1, 1u, __ATOMIC_ACQ_REL,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t arrived = *lds_word;
+    if (arrived + 1 != (uint32_t)U.parts) return;   // uniform
+    __threadfence();
+#pragma unroll
+    for (int b = 0; b < RBP; ++b) {
+      const int rank0 = (wave * RBP + b) * 16 + 4 * kq;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int tok = min(tok0 + mb * 16 + n, U.T - 1);
+        float4_t sum = float4_t{0.f, 0.f, 0.f, 0.f};
+        if (rank0 < U.r) {
+          for (int p = 0; p < U.parts; ++p) {
+            const uint32_t* q = (const uint32_t*)(U.Rpart + ((size_t)p * U.T + tok) * U.r + rank0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              sum[v] += __builtin_bit_cast(float, __hip_atomic_load(q + v, __ATOMIC_RELAXED,
+                                                                    __HIP_MEMORY_SCOPE_AGENT));
+          }
+        }
+        acc[b][mb] = sum;
+      }
+    }
+    if (tid == 0)   // the next launch counts from zero again
+      __hip_atomic_store(U.flags + MB * mt + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 #pragma unroll
   for (int b = 0; b < RBP; ++b) {
     const int rank0 = (wave * RBP + b) * 16 + 4 * kq;
@@ -583,9 +640,11 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
     PfUnit& pu = a.unit[oi];
     const int n_mtiles = (u.T + 16 * MB - 1) / (16 * MB);
     pu.proj_start = -1;
+    pu.parts = ws[ui].pf_parts;
+    pu.part_stages = ws[ui].pf_part_stages;
     if (restore[ui] && u.r > 0) {
       pu.proj_start = n_proj;
-      n_proj += n_mtiles;
+      n_proj += n_mtiles * pu.parts;
     }
   }
   a.n_proj_wgs = n_proj;
@@ -598,6 +657,7 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
     pu.X = (const uint16_t*)u.X;
     pu.B = (const uint16_t*)u.B;
     pu.R16 = (uint16_t*)(ws[ui].base + ws[ui].off_r16);
+    pu.Rpart = (float*)(ws[ui].base + ws[ui].off_rpart);
     pu.flags = (uint32_t*)(ws[ui].base + ws[ui].off_counters);
     pu.status = &((Control*)ws[ui].base)->status;
     pu.T = u.T;

@@ -112,6 +112,12 @@ class Workspace:
             assert cw[2] == 0 and cw[3] == 0, cw
             if T <= 32:
                 assert not any(cw[2:]), cw
+            else:
+                # tiled path: word 1 of each token tile's flag words counts the projection's
+                # K parts and is back at zero when the launch has ended
+                mb = 4 if T <= 64 else 8
+                for i in range(16 + 1, len(cw), mb):
+                    assert cw[i] == 0, (i, cw)
 
 
 def run_group(unit: dict, restore: bool = True, out: str = "f32", ldy_pad: int = 0):

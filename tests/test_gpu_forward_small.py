@@ -53,6 +53,25 @@ def test_every_rank(r, T):
     _check(ys, O.group_forward(u, True), TOL)
 
 
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+@pytest.mark.parametrize("T", [40, 130, 300])
+def test_long_contraction(act, T):
+    # d_in past 2048: the projection tiles of the tiled path work in K parts (here three
+    # of unequal length) and the last one to finish adds them; T = 130 ends in a token
+    # tile of a single 16-token block.  Twice through one workspace: the parts' arrival
+    # counter must be back at zero.
+    shape = UnitShape("g", 4352, (64, 40))
+    u = recipe_unit(O, 1, 0, T, r=24, shape=shape, act=act, G=128)
+    du = DeviceUnit(u)
+    ws = Workspace([du.desc])
+    ref = O.group_forward(u, True)
+    for _ in range(2):
+        du.clear()
+        G.glowq_group_forward(du.desc, True, ws.ptr, ws.bytes, stream())
+        _check(du.outputs(), ref, TOL)
+        ws.assert_idle()
+
+
 @pytest.mark.parametrize("T", [4, 96])
 def test_masked_unit_equals_rank_zero_bitwise(T):
     u = recipe_unit(O, 1, 0, T)
