@@ -31,6 +31,12 @@ def check_no_spills(src: str, remarks: str) -> None:
     for line in remarks.splitlines():
         if "Function Name:" in line:
             name = line.split("Function Name:")[1].strip()
+        elif "AGPRs:" in line and name and any(k in name for k in NO_SPILL):
+            # values parked in accumulation registers are copies too, and a copy of a
+            # register whose load is still in flight (hand-counted waits) reads garbage
+            if int(line.split("AGPRs:")[1].split()[0]):
+                raise RuntimeError(f"{src}: {name} uses accumulation registers; this kernel "
+                                   "must keep everything in vector registers")
         elif "ScratchSize [bytes/lane]:" in line and name:
             n = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
             if n and any(k in name for k in NO_SPILL):

@@ -314,6 +314,9 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   // registers once per tile
   constexpr int WREC = 1024 + 128;
   __shared__ __attribute__((aligned(1024))) uint8_t wstage[PF_WAVES * RB * WREC];
+  // set when a wave's bounded wait for the projection expired: then no wave of the
+  // workgroup applies the correction
+  __shared__ uint32_t corr_failed;
 
   if ((int)blockIdx.x < a.n_proj_wgs) {
     proj_tile<ACT, MB>(a, xs);
@@ -430,6 +433,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 #ifdef GLOWQ_TRACE
   const unsigned long long clk0 = __builtin_amdgcn_s_memtime();
 #endif
+  if (tid == 0) corr_failed = 0;       // ordered before its readers by the loop's barriers
 #pragma unroll
   for (int i = 0; i < XI; ++i) dma_x(0, 0, i);
 #pragma unroll
@@ -549,27 +553,80 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 #ifdef GLOWQ_TRACE
   if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace[blockIdx.x][7] = __builtin_amdgcn_s_memtime() - clk0;
 #endif
-  // correction: r more channels, operand [A_i] against [R]; every lane runs the same
-  // trip count, lanes past the rank contribute zeros on both sides
-  if (U.restore && wait_tile_ready(U.flags + MB * mt, U.status)) {
-    for (int jj = 0; jj * 32 < U.r; ++jj) {
-      const int j0 = jj * 32 + 8 * kq;
-      const bool ok = j0 < U.r;
-      const int j0c = ok ? j0 : 0;
-      u32x4_t af[RB];
+  // correction: r more channels in stages of 64, operand [A_i] against [R].  The A words
+  // do not depend on the projection and are asked for before its flag is looked at; the
+  // R tile then takes the X path (straight into the idle ring, swizzled the same way,
+  // with device-coherent loads: other compute units wrote it during this launch), so
+  // that nothing in here waits for memory more than twice.
+  if (U.restore) {
+    const int rstages = (U.r + 63) >> 6;                       // 1 or 2
+    u32x4_t af[2][2][RB];
 #pragma unroll
-      for (int b = 0; b < RB; ++b) {
-        const int row = min((nb0 + b) * 16 + n, M.d_out - 1);   // clamped like the tiles
-        af[b] = *(const u32x4_t*)(M.A + (size_t)row * U.r + j0c);
-        if (!ok) af[b] = u32x4_t{0u, 0u, 0u, 0u};
-      }
+    for (int rs = 0; rs < 2; ++rs)
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const int tok = min(tok0 + mb * 16 + n, U.T - 1);
-        u32x4_t rf = load16_device(U.R16 + (size_t)tok * U.r + j0c);
-        if (!ok) rf = u32x4_t{0u, 0u, 0u, 0u};
+      for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-        for (int b = 0; b < RB; ++b) acc[b][mb] = mfma16<ACT>(af[b], rf, acc[b][mb]);
+        for (int b = 0; b < RB; ++b) {
+          // ranks past r: operand words of rank 0 here, R words of a valid rank below,
+          // and the product left out
+          const int j0 = 64 * rs + 32 * jj + 8 * kq;
+          const int row = min((nb0 + b) * 16 + n, M.d_out - 1);   // clamped like the tiles
+          if (rs < rstages) vm_load(af[rs][jj][b], M.A + (size_t)row * U.r + (j0 < U.r ? j0 : 0));
+        }
+    const bool ready = wait_tile_ready(U.flags + MB * mt, U.status);
+    if (!ready && lane == 0) atomicOr(&corr_failed, 1u);
+    if (ready) {
+      const uint16_t* rtile = uniform_ptr(U.R16 + (size_t)tok0 * U.r);
+#pragma unroll
+      for (int rs = 0; rs < 2; ++rs)
+#pragma unroll
+        for (int i = 0; i < XI; ++i) {
+          const int row = XR * i + (tid >> 3);
+          const int chunk = (tid & 7) ^ ((row >> 1) & 7);
+          const int rank = min(64 * rs + 8 * chunk, U.r - 8);
+          const uint32_t off = (uint32_t)((min(tok0 + row, U.T - 1) - tok0) * U.r + rank) * 2u;
+          if (rs < rstages)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)((const char*)rtile + off),
+                (__attribute__((address_space(3))) void*)(xs + rs * (MT * 64) + (XR * i + 8 * wave) * 64),
+                16, 0, /*device scope*/ 16);
+        }
+    }
+    vm_wait<0>();
+#pragma unroll
+    for (int rs = 0; rs < 2; ++rs)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int b = 0; b < RB; ++b)
+          if (rs < rstages) after_wait(af[rs][jj][b]);
+    __builtin_amdgcn_s_barrier();
+    if (corr_failed == 0) {
+#pragma unroll
+      for (int rs = 0; rs < 2; ++rs) {
+        if (rs < rstages) {
+          const uint32_t xa[2] = {rd_lane[0] + (uint32_t)rs * STAGE_BYTES, rd_lane[1] + (uint32_t)rs * STAGE_BYTES};
+          u32x4_t xq[3];
+          lds_read(xq[0], xa[0], 0);
+          lds_read(xq[1], xa[0], 2048);
+#pragma unroll
+          for (int f = 0; f < 2 * MB; ++f) {
+            if (f + 2 < 2 * MB) {
+              lds_read(xq[(f + 2) % 3], xa[(f + 2) / MB], ((f + 2) % MB) * 2048);
+              lds_wait<2>(xq[f % 3]);
+            } else if (f + 2 == 2 * MB) lds_wait<1>(xq[f % 3]);
+            else lds_wait<0>(xq[f % 3]);
+            const int jj = f / MB, mb = f % MB;
+            if (64 * rs + 32 * jj < U.r) {           // uniform
+#pragma unroll
+              for (int b = 0; b < RB; ++b) {
+                u32x4_t aw = af[rs][jj][b];
+                if (64 * rs + 32 * jj + 8 * kq >= U.r) aw = u32x4_t{0u, 0u, 0u, 0u};
+                acc[b][mb] = mfma16<ACT>(aw, xq[f % 3], acc[b][mb]);
+              }
+            }
+          }
+        }
       }
     }
   }
