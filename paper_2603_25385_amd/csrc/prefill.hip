@@ -309,11 +309,11 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   constexpr int NBUF = 3;
   constexpr uint32_t STAGE_BYTES = MT * 64 * 2;
   __shared__ __attribute__((aligned(1024))) uint16_t xs[NBUF * MT * 64];
-  // per wave: its RB tile records of the next tile (1 KiB of words each, then 128 bytes
-  // of scale/zero words each), landed here by the same kind of load and taken into
+  // per wave: its RB tile records of the next tile (1 KiB of words each, then 512 bytes
+  // for their scale/zero words), landed here by the same kind of load and taken into
   // registers once per tile
-  constexpr int WREC = 1024 + 128;
-  __shared__ __attribute__((aligned(1024))) uint8_t wstage[PF_WAVES * RB * WREC];
+  constexpr int WSTG = RB * 1024 + 512;
+  __shared__ __attribute__((aligned(1024))) uint8_t wstage[PF_WAVES * WSTG];
   // set when a wave's bounded wait for the projection expired: then no wave of the
   // workgroup applies the correction
   __shared__ uint32_t corr_failed;
@@ -389,21 +389,39 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 
   u32x4_t wcur[RB];
   uint32_t szcur[RB][2];
-  uint8_t* wmine = wstage + wave * (RB * WREC);
+  uint8_t* wmine = wstage + wave * WSTG;
   const uint32_t wmine_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)wmine;
-  // two loads per 16-row block: the 256 words (16 bytes per lane) and the 16 or 32
-  // scale/zero words (4 bytes per lane, low lanes only)
+  // one load per 16-row block for its 256 words (16 bytes per lane), and one (group size
+  // 128: 16 scale/zero words per block, lane -> block lane >> 4) or two (group size 64: 32
+  // words per block, lane -> block lane >> 5 of a pair) for the scale/zero words of all
+  // RB blocks, every lane taking part, so that the loop carries no branch (lanes past the
+  // last block fetch its words once more, into the unused tail of the stage)
+  constexpr int SZB = G128 ? 64 : 128;     // bytes of scale/zero words per block in the stage
+  constexpr int SZI = G128 ? 1 : 2;        // instructions that fetch them
+  static_assert(RB <= 4, "the scale/zero loads cover four blocks");
+  const uint32_t* szsrc[SZI];              // this lane's word of K tile 0, per instruction
+#pragma unroll
+  for (int j = 0; j < SZI; ++j) {
+    const int rsel = G128 ? (lane >> 4) : 2 * j + (lane >> 5);
+    const uint32_t* base = wt[0];
+#pragma unroll
+    for (int b = 1; b < RB; ++b) base = rsel >= b ? wt[b] : base;
+    szsrc[j] = base + 256 + (G128 ? (lane & 15) : (lane & 31));
+  }
   auto dma_w = [&](int kt, int b) {
     const int k = min(kt, ktiles - 1);
     const uint32_t* rec = wt[b] + (size_t)k * RW;
     __builtin_amdgcn_global_load_lds(
         (const __attribute__((address_space(1))) void*)(rec + lane * 4),
         (__attribute__((address_space(3))) void*)(wmine + b * 1024), 16, 0, 0);
-    if (lane < (G128 ? 16 : 32))
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(rec + 256 + lane),
-          (__attribute__((address_space(3))) void*)(wmine + RB * 1024 + b * 128), 4, 0, 0);
   };
+  auto dma_sz = [&](int kt, int j) {
+    const int k = min(kt, ktiles - 1);
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(szsrc[j] + (size_t)k * RW),
+        (__attribute__((address_space(3))) void*)(wmine + RB * 1024 + j * 256), 4, 0, 0);
+  };
+  constexpr int NWL = RB + SZI;            // load instructions per K tile of weights
   // LDS -> registers (the loads that filled the stage must have completed: vm_wait);
   // the results are pending until an lds wait
   const uint32_t wl16 = wmine_lds + lane * 16, wl4 = wmine_lds + RB * 1024 + n * 4;
@@ -411,8 +429,8 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
       lds_read(wcur[b], wl16, b * 1024);
-      lds_read32(szcur[b][0], wl4, b * 128);
-      if (!G128) lds_read32(szcur[b][1], wl4, b * 128 + 64);
+      lds_read32(szcur[b][0], wl4, b * SZB);
+      if (!G128) lds_read32(szcur[b][1], wl4, b * SZB + 64);
     }
   };
   auto tie_w = [&]() {
@@ -438,6 +456,8 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   for (int i = 0; i < XI; ++i) dma_x(0, 0, i);
 #pragma unroll
   for (int b = 0; b < RB; ++b) dma_w(0, b);
+#pragma unroll
+  for (int j = 0; j < SZI; ++j) dma_sz(0, j);
 #pragma unroll
   for (int i = 0; i < XI; ++i) dma_x(1, 1, i);
   vm_wait<0>();
@@ -514,6 +534,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
           if (jj == half && i < XI) dma_x(stage + 2, slot_next2, i);
           // the next tile's records, into this wave's stage (free since the last take)
           if (j == 0 && i >= XI && i < XI + RB) dma_w(kt + 1, i - XI);
+          if (j == 0 && i >= XI + RB && i < XI + NWL) dma_sz(kt + 1, i - XI - RB);
           // the product
           acc[b][mb] = mfma16<ACT>(wa[b], xq[f % (XD + 1)], acc[b][mb]);   // D[row][token]
           // its vector-ALU shadow: word i / 8 of the next step, slice i % 8
@@ -536,9 +557,9 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
       // one barrier per stage: everyone is done reading this stage, and everyone's part
       // of the next stage has landed.  Vector-memory operations complete in order, and
       // the ones issued after the next stage's loads are the XI loads of the stage after
-      // it plus one tile's weight loads (issued in this stage or in the one before).
+      // it plus one tile's NWL weight loads (issued in this stage or in the one before).
       {
-        constexpr int YOUNGER = XI + RB * 2;
+        constexpr int YOUNGER = XI + NWL;
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(YOUNGER) : "memory");
       }
       __builtin_amdgcn_s_barrier();
