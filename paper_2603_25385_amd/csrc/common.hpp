@@ -58,12 +58,15 @@ template <int ACT> struct GroupConst;
 template <> struct GroupConst<ACT_F16> {
   half2_t s2;    // (s, s)
   half2_t nb2;   // (-(1024 + z), -(1024 + z)), exact in binary16 for integer z <= 1023
+  half2_t nb2b;  // (-(64 + z), -(64 + z)), for nibbles read under the exponent of 64
   __device__ inline void set(uint32_t szw) {
     _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(szw & 0xffffu));
     _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)(szw >> 16));
     _Float16 nb = -((_Float16)1024.0f + z);
+    _Float16 nbb = -((_Float16)64.0f + z);
     s2 = half2_t{s, s};
     nb2 = half2_t{nb, nb};
+    nb2b = half2_t{nbb, nbb};
   }
 };
 template <> struct GroupConst<ACT_BF16> {
@@ -215,6 +218,36 @@ template <int NW> struct DequantLockstep<ACT_BF16, NW> {
         v[1] = (__bf16)f[c][1];
         out[w][i] = __builtin_bit_cast(uint32_t, v);
       }
+    }
+  }
+};
+
+// binary16 with two fewer instructions per word (needs one more constant per block and
+// one more register for the second magic constant).
+template <int NW> struct DequantLockstepF16Shiftless {
+  // Nibbles at bits 0-3 / 16-19 of a word become 1024 + q under the exponent of 1024
+  // (0x6400), nibbles at bits 4-7 / 20-23 become 64 + q under the exponent of 64 (0x5400:
+  // one unit in the last place is 1/16, so bit 4 weighs 1) -- no shift; the other four
+  // nibbles take the same two forms after one shift by 8.  13 instructions per word.
+  static constexpr int PH = 13, GS = NW < 2 ? NW : 2;
+  static constexpr int N_OPS = NW * PH;
+  uint32_t ws[GS];   // the word shifted by 8
+  half2_t d[GS];     // (q - z) pair in flight
+  __device__ inline void op(int idx, const u32x4_t (&wq)[NW], int j, const GroupConst<ACT_F16> (&g)[NW],
+                            u32x4_t (&out)[NW]) {
+    const int r_ = idx % (GS * PH), c = r_ % GS, w = (idx / (GS * PH)) * GS + c, ph = r_ / GS;
+    // phases: ao0 add0 mul0 | ao1 add1 mul1 | shr | ao2 add2 mul2 | ao3 add3 mul3
+    const int p = ph < 6 ? ph : ph - 1;            // phase with the shift taken out
+    const int i = p / 3, kind = p % 3;             // pair, 0 and_or / 1 add / 2 mul
+    if (ph == 6) ws[c] = wq[w][j] >> 8;
+    else if (kind == 0) {
+      const uint32_t src = i < 2 ? wq[w][j] : ws[c];
+      const uint32_t t = (i & 1) ? and_or(src, 0x00F000F0u, 0x54005400u) : and_or(src, 0x000F000Fu, 0x64006400u);
+      d[c] = __builtin_bit_cast(half2_t, t);
+    } else if (kind == 1) d[c] = d[c] + ((i & 1) ? g[w].nb2b : g[w].nb2);
+    else {
+      const half2_t v = d[c] * g[w].s2;   // the one rounding
+      out[w][i] = __builtin_bit_cast(uint32_t, v);
     }
   }
 };

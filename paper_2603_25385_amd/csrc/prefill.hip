@@ -14,6 +14,7 @@
 // tile into a per-wave stage.  The operand reads, the waits and the one barrier per
 // stage are placed by hand (see the kernel).  D is [row][token], so a lane ends up with
 // four consecutive rows of one token and stores them with one 8- or 16-byte write.
+#include <type_traits>
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -445,7 +446,9 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   // operand words of step j (32 channels) of the current tile, one per 16-row block
   u32x4_t wf[2][RB];
   GroupConst<ACT> g[RB];
-  DequantLockstep<ACT, RB> dq;
+  // the shorter binary16 recipe where its extra registers fit
+  using DQ = std::conditional_t<ACT == ACT_F16 && G128, DequantLockstepF16Shiftless<RB>, DequantLockstep<ACT, RB>>;
+  DQ dq;
 
   GLOWQ_STAMP(0);
 #ifdef GLOWQ_TRACE
@@ -541,7 +544,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
           // its vector-ALU shadow: the next instructions of the next step's dequantisation
           {
             constexpr int NS = RB * MB;
-            constexpr int NO = DequantLockstep<ACT, RB>::N_OPS;
+            constexpr int NO = DQ::N_OPS;
             if (i < RB && new_group) g[i].set(szcur[i][G128 ? 0 : (jn >> 1)]);
             // the first RB slots carry the group constants when a new group starts; the
             // recipe's instructions are spread evenly over the slots after them
