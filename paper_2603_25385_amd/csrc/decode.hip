@@ -37,11 +37,13 @@ template <int ACT, int TBK>
 __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArgs p, int n_prod,
                                                           int n_blocks) {
   __shared__ float lds[DEC_WAVES * TBK * 4 * 64];
+  __shared__ __attribute__((aligned(16))) uint16_t r_lds[16 * TBK * GLOWQ_MAX_RANK];
+  __shared__ uint32_t r_flag;
   if ((int)blockIdx.x < n_prod) {
     proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds);
     return;
   }
-  decode_workgroup<ACT, TBK>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds);
+  decode_workgroup<ACT, TBK>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds, r_lds, &r_flag);
 }
 
 // Up to DEC_MAX_BATCH units of the same kind (activation type, token class) in one

@@ -461,67 +461,79 @@ __device__ inline CorrFrag correction_prefetch(const DecodeArgs& a, const Module
 }
 
 // Correction R A_i^T as r more channels of the contraction (4 < T <= 32).  R comes from
-// the projection workgroups of the same launch as self-validating slots (PROJ_SLOTS):
-// a lane reads the slots of its own token and eight ranks, every K slice, with
-// device-scope loads, checks the tags and adds the slices in order.  The projection
-// workgroups lead the grid and wait for nothing; the wait is bounded all the same, and a
-// wave that gives up records it in ctl->status and leaves the correction out.
-// R fragments of this wave's correction step for every token block: fetched once per
-// workgroup (all row blocks of the group use the same ones).  Returns false if the
-// bounded wait expired.
+// the projection workgroups of the same launch as self-validating 8-byte slots
+// {fp32 partial sum, launch tag}, slot (t, part, j) at slots[(t ksplit + part) r + j]: one
+// contiguous region per unit.  The workgroup gathers it together: a thread owns pairs of
+// adjacent ranks of a token and reads their slots of every part with 16-byte
+// device-coherent loads (consecutive lanes read consecutive addresses), checks the tags,
+// adds the parts in part order, rounds to the activation type and leaves R in LDS, from
+// where every lane takes the operand words of its token and rank chunk.  (Eight-byte
+// loads per lane, token and rank straight from memory cost several times the whole
+// weight stream's tail: one request per lane and slot.)  The projection workgroups lead
+// the grid and wait for nothing; the wait is bounded all the same, and a workgroup that
+// gives up records it in ctl->status and leaves the correction out.
+// r_lds: act dtype [16 TBK][r]; flag: one LDS word.  Returns false if the bounded wait
+// expired (the same answer in every thread of the workgroup).
+__device__ inline void vm_load_dev(u32x4_t& v, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+}
 template <int ACT, int TBK>
-__device__ inline bool fetch_r_slots(const DecodeArgs& a, const ProjArgs& p, bool active, bool lane_ok,
-                                     int j0c, int lane, u32x4_t (&rf)[TBK]) {
-#pragma unroll
-  for (int tb = 0; tb < TBK; ++tb) rf[tb] = u32x4_t{0u, 0u, 0u, 0u};
-  if (!active) return true;
-  const int n = lane & 15;
+__device__ inline bool fetch_r_coop(const DecodeArgs& a, const ProjArgs& p, uint16_t* r_lds, uint32_t* flag) {
+  const int tid = threadIdx.x;
+  const int hp = a.r >> 1;                     // rank pairs (16-byte units) per token and part
+  const int n_el = a.T * hp;                   // (token, rank pair) elements, <= 32 * 64
   const uint32_t tag = (uint32_t)(launch_tag() & 0xffffffffull);
+  const u32x4_t* units = (const u32x4_t*)p.Rpart;
+  constexpr int EPR = 2;                       // elements per thread and round
+  constexpr int MAXP = 8;                      // parts (ksplit <= 8 for these token counts)
+  if (tid == 0) *flag = 0u;
+  __syncthreads();
+  for (int spin = 0; spin < (1 << 12); ++spin) {
+    bool ok = true;
+    for (int e0 = 0; e0 < n_el; e0 += EPR * DEC_WAVES * 64) {
+      u32x4_t v[EPR][MAXP];
+      int el[EPR];
 #pragma unroll
-  for (int tb = 0; tb < TBK; ++tb) {
-    const int tok = 16 * tb + n;
-    const bool on = lane_ok && tok < a.T;
-    const unsigned long long* q =
-        (const unsigned long long*)p.Rpart + (size_t)(on ? tok : 0) * p.ksplit * a.r + j0c;
-    float s[8];
-    bool done = false;
-    for (int spin = 0; spin < (1 << 14); ++spin) {
-      bool ok = true;
+      for (int k = 0; k < EPR; ++k) {
+        el[k] = e0 + k * DEC_WAVES * 64 + tid;
+        const int ec = min(el[k], n_el - 1);   // clamped: loaded again, not used
+        const int tok = ec / hp, rp = ec - tok * hp;
+        const u32x4_t* q = units + (size_t)tok * p.ksplit * hp + rp;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s[e] = 0.f;
-      for (int part0 = 0; part0 < p.ksplit; part0 += 4) {     // 32 loads in flight per lane
-        unsigned long long v[4][8];
-#pragma unroll
-        for (int pp = 0; pp < 4; ++pp)
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            v[pp][e] = (on && part0 + pp < p.ksplit)
-                           ? __hip_atomic_load(q + (size_t)(part0 + pp) * a.r + e, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT)
-                           : 0ull;
-#pragma unroll
-        for (int pp = 0; pp < 4; ++pp)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            if (part0 + pp < p.ksplit) {
-              ok = ok && ((uint32_t)(v[pp][e] >> 32) == tag);
-              s[e] += __builtin_bit_cast(float, (uint32_t)v[pp][e]);
-            }
-          }
+        for (int part = 0; part < MAXP; ++part)
+          vm_load_dev(v[k][part], q + (size_t)min(part, p.ksplit - 1) * hp);
       }
-      if (!on) ok = true;
-      if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) { done = true; break; }
-      __builtin_amdgcn_s_sleep(32);
-    }
-    if (!done) {
-      if (lane == 0) atomicOr(&a.ctl->status, 1u);
-      return false;
-    }
+      vm_wait<0>();
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      rf[tb][i] = on ? ((uint32_t)to_act16<ACT>(s[2 * i]) | ((uint32_t)to_act16<ACT>(s[2 * i + 1]) << 16)) : 0u;
+      for (int k = 0; k < EPR; ++k) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int part = 0; part < MAXP; ++part) {
+          after_wait(v[k][part]);
+          if (part < p.ksplit) {
+            // (elements copied to scalars first: a bit cast applied directly to a vector
+            // element reads element 0)
+            const uint32_t w0 = v[k][part][0], t0 = v[k][part][1], w1 = v[k][part][2], t1 = v[k][part][3];
+            ok = ok && t0 == tag && t1 == tag;
+            s0 += __builtin_bit_cast(float, w0);
+            s1 += __builtin_bit_cast(float, w1);
+          }
+        }
+        if (el[k] < n_el)
+          ((uint32_t*)r_lds)[el[k]] = (uint32_t)to_act16<ACT>(s0) | ((uint32_t)to_act16<ACT>(s1) << 16);
+      }
+    }
+    if (!ok) *flag = 1u;
+    __syncthreads();
+    const bool failed = *flag != 0u;
+    if (!failed) return true;                  // R is complete in LDS
+    __syncthreads();
+    if (tid == 0) *flag = 0u;
+    __builtin_amdgcn_s_sleep(32);
+    __syncthreads();
   }
-  return true;
+  if (tid == 0) atomicOr(&a.ctl->status, 1u);
+  return false;
 }
 
 // lds: DEC_WAVES * TBK * 256 floats
@@ -559,9 +571,10 @@ __device__ inline const ModuleArgs& find_module(const DecodeArgs& a, int blk) {
 }
 
 // grp: index of the workgroup's group of DEC_RG row blocks; n_blocks: row blocks of the unit
+// lds: DEC_WAVES * TBK * 256 floats (fold); r_lds: act dtype [16 TBK][GLOWQ_MAX_RANK]; flag: one word
 template <int ACT, int TBK>
 __device__ inline void decode_workgroup(const DecodeArgs& a, const ProjArgs& p, int grp, int n_blocks,
-                                        float* lds) {
+                                        float* lds, uint16_t* r_lds, uint32_t* flag) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ktiles = a.K >> 7;
@@ -585,8 +598,21 @@ __device__ inline void decode_workgroup(const DecodeArgs& a, const ProjArgs& p, 
   if (a.G == 128) decode_stream_rows<ACT, TBK, true>(a, recb, wave, lane, acc);
   else decode_stream_rows<ACT, TBK, false>(a, recb, wave, lane, acc);
   GLOWQ_STAMP(1);
+  // R, once per workgroup (all row blocks of the group use the same fragments)
   u32x4_t rf[TBK];
-  const bool have_r = fetch_r_slots<ACT, TBK>(a, p, cf[0].active, cf[0].ok, cf[0].j0c, lane, rf);
+#pragma unroll
+  for (int tb = 0; tb < TBK; ++tb) rf[tb] = u32x4_t{0u, 0u, 0u, 0u};
+  bool have_r = false;
+  if (a.restore && a.r > 0) {                      // uniform
+    have_r = fetch_r_coop<ACT, TBK>(a, p, r_lds, flag);
+    if (have_r && cf[0].active && cf[0].ok) {
+#pragma unroll
+      for (int tb = 0; tb < TBK; ++tb) {
+        const int tok = 16 * tb + (lane & 15);
+        if (tok < a.T) rf[tb] = *(const u32x4_t*)(r_lds + (size_t)tok * a.r + cf[0].j0c);
+      }
+    }
+  }
 #pragma unroll
   for (int g = 0; g < DEC_RG; ++g) {
     const int blk = grp * DEC_RG + g;
