@@ -45,7 +45,7 @@ def test_ragged_group(act, T):
 
 
 @pytest.mark.parametrize("r", [8, 16, 32, 64, 128])
-@pytest.mark.parametrize("T", [2, 12, 48])
+@pytest.mark.parametrize("T", [2, 12, 32, 48])
 def test_every_rank(r, T):
     shape = UnitShape("g", 256, (128, 64))
     u = recipe_unit(O, 1, 0, T, r=r, shape=shape, G=64)
