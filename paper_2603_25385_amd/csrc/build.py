@@ -21,6 +21,10 @@ SOURCES = ["api.hip", "prepare.hip", "proj.hip", "decode.hip", "prefill.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Rpass-analysis=kernel-resource-usage"]
+# Per-file flags.  decode.hip: matrix-instruction results stay in ordinary vector registers
+# (the few-token kernels issue one correction product per workgroup; with it in an
+# accumulation register the 2- and 4-token kernels measured 4-7 % slower).
+FILE_FLAGS = {"decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 # Kernels that count their own outstanding memory operations (hand-placed s_waitcnt): a
 # register spill would add loads of the compiler's to that count, so they must have none.
 NO_SPILL = ("k_prefill",)
@@ -51,7 +55,7 @@ def build(verbose: bool = False, extra: list | None = None) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(LIB_DIR, src.replace(".hip", ".o"))
-        cmd = ["hipcc", *FLAGS, *(extra or []), "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = ["hipcc", *FLAGS, *FILE_FLAGS.get(src, []), *(extra or []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
