@@ -57,6 +57,9 @@ struct DecodeBatch {
   int n;
 };
 
+// whether the projection waves ride in the first row-block workgroups (see k_decode_small)
+constexpr bool decode_small_merged(int tm) { return tm > 2; }
+
 template <int ACT, int TM>
 __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeBatch b) {
   __shared__ float lds[DEC_WAVES * 4 * 64];
@@ -70,13 +73,20 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeBatch b) 
   const ProjArgs& p = b.p[ui];
   const int local = (int)blockIdx.x - b.wg_start[ui];
   const int n_prod = b.n_prod[ui];
+  // The 3- and 4-token instance holds three workgroups per compute unit (LDS), which a
+  // 7B-sized unit's row blocks fill exactly: there the projection waves are the first
+  // workgroups' prologue instead of workgroups of their own, so that the whole grid is
+  // resident from the start and no row block waits for a projection workgroup's slot.
+  constexpr bool MERGED = decode_small_merged(TM);
   if (local < n_prod) {
     GLOWQ_STAMP(0);
     proj_wave_direct<ACT>(p, local * DEC_WAVES + (int)(threadIdx.x >> 6), (int)(threadIdx.x & 63));
     GLOWQ_STAMP(1);
-    return;
+    if (!MERGED) return;
   }
-  decode_workgroup_small<ACT, TM>(a, p, local - n_prod, lds, lds_x, lds_rf);
+  const int blk = MERGED ? local : local - n_prod;
+  if (MERGED && blk >= a.mod[a.n_modules - 1].blk_start + a.mod[a.n_modules - 1].rows16) return;
+  decode_workgroup_small<ACT, TM>(a, p, blk, lds, lds_x, lds_rf);
 }
 
 int fill_decode_args(const glowq_unit& u, const UnitWorkspace& ws, bool restore, DecodeArgs& a) {
@@ -137,7 +147,8 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
         b.a[i].in_launch_proj = 1;
       }
       b.wg_start[i] = wg;
-      wg += b.n_prod[i] + blocks;
+      if (decode_small_merged(decode_small_class(u0.T))) wg += b.n_prod[i] > blocks ? b.n_prod[i] : blocks;
+      else wg += b.n_prod[i] + blocks;
     }
     for (int i = n; i < DEC_MAX_BATCH; ++i) {
       b.a[i] = b.a[0];
