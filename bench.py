@@ -65,6 +65,9 @@ def main() -> int:
     ap.add_argument("--rot", type=int, default=None, help="distinct operand copies to rotate over")
     ap.add_argument("--layers", type=int, default=None, help="cfg5 only: layers to instantiate")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--restore", default="workload", choices=["workload", "none", "all"],
+                    help="restore mask: the workload's own (default), no unit, or every unit "
+                         "(to price the correction; the JSON line says how many units were restored)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -94,6 +97,8 @@ def main() -> int:
                                 cfg["restore_fraction"])[:n_units]
     else:
         mask = np.ones(n_units, np.uint8)
+    if args.restore != "workload":
+        mask = np.full(n_units, 1 if args.restore == "all" else 0, np.uint8)
     decode = bound == "hbm"
     steps = args.steps if args.steps is not None else (200 if decode else 20)
     warmup = args.warmup if args.warmup is not None else (20 if decode else 3)
