@@ -102,11 +102,11 @@ static glowq_status forward_all(const glowq_unit* units, int n_units, const uint
     const glowq_unit& u = units[i];
     if (is_decode(u.T)) {
       // consecutive few-token units of one kind share a launch
-      const glowq_unit* dbatch[8];
-      UnitWorkspace dws[8];
-      bool dcorr[8];
+      const glowq_unit* dbatch[32];
+      UnitWorkspace dws[32];
+      bool dcorr[32];
       int nd = 0;
-      while (i < n_units && nd < decode_max_batch() && nd < 8 && is_decode(units[i].T) &&
+      while (i < n_units && nd < decode_max_batch() && nd < 32 && is_decode(units[i].T) &&
              (nd == 0 || decode_batch_compatible(*dbatch[0], units[i]))) {
         dbatch[nd] = &units[i];
         dws[nd] = plan_unit_workspace(units[i], workspace + off);

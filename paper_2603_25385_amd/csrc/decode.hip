@@ -46,28 +46,31 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArg
   decode_workgroup<ACT, TBK>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds, r_lds, &r_flag);
 }
 
-// Up to DEC_MAX_BATCH units of the same kind (activation type, token class) in one
-// launch: the grid is the concatenation of the units' [projection waves][row blocks].
-constexpr int DEC_MAX_BATCH = 8;
-struct DecodeBatch {
-  DecodeArgs a[DEC_MAX_BATCH];
-  ProjArgs p[DEC_MAX_BATCH];
-  int n_prod[DEC_MAX_BATCH];
-  int wg_start[DEC_MAX_BATCH];
+// Up to NB units of the same kind (activation type, token class) in one launch: the grid
+// is the concatenation of the units' [projection waves][row blocks].  The descriptor
+// block travels as the kernel argument; its size is a template parameter because a
+// one-unit call pays measurably for a block sized for many (and a whole model's stack
+// gains from fewer, larger launches).
+constexpr int DEC_MAX_BATCH = 32;
+template <int NB> struct DecodeBatch {
+  DecodeArgs a[NB];
+  ProjArgs p[NB];
+  int n_prod[NB];
+  int wg_start[NB];
   int n;
 };
 
 // whether the projection waves ride in the first row-block workgroups (see k_decode_small)
 constexpr bool decode_small_merged(int tm) { return tm > 2; }
 
-template <int ACT, int TM>
-__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeBatch b) {
+template <int ACT, int TM, int NB>
+__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeBatch<NB> b) {
   __shared__ float lds[DEC_WAVES * 4 * 64];
   __shared__ __attribute__((aligned(64))) char lds_x[DEC_WAVES * DecX<TM>::WAVE_BYTES];
   __shared__ __attribute__((aligned(16))) uint32_t lds_rf[DEC_WAVES * TM * DEC_MAX_PARTS * 64];
   int ui = 0;
 #pragma unroll
-  for (int i = 1; i < DEC_MAX_BATCH; ++i)
+  for (int i = 1; i < NB; ++i)
     if (i < b.n && (int)blockIdx.x >= b.wg_start[i]) ui = i;
   const DecodeArgs& a = b.a[ui];
   const ProjArgs& p = b.p[ui];
@@ -124,15 +127,14 @@ bool decode_batch_compatible(const glowq_unit& a, const glowq_unit& b) {
 }
 int decode_max_batch() { return DEC_MAX_BATCH; }
 
-// units[i] uses workspace slice ws[i]; all of them pass decode_batch_compatible with
-// units[0] (or n == 1, any decode-sized unit).
-hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspace* ws,
-                               const bool* restore, int n, hipStream_t st) {
+template <int NB>
+static hipError_t launch_decode_small(const glowq_unit* const* units, const UnitWorkspace* ws,
+                                      const bool* restore, int n, hipStream_t st) {
   const glowq_unit& u0 = *units[0];
   const bool f16 = (u0.act_dtype == GLOWQ_F16);
   dim3 block(DEC_WAVES * 64);
-  if (u0.T <= DEC_SMALL_T) {
-    DecodeBatch b;
+  {
+    DecodeBatch<NB> b;
     int wg = 0;
     for (int i = 0; i < n; ++i) {
       const glowq_unit& u = *units[i];
@@ -150,7 +152,7 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
       if (decode_small_merged(decode_small_class(u0.T))) wg += b.n_prod[i] > blocks ? b.n_prod[i] : blocks;
       else wg += b.n_prod[i] + blocks;
     }
-    for (int i = n; i < DEC_MAX_BATCH; ++i) {
+    for (int i = n; i < NB; ++i) {
       b.a[i] = b.a[0];
       b.p[i] = b.p[0];
       b.n_prod[i] = 0;
@@ -162,18 +164,32 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
     // per compute unit, so that a unit's whole grid is resident at once
     switch (decode_small_class(u0.T)) {
       case 1:
-        if (f16) k_decode_small<ACT_F16, 1><<<grid, block, 0, st>>>(b);
-        else k_decode_small<ACT_BF16, 1><<<grid, block, 0, st>>>(b);
+        if (f16) k_decode_small<ACT_F16, 1, NB><<<grid, block, 0, st>>>(b);
+        else k_decode_small<ACT_BF16, 1, NB><<<grid, block, 0, st>>>(b);
         break;
       case 2:
-        if (f16) k_decode_small<ACT_F16, 2><<<grid, block, 0, st>>>(b);
-        else k_decode_small<ACT_BF16, 2><<<grid, block, 0, st>>>(b);
+        if (f16) k_decode_small<ACT_F16, 2, NB><<<grid, block, 0, st>>>(b);
+        else k_decode_small<ACT_BF16, 2, NB><<<grid, block, 0, st>>>(b);
         break;
       default:
-        if (f16) k_decode_small<ACT_F16, DEC_SMALL_T><<<grid, block, 0, st>>>(b);
-        else k_decode_small<ACT_BF16, DEC_SMALL_T><<<grid, block, 0, st>>>(b);
+        if (f16) k_decode_small<ACT_F16, DEC_SMALL_T, NB><<<grid, block, 0, st>>>(b);
+        else k_decode_small<ACT_BF16, DEC_SMALL_T, NB><<<grid, block, 0, st>>>(b);
     }
     return hipGetLastError();
+  }
+}
+
+// units[i] uses workspace slice ws[i]; all of them pass decode_batch_compatible with
+// units[0] (or n == 1, any decode-sized unit).
+hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspace* ws,
+                               const bool* restore, int n, hipStream_t st) {
+  const glowq_unit& u0 = *units[0];
+  const bool f16 = (u0.act_dtype == GLOWQ_F16);
+  dim3 block(DEC_WAVES * 64);
+  if (u0.T <= DEC_SMALL_T) {
+    if (n <= 2) return launch_decode_small<2>(units, ws, restore, n, st);
+    if (n <= 8) return launch_decode_small<8>(units, ws, restore, n, st);
+    return launch_decode_small<DEC_MAX_BATCH>(units, ws, restore, n, st);
   }
   // 4 < T <= 32: one unit per launch
   for (int i = 0; i < n; ++i) {
