@@ -71,7 +71,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(no collective is part of the path, see DESIGN.md)", file=sys.stderr)
+              "(no collective is part of the path: units are independent and would be sharded "
+              "whole, one process per GPU)", file=sys.stderr)
         return 2
 
     import numpy as np
