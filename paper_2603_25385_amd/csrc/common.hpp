@@ -97,19 +97,22 @@ __device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) {
   return r;
 }
 
-// The eight values (q - z) of one prepared word as binary16 pairs, exact: the pair
-// (1024 + q_a, 1024 + q_b) is made by OR-ing two nibbles into the fraction of 0x6400,
-// and adding -(1024 + z) cancels the offset and the zero-point in one packed add.
-__device__ inline u32x4_t q_minus_z_f16(uint32_t w, half2_t nb2) {
+// The eight values (q - z) of one prepared word as binary16 pairs, exact.  Nibbles at bits
+// 0-3 / 16-19 are OR-ed into the fraction of 0x6400 (1024 + q), nibbles at bits 4-7 / 20-23
+// into the fraction of 0x5400 (64 + q: one unit in the last place is 1/16 there, so bit 4
+// weighs 1), the other four take the same two forms after one shift by 8; adding
+// -(1024 + z) or -(64 + z) cancels the offset and the zero-point in one packed add.
+__device__ inline u32x4_t q_minus_z_f16(uint32_t w, half2_t nb2, half2_t nb2b) {
 #ifdef GLOWQ_PROBE_NODEQ
   return u32x4_t{w, w ^ 1u, w ^ 2u, w ^ 3u};
 #endif
-  const uint32_t magic = 0x64006400u;
+  const uint32_t ws = w >> 8;
   u32x4_t out;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    uint32_t t = and_or(w >> (4 * i), 0x000F000Fu, magic);
-    half2_t v = __builtin_bit_cast(half2_t, t) + nb2;
+    const uint32_t src = i < 2 ? w : ws;
+    const uint32_t t = (i & 1) ? and_or(src, 0x00F000F0u, 0x54005400u) : and_or(src, 0x000F000Fu, 0x64006400u);
+    const half2_t v = __builtin_bit_cast(half2_t, t) + ((i & 1) ? nb2b : nb2);
     out[i] = __builtin_bit_cast(uint32_t, v);
   }
   return out;
@@ -117,7 +120,7 @@ __device__ inline u32x4_t q_minus_z_f16(uint32_t w, half2_t nb2) {
 
 template <>
 __device__ inline u32x4_t dequant_word<ACT_F16>(uint32_t w, const GroupConst<ACT_F16>& g) {
-  u32x4_t d = q_minus_z_f16(w, g.nb2);
+  u32x4_t d = q_minus_z_f16(w, g.nb2, g.nb2b);
   u32x4_t out;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {

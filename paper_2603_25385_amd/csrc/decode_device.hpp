@@ -51,7 +51,7 @@ __device__ inline void decode_tile(const u32x4_t w, uint32_t sz0, uint32_t sz1, 
 #pragma unroll
       for (int jj = 0; jj < WPH; ++jj) {
         const int j = hf * WPH + jj;
-        const u32x4_t wf = q_minus_z_f16(w[j], g.nb2);
+        const u32x4_t wf = q_minus_z_f16(w[j], g.nb2, g.nb2b);
 #pragma unroll
         for (int tb = 0; tb < TBK; ++tb) {
           const u32x4_t xf = xfrag(tb, j);
