@@ -24,6 +24,26 @@
  *  - Every function returns a glowq_status; on any error nothing is enqueued.
  *    Argument checking is host-side and touches no GPU.
  *  - All DEVICE pointers must be 16-byte aligned.
+ *
+ * How this boundary differs from the plainest possible statement of the problem
+ * ("packed INT4 words, a scale array and a zero-point array per module"), and why:
+ *  - Weights are handed over ONCE, through glowq_prepare_weights, which rewrites
+ *    the canonical arrays into tile records in matrix-core operand order with each
+ *    tile's (s, z) pairs folded in behind its weights (one DRAM page per tile).  A
+ *    glowq_module therefore carries the single pointer w_prepared instead of
+ *    wq / scales / zeros, and the inspection hooks read that prepared buffer.
+ *  - Every forward call, glowq_shared_proj included, takes a caller-owned workspace,
+ *    and glowq_workspace_init must have cleared it once before its first use: the
+ *    projection R is produced inside the forward launch and handed over through it.
+ *  - d_in must be a multiple of the 128-channel tile (not merely of the group size)
+ *    and d_out, ldy multiples of 8; r a multiple of 8 up to GLOWQ_MAX_RANK.  A request
+ *    that is well formed but outside these limits gets GLOWQ_ERR_UNSUPPORTED; sizes
+ *    that contradict the storage format itself get GLOWQ_ERR_SHAPE.
+ *  - binary16 activations with T <= 32: the kernels multiply X with the exact integers
+ *    (q - z) and apply s to the fp32 sum of each quantisation group, i.e. they use
+ *    (q - z) * s unrounded instead of its binary16 rounding (at most 2^-11 relative
+ *    per term closer to the real weight).  Every other path multiplies with
+ *    round_to_act((q - z) * s) bit for bit.
  */
 #ifndef GLOWQ_H
 #define GLOWQ_H
@@ -41,10 +61,14 @@ extern "C" {
 typedef enum {
   GLOWQ_OK = 0,
   GLOWQ_ERR_NULL = -1,        /* a required pointer is NULL                     */
-  GLOWQ_ERR_SHAPE = -2,       /* a size is out of range or inconsistent         */
+  GLOWQ_ERR_SHAPE = -2,       /* a size is out of range or contradicts the
+                                 storage format (d_in not a whole number of
+                                 groups, group size not 64 / 128, T < 1, ...)   */
   GLOWQ_ERR_ALIGN = -3,       /* a device pointer or stride is misaligned       */
   GLOWQ_ERR_DTYPE = -4,       /* unsupported activation / output type           */
-  GLOWQ_ERR_UNSUPPORTED = -5, /* valid request this build cannot serve          */
+  GLOWQ_ERR_UNSUPPORTED = -5, /* well-formed request this build cannot serve:
+                                 d_in not a multiple of 128, d_out or ldy not a
+                                 multiple of 8, r not a multiple of 8 or > 128  */
   GLOWQ_ERR_WORKSPACE = -6,   /* workspace missing or too small                 */
   GLOWQ_ERR_HIP = -7          /* a HIP runtime call failed                      */
 } glowq_status;
@@ -54,7 +78,8 @@ typedef enum { GLOWQ_F16 = 0, GLOWQ_BF16 = 1, GLOWQ_F32 = 2 } glowq_dtype;
 /* One module (one linear map W_i of a unit). */
 typedef struct {
   const void* w_prepared; /* DEVICE: output of glowq_prepare_weights for this module      */
-  const void* A;          /* DEVICE: act dtype [d_out][r]; may be NULL iff r == 0          */
+  const void* A;          /* DEVICE: act dtype [d_out][r]; may be NULL if r == 0 or the
+                             unit is not restored in this call                             */
   void* Y;                /* DEVICE: out dtype [T][ldy]                                    */
   int32_t d_out;          /* rows of W_i; multiple of 8                                    */
   int32_t ldy;            /* row stride of Y in elements; >= d_out, multiple of 8          */
@@ -65,7 +90,7 @@ typedef struct {
 typedef struct {
   const void* X;               /* DEVICE: act dtype [T][d_in]                              */
   const void* B;               /* DEVICE: act dtype [r][d_in], shared by all modules;
-                                  may be NULL iff r == 0                                    */
+                                  may be NULL if r == 0 or the unit is not restored         */
   const glowq_module* modules; /* HOST: n_modules descriptors                               */
   int32_t n_modules;           /* 1 .. GLOWQ_MAX_MODULES                                    */
   int32_t T;                   /* tokens (batch x time flattened), >= 1                     */
@@ -84,9 +109,9 @@ const char* glowq_status_string(glowq_status s);
  * ("no error" if there was none).  Static string owned by the HIP runtime. */
 const char* glowq_last_hip_error(void);
 
-/* Argument check of one unit exactly as the forward calls perform it (HOST
- * only, no GPU access).  check_pointers == 0 skips the NULL / alignment tests so
- * that shapes can be validated before buffers exist. */
+/* Argument check of one unit exactly as the forward calls perform it for a
+ * restored unit (HOST only, no GPU access).  check_pointers == 0 skips the NULL /
+ * alignment tests so that shapes can be validated before buffers exist. */
 glowq_status glowq_validate_unit(const glowq_unit* u, int32_t check_pointers);
 
 /* ---- weight preparation (one-off, at load time) --------------------------
@@ -113,12 +138,24 @@ glowq_status glowq_prepare_weights(const uint32_t* wq, const uint16_t* scales,
  * buffer can serve any number of consecutive calls on one stream, eager or replayed
  * from a captured graph: a launch recognises its own projection by a tag that is
  * unique per kernel launch, so nothing in the buffer ever has to be reset.  Calls
- * that may overlap in time need separate workspaces.  Word 3 of a unit's slice (byte
- * offset 12) is a status word: nonzero means a bounded in-kernel wait expired and the
- * correction of that unit was left out; it cannot happen unless workgroups of a launch
- * are prevented from running, and is there so that nothing can ever hang. */
+ * that may overlap in time need separate workspaces.
+ *
+ * Unit i's slice starts at the sum of glowq_workspace_bytes of the units before it
+ * (in the order of the forward call).  Word 3 of a slice (byte offset 12) is the
+ * unit's status word: nonzero means that a bounded in-kernel wait for the projection
+ * expired and the correction R A_i^T of that unit was LEFT OUT of Y (the output then
+ * equals that of a unit that is not restored).  The producers of R lead their launch
+ * and wait for nothing, so this happens only if workgroups of a launch are kept from
+ * running; the bound is there so that nothing can ever hang.  Status words stay set
+ * until glowq_workspace_init.  glowq_workspace_status counts them:
+ * it enqueues one small kernel that writes to *failed_units (DEVICE, 4-byte aligned)
+ * the number of the `n_units` units whose status word is nonzero; it allocates
+ * nothing and does not synchronise (read the word after the stream has run). */
 glowq_status glowq_workspace_bytes(const glowq_unit* units, int32_t n_units, size_t* bytes);
 glowq_status glowq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+glowq_status glowq_workspace_status(const glowq_unit* units, int32_t n_units,
+                                    const void* workspace, size_t workspace_bytes,
+                                    uint32_t* failed_units, void* stream);
 
 /* ---- the forward (Sec. 3.3) ------------------------------------------------
  * glowq_shared_proj: Eq. 8 alone.  R_out DEVICE fp32 [T][r] receives X B^T
@@ -145,11 +182,15 @@ glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,
                                  size_t workspace_bytes, void* stream);
 
 /* ---- inspection hooks (bit-exactness checks of the storage format) ---------
- * Both read the prepared layout of one module, the very words the forward
- * kernels multiply with.
+ * Both read the prepared layout of one module (the buffer the forward kernels
+ * stream) with small kernels of their own.
  * glowq_debug_unpack:  q_out DEVICE uint8 [d_out][d_in], values 0..15.
  * glowq_debug_dequant: w_out DEVICE act dtype [d_out][d_in],
- *                      round_to_act((q - z) * s), one rounding. */
+ *                      round_to_act((q - z) * s), one rounding, formed by the
+ *                      reference dequantiser of the library.  The forward kernels
+ *                      use instruction sequences of their own; what THEY multiply
+ *                      with can be read through a forward call whose X is rows of
+ *                      the identity and r = 0. */
 glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d_in,
                                 int32_t group_size, uint8_t* q_out, void* stream);
 glowq_status glowq_debug_dequant(const void* w_prepared, int32_t d_out, int32_t d_in,

@@ -68,6 +68,7 @@ def _load():
         "glowq_prepare_weights": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, vp, vp]),
         "glowq_workspace_bytes": (ctypes.c_int, [up, i32, ctypes.POINTER(sz)]),
         "glowq_workspace_init": (ctypes.c_int, [vp, sz, vp]),
+        "glowq_workspace_status": (ctypes.c_int, [up, i32, vp, sz, vp, vp]),
         "glowq_shared_proj": (ctypes.c_int, [up, vp, vp, sz, vp]),
         "glowq_group_forward": (ctypes.c_int, [up, i32, vp, sz, vp]),
         "glowq_block_forward": (ctypes.c_int, [up, i32, vp, vp, sz, vp]),
@@ -166,6 +167,15 @@ def glowq_workspace_bytes(units: Sequence[glowq_unit]) -> int:
 def glowq_workspace_init(workspace: int, workspace_bytes: int, stream: int = 0) -> None:
     _check(_lib.glowq_workspace_init(workspace or None, workspace_bytes, stream or None),
            "glowq_workspace_init")
+
+
+def glowq_workspace_status(units: Sequence[glowq_unit], workspace: int, workspace_bytes: int,
+                           failed_units: int, stream: int = 0) -> None:
+    """failed_units: address of a 4-byte device word that receives the count."""
+    arr = _units_array(units)
+    _check(_lib.glowq_workspace_status(arr, len(units), workspace or None, workspace_bytes,
+                                       failed_units or None, stream or None),
+           "glowq_workspace_status")
 
 
 def glowq_shared_proj(unit: glowq_unit, R_out: int, workspace: int, workspace_bytes: int,

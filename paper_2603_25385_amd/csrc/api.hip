@@ -48,40 +48,55 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   return w;
 }
 
-static glowq_status validate(const glowq_unit* u, bool ptrs) {
+// Sizes of one module's weights.  ERR_SHAPE: the sizes contradict the W4A16 storage
+// format itself (no such group size, d_in not a whole number of groups, nothing to do);
+// ERR_UNSUPPORTED: a well-formed request that the tile layout of this build cannot hold
+// (d_in not a multiple of the 128-channel tile, d_out not a multiple of 8).
+static glowq_status check_weights_shape(int d_out, int d_in, int G) {
+  if (G != 64 && G != 128) return GLOWQ_ERR_SHAPE;
+  if (d_in < G || d_in > (1 << 16) || d_in % G) return GLOWQ_ERR_SHAPE;
+  if (d_out < 1 || d_out > (1 << 20)) return GLOWQ_ERR_SHAPE;
+  if (d_in % 128 || d_out % 8) return GLOWQ_ERR_UNSUPPORTED;
+  return GLOWQ_OK;
+}
+
+// ptrs: also check the pointers; corrected: the unit's correction will be applied (a unit
+// that is masked off, or has r == 0, needs neither B nor any A_i)
+static glowq_status validate(const glowq_unit* u, bool ptrs, bool corrected) {
   if (!u) return GLOWQ_ERR_NULL;
   if (u->n_modules < 1 || u->n_modules > GLOWQ_MAX_MODULES) return GLOWQ_ERR_SHAPE;
   if (ptrs && !u->modules) return GLOWQ_ERR_NULL;
   if (u->T < 1 || u->T > (1 << 20)) return GLOWQ_ERR_SHAPE;
   if (u->group_size != 64 && u->group_size != 128) return GLOWQ_ERR_SHAPE;
-  if (u->d_in < 128 || u->d_in > (1 << 16) || u->d_in % 128) return GLOWQ_ERR_SHAPE;
-  if (u->r < 0 || u->r > GLOWQ_MAX_RANK || u->r % 8) return GLOWQ_ERR_SHAPE;
+  if (u->d_in < u->group_size || u->d_in > (1 << 16) || u->d_in % u->group_size) return GLOWQ_ERR_SHAPE;
+  if (u->r < 0) return GLOWQ_ERR_SHAPE;
   if (u->act_dtype != GLOWQ_F16 && u->act_dtype != GLOWQ_BF16) return GLOWQ_ERR_DTYPE;
   if (u->out_dtype != u->act_dtype && u->out_dtype != GLOWQ_F32) return GLOWQ_ERR_DTYPE;
+  if (u->modules)
+    for (int i = 0; i < u->n_modules; ++i) {
+      const glowq_module& m = u->modules[i];
+      if (m.d_out < 1 || m.d_out > (1 << 20) || m.ldy < m.d_out) return GLOWQ_ERR_SHAPE;
+    }
+  // well-formed from here on; what this build cannot serve
+  if (u->d_in % 128 || u->r > GLOWQ_MAX_RANK || u->r % 8) return GLOWQ_ERR_UNSUPPORTED;
   if (!u->modules) return GLOWQ_OK;   // shapes only
   for (int i = 0; i < u->n_modules; ++i) {
     const glowq_module& m = u->modules[i];
-    if (m.d_out < 8 || m.d_out > (1 << 20) || m.d_out % 8) return GLOWQ_ERR_SHAPE;
-    if (m.ldy < m.d_out || m.ldy % 8) return GLOWQ_ERR_SHAPE;
+    if (m.d_out % 8 || m.ldy % 8) return GLOWQ_ERR_UNSUPPORTED;
   }
   if (!ptrs) return GLOWQ_OK;
-  if (!u->X || (u->r > 0 && !u->B)) return GLOWQ_ERR_NULL;
+  const bool need_factors = corrected && u->r > 0;
+  if (!u->X || (need_factors && !u->B)) return GLOWQ_ERR_NULL;
   for (int i = 0; i < u->n_modules; ++i) {
     const glowq_module& m = u->modules[i];
-    if (!m.w_prepared || !m.Y || (u->r > 0 && !m.A)) return GLOWQ_ERR_NULL;
+    if (!m.w_prepared || !m.Y || (need_factors && !m.A)) return GLOWQ_ERR_NULL;
   }
-  if (misaligned(u->X) || misaligned(u->B)) return GLOWQ_ERR_ALIGN;
+  if (misaligned(u->X) || (need_factors && misaligned(u->B))) return GLOWQ_ERR_ALIGN;
   for (int i = 0; i < u->n_modules; ++i) {
     const glowq_module& m = u->modules[i];
-    if (misaligned(m.w_prepared) || misaligned(m.Y) || misaligned(m.A)) return GLOWQ_ERR_ALIGN;
+    if (misaligned(m.w_prepared) || misaligned(m.Y) || (need_factors && misaligned(m.A)))
+      return GLOWQ_ERR_ALIGN;
   }
-  return GLOWQ_OK;
-}
-
-static glowq_status check_weights_shape(int d_out, int d_in, int G) {
-  if (G != 64 && G != 128) return GLOWQ_ERR_SHAPE;
-  if (d_in < 128 || d_in > (1 << 16) || d_in % 128) return GLOWQ_ERR_SHAPE;
-  if (d_out < 8 || d_out > (1 << 20) || d_out % 8) return GLOWQ_ERR_SHAPE;
   return GLOWQ_OK;
 }
 
@@ -109,7 +124,7 @@ static glowq_status forward_all(const glowq_unit* units, int n_units, const uint
       while (i < n_units && nd < decode_max_batch() && nd < 32 && is_decode(units[i].T) &&
              (nd == 0 || decode_batch_compatible(*dbatch[0], units[i]))) {
         dbatch[nd] = &units[i];
-        dws[nd] = plan_unit_workspace(units[i], workspace + off);
+        dws[nd] = plan_unit_workspace(units[i], workspace ? workspace + off : nullptr);
         dcorr[nd] = (!mask || mask[i]) && units[i].r > 0;
         off += dws[nd].bytes;
         ++nd;
@@ -127,7 +142,7 @@ static glowq_status forward_all(const glowq_unit* units, int n_units, const uint
            (nb == 0 || prefill_compatible(*batch[0], units[i])) &&
            nmods + units[i].n_modules <= prefill_max_modules()) {
       batch[nb] = &units[i];
-      bws[nb] = plan_unit_workspace(units[i], workspace + off);
+      bws[nb] = plan_unit_workspace(units[i], workspace ? workspace + off : nullptr);
       corr[nb] = (!mask || mask[i]) && units[i].r > 0;
       off += bws[nb].bytes;
       nmods += units[i].n_modules;
@@ -164,7 +179,7 @@ const char* glowq_status_string(glowq_status s) {
 const char* glowq_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 glowq_status glowq_validate_unit(const glowq_unit* u, int32_t check_pointers) {
-  return validate(u, check_pointers != 0);
+  return validate(u, check_pointers != 0, true);
 }
 
 glowq_status glowq_prepared_bytes(int32_t d_out, int32_t d_in, int32_t group_size, size_t* bytes) {
@@ -192,7 +207,7 @@ glowq_status glowq_workspace_bytes(const glowq_unit* units, int32_t n_units, siz
   if (n_units < 1) return GLOWQ_ERR_SHAPE;
   size_t total = 0;
   for (int i = 0; i < n_units; ++i) {
-    glowq_status s = validate(&units[i], false);
+    glowq_status s = validate(&units[i], false, false);
     if (s != GLOWQ_OK) return s;
     total += plan_unit_workspace(units[i], nullptr).bytes;
   }
@@ -207,9 +222,38 @@ glowq_status glowq_workspace_init(void* workspace, size_t workspace_bytes, void*
   return hip_status(launch_fill_zero(workspace, workspace_bytes, (hipStream_t)stream));
 }
 
+glowq_status glowq_workspace_status(const glowq_unit* units, int32_t n_units,
+                                    const void* workspace, size_t workspace_bytes,
+                                    uint32_t* failed_units, void* stream) {
+  if (!units || !workspace || !failed_units) return GLOWQ_ERR_NULL;
+  if (n_units < 1) return GLOWQ_ERR_SHAPE;
+  if (misaligned(workspace) || ((uintptr_t)failed_units & 3u)) return GLOWQ_ERR_ALIGN;
+  size_t need = 0;
+  for (int i = 0; i < n_units; ++i) {
+    glowq_status s = validate(&units[i], false, false);
+    if (s != GLOWQ_OK) return s;
+    need += plan_unit_workspace(units[i], nullptr).bytes;
+  }
+  if (workspace_bytes < need || (need >> 8) > 0xffffffffull) return GLOWQ_ERR_WORKSPACE;
+  size_t off = 0;
+  bool first = true;
+  for (int i0 = 0; i0 < n_units; i0 += STATUS_BATCH) {
+    StatusBatch b;
+    b.n = n_units - i0 < STATUS_BATCH ? n_units - i0 : STATUS_BATCH;
+    for (int i = 0; i < STATUS_BATCH; ++i) {
+      b.off256[i] = (uint32_t)(off >> 8);
+      if (i < b.n) off += plan_unit_workspace(units[i0 + i], nullptr).bytes;
+    }
+    hipError_t e = launch_status_count(workspace, b, first, failed_units, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_status(e);
+    first = false;
+  }
+  return GLOWQ_OK;
+}
+
 glowq_status glowq_shared_proj(const glowq_unit* u, float* R_out, void* workspace,
                                size_t workspace_bytes, void* stream) {
-  glowq_status s = validate(u, true);
+  glowq_status s = validate(u, true, true);
   if (s != GLOWQ_OK) return s;
   if (u->r == 0) return GLOWQ_ERR_SHAPE;
   if (!R_out) return GLOWQ_ERR_NULL;
@@ -236,10 +280,11 @@ glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,
   size_t need = 0;
   bool any_corr = false;
   for (int i = 0; i < n_units; ++i) {
-    glowq_status s = validate(&units[i], true);
+    const bool corrected = units[i].r > 0 && (!restore_mask || restore_mask[i]);
+    glowq_status s = validate(&units[i], true, corrected);
     if (s != GLOWQ_OK) return s;
     need += plan_unit_workspace(units[i], nullptr).bytes;
-    if (units[i].r > 0 && (!restore_mask || restore_mask[i])) any_corr = true;
+    if (corrected) any_corr = true;
   }
   if (any_corr) {
     if (!workspace) return GLOWQ_ERR_WORKSPACE;

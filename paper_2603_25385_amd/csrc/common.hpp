@@ -4,6 +4,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "trace.hpp"
 
 namespace glowq {
 
@@ -103,17 +104,18 @@ __device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) {
 // weighs 1), the other four take the same two forms after one shift by 8; adding
 // -(1024 + z) or -(64 + z) cancels the offset and the zero-point in one packed add.
 __device__ inline u32x4_t q_minus_z_f16(uint32_t w, half2_t nb2, half2_t nb2b) {
-#ifdef GLOWQ_PROBE_NODEQ
-  return u32x4_t{w, w ^ 1u, w ^ 2u, w ^ 3u};
-#endif
   const uint32_t ws = w >> 8;
   u32x4_t out;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const uint32_t src = i < 2 ? w : ws;
     const uint32_t t = (i & 1) ? and_or(src, 0x00F000F0u, 0x54005400u) : and_or(src, 0x000F000Fu, 0x64006400u);
+#ifdef GLOWQ_EXP_NOADD
+    out[i] = t;
+#else
     const half2_t v = __builtin_bit_cast(half2_t, t) + ((i & 1) ? nb2b : nb2);
     out[i] = __builtin_bit_cast(uint32_t, v);
+#endif
   }
   return out;
 }
@@ -305,25 +307,10 @@ template <int N> __device__ inline void vm_wait() {
 __device__ inline void after_wait(u32x4_t& v) { asm volatile("" : "+v"(v)); }
 __device__ inline void after_wait32(uint32_t& v) { asm volatile("" : "+v"(v)); }
 
-// Optional stage timestamps (builds with -DGLOWQ_TRACE only): 100 MHz real-time counter
-// values per workgroup and stage, fetched with glowq_debug_trace().
-#ifdef GLOWQ_TRACE
-static __device__ unsigned long long g_trace[8192][8];   // one copy per translation unit
-#define GLOWQ_STAMP(slot)                                                         \
-  do {                                                                            \
-    const unsigned b_ = blockIdx.x + blockIdx.y * gridDim.x;                      \
-    if (threadIdx.x == 0 && b_ < 8192)                                            \
-      g_trace[b_][slot] = __builtin_amdgcn_s_memrealtime();                       \
-  } while (0)
-#else
-#define GLOWQ_STAMP(slot) do { } while (0)
-#endif
-
 // Control words at the head of a unit's workspace slice.
 struct Control {
-  unsigned long long reserved0;
-  uint32_t reserved1;
-  uint32_t status;           // nonzero: a bounded wait expired (cannot happen: producers wait for nothing)
+  uint32_t unused[3];
+  uint32_t status;           // word 3; nonzero: a bounded wait expired and the unit's correction was left out
   uint32_t pad[12];
 };
 

@@ -109,7 +109,6 @@ int fill_decode_args(const glowq_unit& u, const UnitWorkspace& ws, bool restore,
   for (int i = u.n_modules; i < GLOWQ_MAX_MODULES; ++i) a.mod[i] = a.mod[0];
   a.n_modules = u.n_modules;
   a.X = (const uint16_t*)u.X;
-  a.R16 = (const uint16_t*)(ws.base + ws.off_r16);
   a.T = u.T;
   a.K = u.d_in;
   a.r = u.r;
@@ -142,11 +141,9 @@ static hipError_t launch_decode_small(const glowq_unit* const* units, const Unit
       b.p[i] = ProjArgs{};
       b.n_prod[i] = 0;
       b.a[i].ctl = (Control*)ws[i].base;
-      b.a[i].in_launch_proj = 0;
       if (restore[i]) {
         b.p[i] = make_proj_args(u, ws[i], nullptr, true);
         b.n_prod[i] = (u.r * ws[i].ksplit + DEC_WAVES - 1) / DEC_WAVES;   // one wave per (rank, part)
-        b.a[i].in_launch_proj = 1;
       }
       b.wg_start[i] = wg;
       if (decode_small_merged(decode_small_class(u0.T))) wg += b.n_prod[i] > blocks ? b.n_prod[i] : blocks;
@@ -199,11 +196,9 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
     ProjArgs p = {};
     int n_prod = 0;
     a.ctl = (Control*)ws[i].base;
-    a.in_launch_proj = 0;
     if (restore[i]) {
       p = make_proj_args(u, ws[i], nullptr, true);
       n_prod = ((u.T + 15) / 16) * ws[i].ksplit;
-      a.in_launch_proj = 1;
     }
     dim3 grid((unsigned)(n_prod + (blocks + DEC_RG - 1) / DEC_RG));
     if (u.T <= 16) {
@@ -221,9 +216,4 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
 
 }  // namespace glowq
 
-#ifdef GLOWQ_TRACE
-// stage timestamps of the decode kernels' most recent launch (tracing builds only)
-extern "C" int glowq_debug_trace(unsigned long long* host_out /* [8192][8] */) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(glowq::g_trace), sizeof(glowq::g_trace));
-}
-#endif
+GLOWQ_TRACE_EXPORT(glowq_debug_trace)

@@ -21,13 +21,9 @@ struct DecodeArgs {
   ModuleArgs mod[GLOWQ_MAX_MODULES];
   int n_modules;
   const uint16_t* X;
-  const uint16_t* R16;
   int T, K, r, G;
   int restore, out_f32;
-  // single-launch mode: the projection runs in the first workgroups of the same grid
-  Control* ctl;        // control words of the unit's workspace slice
-  int in_launch_proj;  // 1: wait for this launch's tag before reading R; 0: R is already
-                       // in memory when the kernel starts
+  Control* ctl;        // control words of the unit's workspace slice (null if not restored)
 };
 
 // One tile (16 rows x 128 channels) against TBK blocks of 16 tokens.
@@ -405,9 +401,7 @@ __device__ inline bool r_fetch_finish(const ProjArgs& p, RFetch& f, u32x4_t& rf)
     if (!f.on) ok = true;
     if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) {
       done = true;
-#ifdef GLOWQ_TRACE
-      if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace[blockIdx.x][5] = (unsigned long long)(spin + 1);
-#endif
+      GLOWQ_TRACE_VALUE(5, spin + 1);
       break;
     }
     __builtin_amdgcn_s_sleep(32);
@@ -640,13 +634,7 @@ __device__ inline void decode_workgroup_small(const DecodeArgs& a, const ProjArg
 
   float4_t acc[1] = {float4_t{0.f, 0.f, 0.f, 0.f}};
   GLOWQ_STAMP(0);
-#ifdef GLOWQ_TRACE
-  if (threadIdx.x == 0 && blockIdx.x < 8192) {
-    unsigned hw = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));    // HW_ID
-    unsigned xcc = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));  // XCC_ID
-    g_trace[blockIdx.x][7] = ((unsigned long long)xcc << 32) | hw;
-  }
-#endif
+  GLOWQ_TRACE_HWID(7);
   const CorrFrag cf = correction_prefetch(a, M, rb, wave, lane);
   RFetch rfetch;
   r_fetch_plan(a, p, cf.j0c, a.restore && cf.active && cf.ok, lane, rfetch);

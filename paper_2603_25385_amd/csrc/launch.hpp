@@ -10,13 +10,14 @@ namespace glowq {
 struct UnitWorkspace {
   char* base;         // start of the slice (256-byte aligned)
   size_t bytes;       // size of the slice
-  size_t off_counters;  // uint32 per 32-token block of the projection
-  size_t off_rpart;   // fp32 [T][r][ksplit rounded up to 4]
-  size_t off_r16;     // act dtype [T][r]
+  size_t off_counters;  // T > 32: per token tile, a ready flag and an arrival counter of K parts
+  size_t off_rpart;   // partial sums of the projection (T <= 32: 8-byte slots {fp32, launch tag},
+                      // [T][ksplit][r]; T > 32 and glowq_shared_proj: fp32 [part][T][r])
+  size_t off_r16;     // T > 32: R in the activation type, [T][r]
   size_t ctl_bytes;   // leading bytes that must be zero between calls
   int ksplit;         // K slices of the projection
   int kslice;         // channels per slice (multiple of 32)
-  int kstride;        // elements between the slice arrays of two outputs in the partial-sum area
+  int kstride;        // ksplit rounded up to a multiple of 4 (sizes the partial-sum area)
   int pf_parts;       // T > 32: K parts of a projection tile inside the GEMM launch
   int pf_part_stages; // 64-channel stages per such part
 };
@@ -33,12 +34,20 @@ hipError_t launch_debug_unpack(const void* prepared, int d_out, int d_in, int G,
 hipError_t launch_debug_dequant(const void* prepared, int d_out, int d_in, int G, int act,
                                 void* w_out, hipStream_t st);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+// slices' start offsets in units of 256 bytes (every slice is 256-byte aligned)
+constexpr int STATUS_BATCH = 256;
+struct StatusBatch {
+  uint32_t off256[STATUS_BATCH];
+  int n;
+};
+hipError_t launch_status_count(const void* ws, const StatusBatch& b, bool first, uint32_t* out,
+                               hipStream_t st);
 
 struct ProjArgs;
 ProjArgs make_proj_args(const glowq_unit& u, const UnitWorkspace& ws, float* R32, bool want_r16);
 
-// R = X B^T: fp32 partial sums per K slice, reduced by the last workgroup of each
-// 32-token block into R32 (optional) and R16 (optional).
+// R = X B^T, stand-alone: fp32 partial sums per K slice, then a second launch adds them in
+// slice order into R32 (optional) and R16 (optional).
 hipError_t launch_proj(const glowq_unit& u, const UnitWorkspace& ws, float* R32, bool want_r16,
                        hipStream_t st);
 // T <= 32: streaming pass over the prepared weights; when restore, the projection runs

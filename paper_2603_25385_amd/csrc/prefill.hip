@@ -451,9 +451,6 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   DQ dq;
 
   GLOWQ_STAMP(0);
-#ifdef GLOWQ_TRACE
-  const unsigned long long clk0 = __builtin_amdgcn_s_memtime();
-#endif
   if (tid == 0) corr_failed = 0;       // ordered before its readers by the loop's barriers
 #pragma unroll
   for (int i = 0; i < XI; ++i) dma_x(0, 0, i);
@@ -483,10 +480,6 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   // ahead and sit in the first slices of a stage.
   int slot_cur = 0, slot_next2 = 2;   // ring slots of the stage being read and of stage+2
   for (int kt = 0; kt < ktiles; ++kt) {
-#ifdef GLOWQ_TRACE
-    if (kt == 8) GLOWQ_STAMP(2);
-    if (kt == 16) GLOWQ_STAMP(3);
-#endif
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int stage = 2 * kt + half;
@@ -574,9 +567,6 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   GLOWQ_STAMP(4);
-#ifdef GLOWQ_TRACE
-  if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace[blockIdx.x][7] = __builtin_amdgcn_s_memtime() - clk0;
-#endif
   // correction: r more channels in stages of 64, operand [A_i] against [R].  The A words
   // do not depend on the projection and are asked for before its flag is looked at; the
   // R tile then takes the X path (straight into the idle ring, swizzled the same way,
@@ -737,10 +727,12 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
     PfUnit& pu = a.unit[oi];
     pu.X = (const uint16_t*)u.X;
     pu.B = (const uint16_t*)u.B;
-    pu.R16 = (uint16_t*)(ws[ui].base + ws[ui].off_r16);
-    pu.Rpart = (float*)(ws[ui].base + ws[ui].off_rpart);
-    pu.flags = (uint32_t*)(ws[ui].base + ws[ui].off_counters);
-    pu.status = &((Control*)ws[ui].base)->status;
+    // (a call without any restored unit may come without a workspace)
+    char* wsb = ws[ui].base;
+    pu.R16 = wsb ? (uint16_t*)(wsb + ws[ui].off_r16) : nullptr;
+    pu.Rpart = wsb ? (float*)(wsb + ws[ui].off_rpart) : nullptr;
+    pu.flags = wsb ? (uint32_t*)(wsb + ws[ui].off_counters) : nullptr;
+    pu.status = wsb ? &((Control*)wsb)->status : nullptr;
     pu.T = u.T;
     pu.K = u.d_in;
     pu.r = u.r;
@@ -775,9 +767,4 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
 
 }  // namespace glowq
 
-#ifdef GLOWQ_TRACE
-// stage timestamps of the prefill kernel's most recent launch (tracing builds only)
-extern "C" int glowq_debug_trace_prefill(unsigned long long* host_out /* [8192][8] */) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(glowq::g_trace), sizeof(glowq::g_trace));
-}
-#endif
+GLOWQ_TRACE_EXPORT(glowq_debug_trace_prefill)

@@ -2,8 +2,9 @@
 //
 // prepare:       canonical W4A16 arrays -> tiled layout the forward kernels read
 // debug_unpack:  tiled layout -> q[d_out][d_in] bytes
-// debug_dequant: tiled layout -> round_to_act((q - z) * s), through the very
-//                dequant_word() the forward kernels feed the matrix cores with
+// debug_dequant: tiled layout -> round_to_act((q - z) * s) through dequant_word(), the
+//                library's reference dequantiser (the forward kernels schedule
+//                instruction sequences of their own, checked through forward calls)
 #include "common.hpp"
 #include "launch.hpp"
 

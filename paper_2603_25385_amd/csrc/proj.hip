@@ -14,8 +14,8 @@
 
 namespace glowq {
 
-// Stand-alone projection, used ahead of the prefill GEMM and by glowq_shared_proj: a
-// partial-sum kernel over (16-token block, K slice) followed by a reduce kernel.  Two
+// Stand-alone projection, used by glowq_shared_proj only (the forward kernels run their
+// projection inside their own launch): a partial-sum kernel over (16-token block, K slice) followed by a reduce kernel.  Two
 // plain launches instead of fences and arrival counters: at these sizes the second
 // launch costs a few microseconds and every store stays an ordinary cached store.
 template <int ACT>
@@ -89,6 +89,28 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Counts the unit slices whose status word (word 3) is nonzero.  One launch looks at up
+// to STATUS_BATCH slices; `first` says whether this launch starts the count.
+__global__ void k_status_count(const char* ws, StatusBatch b, int first, uint32_t* out) {
+  __shared__ uint32_t n_bad;
+  if (threadIdx.x == 0) n_bad = 0;
+  __syncthreads();
+  const int i = (int)threadIdx.x;
+  if (i < b.n) {
+    const uint32_t* slice = (const uint32_t*)(ws + ((size_t)b.off256[i] << 8));
+    if (__hip_atomic_load(slice + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
+      atomicAdd(&n_bad, 1u);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) *out = (first ? 0u : *out) + n_bad;
+}
+
+hipError_t launch_status_count(const void* ws, const StatusBatch& b, bool first, uint32_t* out,
+                               hipStream_t st) {
+  k_status_count<<<dim3(1), dim3(STATUS_BATCH), 0, st>>>((const char*)ws, b, first ? 1 : 0, out);
+  return hipGetLastError();
+}
+
 ProjArgs make_proj_args(const glowq_unit& u, const UnitWorkspace& ws, float* R32, bool want_r16) {
   ProjArgs a;
   a.X = (const uint16_t*)u.X;
@@ -98,13 +120,10 @@ ProjArgs make_proj_args(const glowq_unit& u, const UnitWorkspace& ws, float* R32
   a.r = u.r;
   a.ksplit = ws.ksplit;
   a.kslice = ws.kslice;
-  a.kstride = ws.kstride;
   a.Rpart = (float*)(ws.base + ws.off_rpart);
   a.R32 = R32;
   a.R16 = want_r16 ? (uint16_t*)(ws.base + ws.off_r16) : nullptr;
   a.ctl = (Control*)ws.base;
-  a.counters = (uint32_t*)(ws.base + ws.off_counters);
-  a.tblocks = (u.T + 15) / 16;
   return a;
 }
 
@@ -135,8 +154,4 @@ hipError_t launch_proj(const glowq_unit& u, const UnitWorkspace& ws, float* R32,
 
 }  // namespace glowq
 
-#ifdef GLOWQ_TRACE
-extern "C" int glowq_debug_trace_proj(unsigned long long* host_out /* [8192][8] */) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(glowq::g_trace), sizeof(glowq::g_trace));
-}
-#endif
+GLOWQ_TRACE_EXPORT(glowq_debug_trace_proj)

@@ -12,14 +12,11 @@ struct ProjArgs {
   int T, K, r;
   int ksplit;          // K slices
   int kslice;          // channels per slice, multiple of 32
-  int kstride;         // ksplit rounded up to a multiple of 4
   float* Rpart;        // stand-alone projection: fp32 [slice][T][r]; in-launch projection
                        // of the decode kernels: 8-byte slots {fp32 bits, launch tag}
   float* R32;          // optional fp32 [T][r]
   uint16_t* R16;       // optional act dtype [T][r]
-  Control* ctl;
-  uint32_t* counters;  // one word per 16-token block (ready flags of the prefill tiles)
-  int tblocks;         // 16-token blocks of the unit
+  Control* ctl;        // control words of the unit's workspace slice
 };
 
 // One workgroup = (16-token block tb, K slice kz); any whole number of waves.

@@ -10,6 +10,7 @@ import paper_2603_25385_amd as G
 
 ACT_CODE = {"f16": G.GLOWQ_F16, "bf16": G.GLOWQ_BF16, "f32": G.GLOWQ_F32}
 TORCH_ACT = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}
+GUARD_ROWS = 2
 
 
 def dev_bits(bits: np.ndarray) -> torch.Tensor:
@@ -56,8 +57,11 @@ class DeviceUnit:
         self.B = None if self.r == 0 else _as_dev16(unit["B"])
         self.modules = [DeviceModule(m, self.d_in, self.Gs) for m in unit["modules"]]
         self.out = self.act if out == "act" else out
-        self.Y = [torch.full((self.T, m.d_out + ldy_pad), float("nan"), dtype=TORCH_ACT[self.out],
-                             device="cuda") for m in self.modules]
+        # every output buffer carries canaries: `ldy_pad` columns to the right of the rows
+        # and GUARD_ROWS rows below them, all NaN, which no call may touch
+        self.Ybuf = [torch.full((self.T + GUARD_ROWS, m.d_out + ldy_pad), float("nan"),
+                                dtype=TORCH_ACT[self.out], device="cuda") for m in self.modules]
+        self.Y = [b[:self.T] for b in self.Ybuf]
         self.desc = self.describe()
 
     def describe(self, T=None, r=None, X=None):
@@ -69,14 +73,20 @@ class DeviceUnit:
                            self.T if T is None else T, self.d_in, self.r if r is None else r,
                            self.Gs, ACT_CODE[self.act], ACT_CODE[self.out])
 
-    def outputs(self):
+    def outputs(self, T=None):
+        """Outputs of the last call (rows of the first T tokens if the call was made for
+        fewer tokens than the buffers hold); asserts that the canaries are intact."""
         torch.cuda.synchronize()
-        return [y[:, :m.d_out].to(torch.float64).cpu().numpy()
+        T = self.T if T is None else T
+        for b, m in zip(self.Ybuf, self.modules):
+            assert torch.isnan(b[:, m.d_out:]).all(), "padding columns of Y were written"
+            assert torch.isnan(b[T:]).all(), "rows past T of Y were written"
+        return [y[:T, :m.d_out].to(torch.float64).cpu().numpy()
                 for y, m in zip(self.Y, self.modules)]
 
     def clear(self):
-        for y in self.Y:
-            y.fill_(float("nan"))
+        for b in self.Ybuf:
+            b.fill_(float("nan"))
 
 
 class Workspace:

@@ -42,10 +42,13 @@ def test_valid_unit_passes():
     (dict(wp=0), G.GLOWQ_ERR_NULL), (dict(Y=0), G.GLOWQ_ERR_NULL),
     (dict(X=0x1008), G.GLOWQ_ERR_ALIGN), (dict(Y=0x5004), G.GLOWQ_ERR_ALIGN),
     (dict(T=0), G.GLOWQ_ERR_SHAPE), (dict(d_in=200), G.GLOWQ_ERR_SHAPE),
-    (dict(group_size=32), G.GLOWQ_ERR_SHAPE), (dict(r=12), G.GLOWQ_ERR_SHAPE),
-    (dict(r=136), G.GLOWQ_ERR_SHAPE), (dict(d_out=60), G.GLOWQ_ERR_SHAPE),
-    (dict(ldy=56), G.GLOWQ_ERR_SHAPE), (dict(ldy=68), G.GLOWQ_ERR_SHAPE),
+    (dict(group_size=32), G.GLOWQ_ERR_SHAPE), (dict(r=-8), G.GLOWQ_ERR_SHAPE),
+    (dict(d_out=0), G.GLOWQ_ERR_SHAPE), (dict(ldy=56), G.GLOWQ_ERR_SHAPE),
     (dict(n=0), G.GLOWQ_ERR_SHAPE), (dict(n=9), G.GLOWQ_ERR_SHAPE),
+    # well formed, but outside what the tile layout of this build holds
+    (dict(d_in=192), G.GLOWQ_ERR_UNSUPPORTED), (dict(d_in=320, group_size=64), G.GLOWQ_ERR_UNSUPPORTED),
+    (dict(r=12), G.GLOWQ_ERR_UNSUPPORTED), (dict(r=136), G.GLOWQ_ERR_UNSUPPORTED),
+    (dict(d_out=60), G.GLOWQ_ERR_UNSUPPORTED), (dict(ldy=68), G.GLOWQ_ERR_UNSUPPORTED),
     (dict(act=G.GLOWQ_F32), G.GLOWQ_ERR_DTYPE), (dict(act=G.GLOWQ_F16, out=G.GLOWQ_BF16), G.GLOWQ_ERR_DTYPE),
 ])
 def test_bad_units_are_rejected(kw, status):
@@ -75,5 +78,34 @@ def test_workspace_and_misc_errors():
     with pytest.raises(G.GlowqError) as e:
         G.glowq_prepared_bytes(64, 250, 64)
     assert e.value.status == G.GLOWQ_ERR_SHAPE
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_prepared_bytes(64, 192, 64)
+    assert e.value.status == G.GLOWQ_ERR_UNSUPPORTED
     assert G.glowq_prepared_bytes(40, 128, 128) == 3 * 1 * 272 * 4
     assert "NULL" in G.glowq_status_string(G.GLOWQ_ERR_NULL)
+
+
+def test_unit_that_is_not_restored_needs_no_factors():
+    """A masked unit reads neither B nor any A_i, so they may be NULL; with no restored
+    unit in the call the workspace may be NULL as well.  (Checked on the host through a
+    deliberately failing later argument: the call must get PAST the factor checks.)"""
+    u = _unit(B=0, A=0)
+    assert G.glowq_validate_unit(u) == G.GLOWQ_ERR_NULL          # as a restored unit
+    bad = _unit(B=0, A=0, Y=0x5004)                              # misaligned Y comes later
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_group_forward(bad, False, 0, 0, 0)
+    assert e.value.status == G.GLOWQ_ERR_ALIGN
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_group_forward(u, True, 0x9000, 1 << 20, 0)
+    assert e.value.status == G.GLOWQ_ERR_NULL
+
+
+def test_workspace_status_argument_checks():
+    u = _unit()
+    need = G.glowq_workspace_bytes([u])
+    for args, status in [((0x9000, need, 0), G.GLOWQ_ERR_NULL), ((0, need, 0x8000), G.GLOWQ_ERR_NULL),
+                         ((0x9000, need, 0x8002), G.GLOWQ_ERR_ALIGN),
+                         ((0x9000, need - 1, 0x8000), G.GLOWQ_ERR_WORKSPACE)]:
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_workspace_status([u], *args)
+        assert e.value.status == status

@@ -44,13 +44,26 @@ def test_ragged_group(act, T):
     _check(ys16, O.group_forward(u, True), TOL + ULP[act])
 
 
-@pytest.mark.parametrize("r", [8, 16, 32, 64, 128])
+@pytest.mark.parametrize("r", [8, 16, 24, 32, 40, 64, 72, 120, 128])
 @pytest.mark.parametrize("T", [2, 12, 32, 48])
 def test_every_rank(r, T):
     shape = UnitShape("g", 256, (128, 64))
     u = recipe_unit(O, 1, 0, T, r=r, shape=shape, G=64)
     ys, _, _ = run_group(u, True)
     _check(ys, O.group_forward(u, True), TOL)
+
+
+@pytest.mark.parametrize("T", [1, 3, 4, 20, 32, 70, 200])
+def test_bf16_with_group_size_64(T):
+    # bfloat16 activations with two quantisation groups per 128-channel tile, ragged rows
+    shape = UnitShape("g", 384, (40, 264, 96))
+    u = recipe_unit(O, 1, 0, T, r=24, shape=shape, act="bf16", G=64)
+    ys, _, _ = run_group(u, True, ldy_pad=8)
+    _check(ys, O.group_forward(u, True), TOL)
+    ys16, _, _ = run_group(u, True, out="act")
+    _check(ys16, O.group_forward(u, True), TOL + ULP["bf16"])
+    off, _, _ = run_group(u, False, ldy_pad=16)
+    _check(off, O.group_forward(u, False), TOL)
 
 
 @pytest.mark.parametrize("act", ["f16", "bf16"])
@@ -114,7 +127,7 @@ def test_token_independence_across_kernel_paths():
         ut = dict(u, X=u["X"][t:t + 1], T=1)
         one, _, _ = run_group(ut, True)
         for a, b in zip(many, one):
-            assert rel_err(b[0], a[t]) <= 1.5e-3
+            assert rel_err(b[0], a[t]) <= 4e-4
 
 
 def test_block_forward_with_mask():

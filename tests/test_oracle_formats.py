@@ -215,3 +215,37 @@ def test_dequant_group_index_runs_along_input_dim():
     w = O.dequant(q, s, z, 128, "f16")
     assert np.all(w[0, :128] == 1.0) and np.all(w[0, 128:] == 4.0)
     assert np.all(w[1, :128] == 12.0) and np.all(w[1, 128:] == 32.0)
+
+
+# --------------------------------------------------------------------------
+# the row-chunk helper: the threaded branch returns what the single-chunk branch returns
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("n_rows", [1, 255, 256, 511, 512, 1000, 1025, 4097, 5000])
+def test_row_chunks_cover_every_row_once_in_order(n_rows):
+    parts = O._by_row_chunks(lambda lo, hi: (lo, hi), n_rows)
+    assert parts[0][0] == 0 and parts[-1][1] == n_rows
+    for (lo, hi), (lo2, _) in zip(parts, parts[1:]):
+        assert lo < hi == lo2
+    if n_rows >= 512 and (os.cpu_count() or 1) > 1:
+        assert len(parts) > 1            # the threaded branch really ran
+
+
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+def test_threaded_rows_equal_single_chunk_rows(act):
+    """quantize_rtn / dequant_bits / dequant on 1536 + 40 rows (several chunks, a ragged
+    last one) equal, row for row, the same functions applied to slices short enough to
+    take the single-chunk branch."""
+    rng = np.random.default_rng(11)
+    n_rows, d, G = 1576, 256, 64
+    W = (rng.standard_normal((n_rows, d)) * 0.02).astype(np.float32)
+    q, s_bits, z_bits = O.quantize_rtn(W, G)
+    wb = O.dequant_bits(q, s_bits, z_bits, G, act)
+    wf = O.dequant(q, s_bits, z_bits, G, act)
+    assert q.shape == (n_rows, d) and s_bits.shape == (n_rows, d // G) and wb.shape == (n_rows, d)
+    for lo in range(0, n_rows, 200):                 # 200 < 256: one chunk, no threads
+        hi = min(n_rows, lo + 200)
+        q1, s1, z1 = O.quantize_rtn(W[lo:hi], G)
+        assert np.array_equal(q[lo:hi], q1)
+        assert np.array_equal(s_bits[lo:hi], s1) and np.array_equal(z_bits[lo:hi], z1)
+        assert np.array_equal(wb[lo:hi], O.dequant_bits(q1, s1, z1, G, act))
+        assert np.array_equal(wf[lo:hi], O.dequant(q1, s1, z1, G, act))
