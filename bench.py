@@ -7,15 +7,23 @@ A step is one pass of the whole hot path (projection R = X B^T once per unit,
 then Y_i = X dequant(W_q,i)^T + R A_i^T for every module, restore mask applied)
 over one batch of seeded synthetic input that is already resident in HBM.  The
 read-only operands are rotated over several distinct copies so that consecutive
-steps do not find their weights in the 256 MB Infinity Cache.  The default
-workload is the Llama-2-7B-shaped QKV group at one token (decode); others are
-selectable with --workload.  Prints ONE JSON line.
+steps do not find their weights in the 256 MB Infinity Cache.
+
+Without --workload the run times BOTH halves of the metric in one process: the
+Llama-2-7B-shaped QKV group at one token (decode, HBM GB/s: the headline `value`)
+and the Llama-2-7B-shaped gate/up group at 2048 tokens (prefill, TFLOP/s: the
+`prefill` object of the same JSON line).  Every workload is timed as R replays of
+K steps (median and minimum reported), once more on a single operand set that stays
+cache resident (labelled `hot`), and is then checked: no unit may have dropped its
+correction (status words) and unit 0's output must match the CPU oracle.
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import platform
 import sys
 import time
 
@@ -24,6 +32,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 / bf16 matrix throughput
+REPLAYS = 5
+TOL = 2e-3                     # max relative error of the outputs (fp32 accumulation)
+ULP = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8}
 
 # name -> (config id, T, bound)
 WORKLOADS = {
@@ -39,7 +50,13 @@ WORKLOADS = {
     "cfg1": (1, 16, "hbm"),
     # calibration of the HBM traffic counters: a plain device copy of 256 MiB
     "copy256": (0, 0, "copy"),
+    # measured ceilings (no part of the method): one launch that only reads 24 MiB with
+    # 128-bit loads, and a register-resident loop of 16x16x32 matrix instructions
+    "stream24": (0, 0, "stream"),
+    "mfma_f16": (0, 0, "mfma_probe"),
+    "mfma_bf16": (0, 0, "mfma_probe"),
 }
+METRIC = "grouped W4+low-rank forward: decode HBM GB/s & us/group; prefill TFLOP/s"
 
 
 def unit_cost(shape, T, r, G, restored):
@@ -54,39 +71,68 @@ def unit_cost(shape, T, r, G, restored):
     return by, fl
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="cfg2_T1", choices=sorted(WORKLOADS))
-    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
-                    help="graph: the K timed steps are captured once into a HIP graph")
-    ap.add_argument("--rot", type=int, default=None, help="distinct operand copies to rotate over")
-    ap.add_argument("--layers", type=int, default=None, help="cfg5 only: layers to instantiate")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--restore", default="workload", choices=["workload", "none", "all"],
-                    help="restore mask: the workload's own (default), no unit, or every unit "
-                         "(to price the correction; the JSON line says how many units were restored)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(no collective is part of the path: units are independent and would be sharded "
-              "whole, one process per GPU)", file=sys.stderr)
-        return 2
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return platform.processor() or "unknown"
 
+
+def rel_err(y, y_ref):
+    """max |y - y_ref| / max(|y_ref|, rms(y_ref))"""
     import numpy as np
-    import torch
+    y, y_ref = np.asarray(y, np.float64), np.asarray(y_ref, np.float64)
+    rms = float(np.sqrt(np.mean(y_ref ** 2))) or 1.0
+    return float(np.max(np.abs(y - y_ref) / np.maximum(np.abs(y_ref), rms)))
+
+
+def time_steps(torch, step, steps, mode, replays):
+    """Event-timed milliseconds per step of `replays` runs of `steps` steps each."""
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out, wall = [], []
+    if mode == "graph":
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(steps):
+                    step(i)
+            graph.replay()               # one untimed replay
+            torch.cuda.synchronize()
+            for _ in range(replays):
+                t0 = time.perf_counter()
+                ev0.record(side)
+                graph.replay()
+                ev1.record(side)
+                torch.cuda.synchronize()
+                wall.append((time.perf_counter() - t0) * 1e3 / steps)
+                out.append(ev0.elapsed_time(ev1) / steps)
+    else:
+        for _ in range(replays):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev0.record()
+            for i in range(steps):
+                step(i)
+            ev1.record()
+            torch.cuda.synchronize()
+            wall.append((time.perf_counter() - t0) * 1e3 / steps)
+            out.append(ev0.elapsed_time(ev1) / steps)
+    return out, wall
+
+
+def run_workload(name, args, torch, want_cpu_baseline):
+    import numpy as np
 
     import paper_2603_25385_amd as G
     from glowq_inputs import CONFIGS, config_units, gen_direct_unit, gen_restore_mask
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
     dev = "cuda"
-    cfg_id, T, bound = WORKLOADS[args.workload]
-    if bound == "copy":
-        return copy_calibration(torch, args)
+    cfg_id, T, bound = WORKLOADS[name]
     cfg = CONFIGS[cfg_id]
     r, Gs, act = cfg["r"], cfg["G"], cfg["act"]
     shapes = config_units(cfg_id)
@@ -114,24 +160,21 @@ def main() -> int:
     tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[act]
     st = torch.cuda.current_stream().cuda_stream
     keep = []               # device buffers stay alive here
-    host_unit0 = None       # host copy of unit 0 for the CPU baseline
+    host_unit0 = None       # host copy of unit 0, rotation 0, for the oracle
+    y_unit0 = None          # its output buffers
 
     def build_rotation(rot):
-        nonlocal host_unit0
+        nonlocal host_unit0, y_unit0
         descs = []
         for ui, shape in enumerate(shapes):
             src = gen_direct_unit(cfg["seed"], ui, shape, T, r, Gs, act, device=dev)
-            if rot == 0 and ui == 0 and not args.no_cpu_baseline:
+            if rot == 0 and ui == 0:
+                b16 = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
                 host_unit0 = dict(
-                    X=src["X"].view(torch.int16).cpu().numpy().view(np.uint16),
-                    B=src["B"].view(torch.int16).cpu().numpy().view(np.uint16),
-                    act=act, G=Gs, r=r, d_in=shape.d_in, T=T,
-                    modules=[dict(wq=m["wq"].cpu().numpy().view(np.uint32),
-                                  scales=m["scales"].view(torch.int16).cpu().numpy().view(np.uint16),
-                                  zeros=m["zeros"].view(torch.int16).cpu().numpy().view(np.uint16),
-                                  A=m["A"].view(torch.int16).cpu().numpy().view(np.uint16))
-                             for m in src["modules"]])
-            mods = []
+                    X=b16(src["X"]), B=b16(src["B"]), act=act, G=Gs, r=r, d_in=shape.d_in, T=T,
+                    modules=[dict(wq=m["wq"].cpu().numpy().view(np.uint32), scales=b16(m["scales"]),
+                                  zeros=b16(m["zeros"]), A=b16(m["A"])) for m in src["modules"]])
+            mods, ys = [], []
             for m in src["modules"]:
                 nb = G.glowq_prepared_bytes(m["d_out"], shape.d_in, Gs)
                 prep = torch.empty(nb, dtype=torch.uint8, device=dev)
@@ -140,8 +183,11 @@ def main() -> int:
                                         prep.data_ptr(), st)
                 Y = torch.empty((T, m["d_out"]), dtype=tdt, device=dev)
                 keep.extend([prep, m["A"], Y])
+                ys.append(Y)
                 mods.append(G.make_module(prep.data_ptr(), m["A"].data_ptr(), Y.data_ptr(),
                                           m["d_out"], m["d_out"]))
+            if rot == 0 and ui == 0:
+                y_unit0 = ys
             keep.extend([src["X"], src["B"]])
             descs.append(G.make_unit(src["X"].data_ptr(), src["B"].data_ptr(), mods, T,
                                      shape.d_in, r, Gs, act_code, act_code))
@@ -163,38 +209,27 @@ def main() -> int:
         G.glowq_block_forward(rotations[i % n_rot], cmask, ws.data_ptr(), ws_bytes,
                               torch.cuda.current_stream().cuda_stream)
 
+    def step_hot(i):
+        G.glowq_block_forward(rotations[0], cmask, ws.data_ptr(), ws_bytes,
+                              torch.cuda.current_stream().cuda_stream)
+
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
+    ms, wall = time_steps(torch, step, steps, args.mode, REPLAYS)
+    ms_hot, _ = time_steps(torch, step_hot, steps, args.mode, 2)
+    ms_per_step = float(np.median(ms))
 
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    if args.mode == "graph":
-        side = torch.cuda.Stream()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(steps):
-                    step(i)
-            graph.replay()               # one untimed replay
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            ev0.record(side)
-            graph.replay()
-            ev1.record(side)
-            torch.cuda.synchronize()
-            wall = time.perf_counter() - t0
-    else:
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        ev0.record()
-        for i in range(steps):
-            step(i)
-        ev1.record()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-    ev_ms = ev0.elapsed_time(ev1)
-    ms_per_step = max(ev_ms, 0.0) / steps
-    wall_ms_per_step = wall * 1e3 / steps
+    # after the timed region: no unit dropped its correction, and unit 0 matches the oracle
+    failed = torch.zeros(1, dtype=torch.int32, device=dev)
+    G.glowq_workspace_status(rotations[0], ws.data_ptr(), ws_bytes, failed.data_ptr(), st)
+    for ys in [y_unit0]:
+        for y in ys:
+            y.fill_(float("nan"))
+    step_hot(0)
+    torch.cuda.synchronize()
+    n_failed = int(failed.item())
+    parity = check_against_oracle(host_unit0, y_unit0, shapes[0], T, bool(mask[0]), decode, act)
 
     gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
     tfs = alg_flops / (ms_per_step * 1e-3) / 1e12
@@ -207,29 +242,156 @@ def main() -> int:
         roof = dict(bound="mfma", achieved=tfs, peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=tfs / MFMA_PEAK_TFLOPS)
     roof["traffic"] = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{name}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             roof["traffic"] = json.load(f).get("hbm_bytes_per_step")
-    roof["kernels_per_step"] = "see profiles/"
+    roof["traffic_source"] = f"profiles/{name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)"
 
     out = {
-        "metric": "grouped W4+low-rank forward: decode HBM GB/s & us/group; prefill TFLOP/s",
-        "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": act, "data": "synthetic",
-        "config": {"workload": f"{cfg['name']} T={T} r={r} G={Gs} ({args.workload})",
+        "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": act, "data": "synthetic",
+        "config": {"workload": f"{cfg['name']} T={T} r={r} G={Gs} ({name})",
                    "units": n_units, "restored_units": int(mask.sum()), "rotating_copies": n_rot,
                    "launch": args.mode},
         "us_per_step": ms_per_step * 1e3,
-        "wall_ms_per_step": wall_ms_per_step,
+        "timing": {"replays": REPLAYS, "us_per_step_median": ms_per_step * 1e3,
+                   "us_per_step_min": min(ms) * 1e3, "us_per_step_max": max(ms) * 1e3,
+                   "wall_us_per_step_median": float(np.median(wall)) * 1e3,
+                   "hot_us_per_step": min(ms_hot) * 1e3,
+                   "hot_note": "one operand set replayed: weights stay in the Infinity Cache; "
+                               "not the figure of merit"},
         "algorithmic_bytes": alg_bytes, "algorithmic_flops": alg_flops,
         "achieved_GBps": gbs, "achieved_TFLOPs": tfs,
         "roofline": roof,
+        "checks": {"units_that_dropped_their_correction": n_failed, "parity": parity},
     }
-
-    if not args.no_cpu_baseline:
+    if args.no_checks:
+        pass
+    elif n_failed:
+        raise SystemExit(f"bench.py: {n_failed} unit(s) reported an expired in-kernel wait "
+                         "(correction left out); the timing is void")
+    if not args.no_checks and not parity["ok"]:
+        raise SystemExit(f"bench.py: output of unit 0 does not match the oracle: {parity}")
+    if want_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host_unit0, shapes[0], T, r, Gs, decode)
+    return out
+
+
+def sample_rows(shape, T, decode):
+    """Output rows the oracle computes: all of them for decode, a bounded seeded sample
+    per module for prefill."""
+    import numpy as np
+    if decode:
+        return None, shape.rows
+    per = max(8, int(2.0e10 // (2 * T * shape.d_in * len(shape.d_outs))))
+    rng = np.random.default_rng(7)
+    rows = [np.sort(rng.choice(o, size=min(o, per), replace=False)).astype(np.int32)
+            for o in shape.d_outs]
+    return rows, int(sum(len(x) for x in rows))
+
+
+def check_against_oracle(unit, ys, shape, T, restored, decode, act):
+    """Unit 0 of rotation 0, computed once more after the timed loop, against the naive
+    float64 oracle (all rows for decode, the sampled rows for prefill)."""
+    import numpy as np
+
+    from oracle import naive
+
+    naive.load()
+    rows, sampled = sample_rows(shape, T, decode)
+    refs = naive.group_forward(unit, restored, rows=rows)
+    worst = 0.0
+    for i, (y, ref) in enumerate(zip(ys, refs)):
+        got = y.double().cpu().numpy()
+        if rows is not None:
+            got = got[:, rows[i]]
+        worst = max(worst, rel_err(got, ref) if np.isfinite(got).all() else float("inf"))
+    tol = TOL + ULP[act]
+    return {"max_rel_err": worst, "tolerance": tol, "ok": bool(worst <= tol),
+            "checked": f"unit 0 ({shape.name}), {sampled} of {shape.rows} output rows, all tokens"}
+
+
+def cpu_baseline(unit, shape, T, r, Gs, decode):
+    """The oracle (naive C loops, float64) timed on this machine's host cores on a
+    bounded sample of the same workload: unit 0, all tokens, a fixed number of
+    output rows per module."""
+    from oracle import naive
+
+    rows, sampled = sample_rows(shape, T, decode)
+    naive.load()
+    naive.group_forward(unit, True, rows=rows)          # first touch of the operands
+    # repeat the same sample until about ten seconds of CPU work have been timed
+    reps, total = 0, 0.0
+    while total < 10.0 and reps < 400:
+        t0 = time.perf_counter()
+        naive.group_forward(unit, True, rows=rows)
+        total += time.perf_counter() - t0
+        reps += 1
+    dt = total / reps
+    K = shape.d_in
+    by = sampled * K // 2 + sampled * (K // Gs) * 4 + sampled * r * 2 + r * K * 2 + T * K * 2 \
+        + T * sampled * 2
+    fl = 2 * T * K * sampled + 2 * T * r * K + 2 * T * r * sampled
+    if decode:
+        val, unit_s = by / dt / 1e9, "GB/s"
+    else:
+        val, unit_s = fl / dt / 1e12, "TFLOP/s"
+    return {"value": val, "unit": unit_s, "cores": naive.max_threads(), "kind": "oracle",
+            "cpu_model": cpu_model(), "seconds": total,
+            "sample": f"unit 0 ({shape.name}), {T} token(s), {sampled} of {shape.rows} output rows, "
+                      f"{reps} repetitions, naive C loops in float64 with OpenMP"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS),
+                    help="one workload only (default: cfg2_T1 as the headline plus cfg3 as `prefill`)")
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
+                    help="graph: the K timed steps are captured once into a HIP graph")
+    ap.add_argument("--rot", type=int, default=None, help="distinct operand copies to rotate over")
+    ap.add_argument("--layers", type=int, default=None, help="cfg5 only: layers to instantiate")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-checks", action="store_true",
+                    help="report the status / parity checks but do not fail on them (tuning runs "
+                         "of deliberately incomplete kernels only)")
+    ap.add_argument("--restore", default="workload", choices=["workload", "none", "all"],
+                    help="restore mask: the workload's own (default), no unit, or every unit "
+                         "(to price the correction; the JSON line says how many units were restored)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collective is part of the path: units are independent and would be sharded "
+              "whole, one process per GPU)", file=sys.stderr)
+        return 2
+
+    import torch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.workload is not None:
+        bound = WORKLOADS[args.workload][2]
+        if bound == "copy":
+            return copy_calibration(torch, args)
+        if bound == "stream":
+            return stream_ceiling(torch, args)
+        if bound == "mfma_probe":
+            return mfma_ceiling(torch, args, args.workload.endswith("bf16"))
+        out = run_workload(args.workload, args, torch, not args.no_cpu_baseline)
+        out["peaks"] = {"hbm_GBps": HBM_PEAK_GBS, "mfma_f16_bf16_TFLOPs": MFMA_PEAK_TFLOPS}
+        print(json.dumps(out))
+        return 0
+    # default: both halves of the metric
+    out = run_workload("cfg2_T1", args, torch, not args.no_cpu_baseline)
+    pf = run_workload("cfg3", args, torch, False)
+    out["prefill"] = {k: pf[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "dtype",
+                                         "config", "timing", "algorithmic_bytes",
+                                         "algorithmic_flops", "roofline", "checks")}
+    out["peaks"] = {"hbm_GBps": HBM_PEAK_GBS, "mfma_f16_bf16_TFLOPs": MFMA_PEAK_TFLOPS}
     print(json.dumps(out))
     return 0
 
@@ -257,44 +419,69 @@ def copy_calibration(torch, args):
     return 0
 
 
-def cpu_baseline(unit, shape, T, r, Gs, decode):
-    """The oracle (naive C loops, float64) timed on this machine's host cores on a
-    bounded sample of the same workload: unit 0, all tokens, a fixed number of
-    output rows per module."""
+def stream_ceiling(torch, args):
+    """What ONE launch can read when it does nothing else: 24 MiB (the size of the headline
+    workload's weight stream) per launch, 128-bit loads, rotated over 25 buffers (600 MiB)
+    so that no launch finds its bytes in the Infinity Cache; and the same on one buffer."""
     import numpy as np
 
-    from oracle import naive
+    import paper_2603_25385_amd as G
 
-    rows_per_module = None if decode else max(8, int(2.0e10 // (2 * T * shape.d_in * len(shape.d_outs))))
-    rows = None
-    sampled = shape.rows
-    if rows_per_module is not None:
-        rng = np.random.default_rng(7)
-        rows = [np.sort(rng.choice(o, size=min(o, rows_per_module), replace=False)).astype(np.int32)
-                for o in shape.d_outs]
-        sampled = int(sum(len(x) for x in rows))
-    naive.load()
-    naive.group_forward(unit, True, rows=rows)          # first touch of the operands
-    # repeat the same sample until about ten seconds of CPU work have been timed
-    reps, total = 0, 0.0
-    while total < 10.0 and reps < 400:
-        t0 = time.perf_counter()
-        naive.group_forward(unit, True, rows=rows)
-        total += time.perf_counter() - t0
-        reps += 1
-    dt = total / reps
-    K = shape.d_in
-    by = sampled * K // 2 + sampled * (K // Gs) * 4 + sampled * r * 2 + r * K * 2 + T * K * 2 \
-        + T * sampled * 2
-    fl = 2 * T * K * sampled + 2 * T * r * K + 2 * T * r * sampled
-    if decode:
-        val, unit_s = by / dt / 1e9, "GB/s"
-    else:
-        val, unit_s = fl / dt / 1e12, "TFLOP/s"
-    return {"value": val, "unit": unit_s, "cores": naive.max_threads(), "kind": "oracle",
-            "seconds": total,
-            "sample": f"unit 0 ({shape.name}), {T} token(s), {sampled} of {shape.rows} output rows, "
-                      f"{reps} repetitions, naive C loops in float64 with OpenMP"}
+    n = 24 << 20
+    steps = args.steps or 200
+    bufs = [torch.empty(n, dtype=torch.uint8, device="cuda").fill_(i + 1) for i in range(25)]
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+
+    def step(i):
+        G.glowq_probe_stream_read(bufs[i % len(bufs)].data_ptr(), n, sink.data_ptr(),
+                                  torch.cuda.current_stream().cuda_stream)
+
+    def step_hot(i):
+        G.glowq_probe_stream_read(bufs[0].data_ptr(), n, sink.data_ptr(),
+                                  torch.cuda.current_stream().cuda_stream)
+
+    for i in range(25):
+        step(i)
+    torch.cuda.synchronize()
+    ms, _ = time_steps(torch, step, steps, args.mode, REPLAYS)
+    ms_hot, _ = time_steps(torch, step_hot, steps, args.mode, 2)
+    med = float(np.median(ms))
+    print(json.dumps({"metric": "one-launch streaming read of 24 MiB (measured ceiling)",
+                      "value": n / med / 1e6, "unit": "GB/s", "steps": steps, "launch": args.mode,
+                      "us_per_step_median": med * 1e3, "us_per_step_min": min(ms) * 1e3,
+                      "hot_us_per_step": min(ms_hot) * 1e3, "bytes_per_step": n,
+                      "frac_of_hbm_peak": n / med / 1e6 / HBM_PEAK_GBS}))
+    return 0
+
+
+def mfma_ceiling(torch, args, bf16):
+    """What the matrix cores deliver on register-resident operands (16x16x32, two waves per
+    SIMD on every compute unit): the clock-limited rate under a full-chip load."""
+    import numpy as np
+
+    import paper_2603_25385_amd as G
+
+    iters = 20000
+    steps = args.steps or 5
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    flops = [0.0]
+
+    def step(i):
+        flops[0] = G.glowq_probe_mfma(iters, bf16, sink.data_ptr(),
+                                      torch.cuda.current_stream().cuda_stream)
+
+    step(0)
+    torch.cuda.synchronize()
+    ms, _ = time_steps(torch, step, steps, "eager", REPLAYS)
+    med = float(np.median(ms))
+    tf = flops[0] / (med * 1e-3) / 1e12
+    print(json.dumps({"metric": f"register-resident 16x16x32 {'bf16' if bf16 else 'f16'} matrix loop "
+                                "(measured ceiling)",
+                      "value": tf, "unit": "TFLOP/s", "steps": steps, "ms_per_step_median": med,
+                      "ms_per_step_min": min(ms), "flops_per_step": flops[0],
+                      "frac_of_mfma_peak": tf / MFMA_PEAK_TFLOPS,
+                      "implied_clock_GHz": tf * 1e12 / (256 * 4 * 1024) / 1e9}))
+    return 0
 
 
 if __name__ == "__main__":

@@ -1,0 +1,31 @@
+/* glowq_probe.h -- two measured ceilings that the benchmark prints beside the published
+ * peaks of the MI355X.  They are measurement aids in the same shared library as the GlowQ
+ * forward (include/glowq.h) and no part of the method.  Return value: 0 on success, -1 a
+ * required pointer is NULL, -2 a size is out of range, -7 the launch failed.  Both calls
+ * enqueue one kernel on `stream` (a hipStream_t as void*, NULL = default) and return. */
+#ifndef GLOWQ_PROBE_H
+#define GLOWQ_PROBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* One launch that reads `bytes` (a multiple of 32768) from src (DEVICE, 16-byte aligned)
+ * with 128-bit loads, eight 1 KiB wave loads in flight per wave, and does nothing else:
+ * the shape of a weight stream without its arithmetic.  sink: DEVICE, one word, never
+ * written in practice (it keeps the loads alive). */
+int32_t glowq_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+
+/* One launch of 512 workgroups x 4 waves in which every wave issues iters x 8 independent
+ * 16x16x32 matrix-core instructions (binary16, or bfloat16 if bf16 != 0) on operands that
+ * stay in registers.  *flops (HOST) receives the floating-point operations of the
+ * launch.  sink: DEVICE, one float, never written in practice. */
+int32_t glowq_probe_mfma(int32_t iters, int32_t bf16, float* sink, double* flops, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLOWQ_PROBE_H */

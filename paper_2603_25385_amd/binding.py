@@ -74,6 +74,9 @@ def _load():
         "glowq_block_forward": (ctypes.c_int, [up, i32, vp, vp, sz, vp]),
         "glowq_debug_unpack": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
         "glowq_debug_dequant": (ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]),
+        # include/glowq_probe.h
+        "glowq_probe_stream_read": (ctypes.c_int32, [vp, sz, vp, vp]),
+        "glowq_probe_mfma": (ctypes.c_int32, [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)          # AttributeError if a declared symbol is not exported
@@ -212,3 +215,19 @@ def glowq_debug_dequant(w_prepared: int, d_out: int, d_in: int, group_size: int,
                         w_out: int, stream: int = 0) -> None:
     _check(_lib.glowq_debug_dequant(w_prepared or None, d_out, d_in, group_size, act_dtype,
                                     w_out or None, stream or None), "glowq_debug_dequant")
+
+
+def glowq_probe_stream_read(src: int, nbytes: int, sink: int, stream: int = 0) -> None:
+    rc = _lib.glowq_probe_stream_read(src or None, nbytes, sink or None, stream or None)
+    if rc != 0:
+        raise GlowqError(rc, "glowq_probe_stream_read")
+
+
+def glowq_probe_mfma(iters: int, bf16: bool, sink: int, stream: int = 0) -> float:
+    """Returns the floating-point operations of the launch."""
+    fl = ctypes.c_double(0.0)
+    rc = _lib.glowq_probe_mfma(iters, 1 if bf16 else 0, sink or None, ctypes.byref(fl),
+                               stream or None)
+    if rc != 0:
+        raise GlowqError(rc, "glowq_probe_mfma")
+    return fl.value

@@ -78,6 +78,9 @@ template <> struct GroupConst<ACT_BF16> {
     float z = (float)__builtin_bit_cast(_Float16, (uint16_t)(szw >> 16));
     nzs = -z * s;
   }
+  // -(1024 + z) s and -(64 + z) s: exact in fp32 (11 + 11 significant bits)
+  __device__ inline float c1024() const { return __builtin_fmaf(-1024.0f, s, nzs); }
+  __device__ inline float c64() const { return __builtin_fmaf(-64.0f, s, nzs); }
 };
 
 // Eight dequantised weights of one prepared word, in channel order e = 0..7,
@@ -110,12 +113,8 @@ __device__ inline u32x4_t q_minus_z_f16(uint32_t w, half2_t nb2, half2_t nb2b) {
   for (int i = 0; i < 4; ++i) {
     const uint32_t src = i < 2 ? w : ws;
     const uint32_t t = (i & 1) ? and_or(src, 0x00F000F0u, 0x54005400u) : and_or(src, 0x000F000Fu, 0x64006400u);
-#ifdef GLOWQ_EXP_NOADD
-    out[i] = t;
-#else
     const half2_t v = __builtin_bit_cast(half2_t, t) + ((i & 1) ? nb2b : nb2);
     out[i] = __builtin_bit_cast(uint32_t, v);
-#endif
   }
   return out;
 }
@@ -167,9 +166,11 @@ __device__ inline u32x4_t dequant_word<ACT_BF16>(uint32_t w, const GroupConst<AC
 template <int ACT, int NW> struct DequantLockstep;
 template <int NW> struct DequantLockstep<ACT_F16, NW> {
   static constexpr int PH = 15, GS = NW < 2 ? NW : 2;
+  static_assert(NW % GS == 0, "words are taken two at a time");
   static constexpr int N_OPS = NW * PH;
   uint32_t ws[GS];   // the word, shifted for the pair in flight
   half2_t d[GS];     // (q - z) pair in flight
+  __device__ inline void set_group(int, const GroupConst<ACT_F16>&) {}
   __device__ inline void op(int idx, const u32x4_t (&wq)[NW], int j, const GroupConst<ACT_F16> (&g)[NW],
                             u32x4_t (&out)[NW]) {
     const int r_ = idx % (GS * PH), c = r_ % GS, w = (idx / (GS * PH)) * GS + c, ph = r_ / GS;
@@ -186,43 +187,54 @@ template <int NW> struct DequantLockstep<ACT_F16, NW> {
     }
   }
 };
+// bfloat16 in 17 instructions per word.  The nibbles take the same binary16 forms as in
+// the shift-free binary16 recipe (1024 + q under the exponent of 1024, 64 + q under the
+// exponent of 64); a mixed-precision fused multiply-add then reads one half of such a
+// pair as binary16 and computes (1024 + q) s - (1024 + z) s in fp32.  Both products have at
+// most 22 significant bits and the result (q - z) s at most 15, so the fp32 value is
+// exact, and the packed fp32 -> bfloat16 conversion is the one rounding of the stored
+// weight.  c[w][0] = -(1024 + z) s and c[w][1] = -(64 + z) s of word w's group travel
+// beside the group constants (set by the caller when a new group starts).
 template <int NW> struct DequantLockstep<ACT_BF16, NW> {
-  static constexpr int PH = 23, GS = 1;
+  static constexpr int PH = 17, GS = NW < 2 ? NW : 2;
   static constexpr int N_OPS = NW * PH;
-  uint32_t m0[GS], m1[GS];
+  uint32_t ws[GS];   // the word shifted by 8
+  uint32_t t[GS];    // binary16 pair in flight
   float f[GS][2];
-  __device__ static inline float ub(int byte, uint32_t m) {
+  float c[NW][2];
+  __device__ inline void set_group(int w, const GroupConst<ACT_BF16>& g) {
+    c[w][0] = g.c1024();
+    c[w][1] = g.c64();
+  }
+  // fp32 = (binary16 half `hi` of pair) * s + c
+  template <int HI> __device__ static inline float mix(uint32_t pair, float s, float c_) {
     float r;
-    if (byte == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(m));
-    else if (byte == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(m));
-    else if (byte == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(m));
-    else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(m));
+    if (HI) asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(pair), "v"(s), "v"(c_));
+    else asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(pair), "v"(s), "v"(c_));
     return r;
   }
-  // nibbles 0,2,4,6 of a word sit in the bytes of m0 (channels e = 0,4,1,5), nibbles
-  // 1,3,5,7 in the bytes of m1 (e = 2,6,3,7); out[i] holds channels (2i, 2i+1):
-  // pair 0 = (m0.b0, m0.b2), pair 1 = (m1.b0, m1.b2), pair 2 = (m0.b1, m0.b3), pair 3 = (m1.b1, m1.b3)
   __device__ inline void op(int idx, const u32x4_t (&wq)[NW], int j, const GroupConst<ACT_BF16> (&g)[NW],
                             u32x4_t (&out)[NW]) {
-    const int r_ = idx % (GS * PH), c = r_ % GS, w = (idx / (GS * PH)) * GS + c, ph = r_ / GS;
-    if (ph == 0) m0[c] = wq[w][j] & 0x0F0F0F0Fu;
-    else if (ph == 1) m1[c] = wq[w][j] >> 4;
-    else if (ph == 2) m1[c] = m1[c] & 0x0F0F0F0Fu;
+    // words in pairs, instruction by instruction alternating between the two; an odd last
+    // word runs alone
+    constexpr int PAIRED = (NW / GS) * GS * PH;
+    const int r_ = idx < PAIRED ? idx % (GS * PH) : idx - PAIRED;
+    const int cc = idx < PAIRED ? r_ % GS : 0;
+    const int w = idx < PAIRED ? (idx / (GS * PH)) * GS + cc : NW - 1;
+    const int ph = idx < PAIRED ? r_ / GS : r_;
+    // phases: shr | ao0 mixlo0 mixhi0 pack0 | ao1 ... | ao2 ... | ao3 ...
+    if (ph == 0) { ws[cc] = wq[w][j] >> 8; return; }
+    const int i = (ph - 1) >> 2, kind = (ph - 1) & 3;
+    if (kind == 0) {
+      const uint32_t src = i < 2 ? wq[w][j] : ws[cc];
+      t[cc] = (i & 1) ? and_or(src, 0x00F000F0u, 0x54005400u) : and_or(src, 0x000F000Fu, 0x64006400u);
+    } else if (kind == 1) f[cc][0] = mix<0>(t[cc], g[w].s, c[w][i & 1]);
+    else if (kind == 2) f[cc][1] = mix<1>(t[cc], g[w].s, c[w][i & 1]);
     else {
-      // phases per pair i: cvt a, cvt b, fma a, fma b, pack
-      const int i = (ph - 3) / 5, kind = (ph - 3) % 5;
-      const uint32_t src = (i & 1) ? m1[c] : m0[c];
-      const int byte_a = (i >> 1), byte_b = (i >> 1) + 2;
-      if (kind == 0) f[c][0] = ub(byte_a, src);
-      else if (kind == 1) f[c][1] = ub(byte_b, src);
-      else if (kind == 2) f[c][0] = __builtin_fmaf(f[c][0], g[w].s, g[w].nzs);
-      else if (kind == 3) f[c][1] = __builtin_fmaf(f[c][1], g[w].s, g[w].nzs);
-      else {
-        bf16x2_t v;
-        v[0] = (__bf16)f[c][0];
-        v[1] = (__bf16)f[c][1];
-        out[w][i] = __builtin_bit_cast(uint32_t, v);
-      }
+      bf16x2_t v;
+      v[0] = (__bf16)f[cc][0];
+      v[1] = (__bf16)f[cc][1];
+      out[w][i] = __builtin_bit_cast(uint32_t, v);
     }
   }
 };
@@ -235,9 +247,11 @@ template <int NW> struct DequantLockstepF16Shiftless {
   // one unit in the last place is 1/16, so bit 4 weighs 1) -- no shift; the other four
   // nibbles take the same two forms after one shift by 8.  13 instructions per word.
   static constexpr int PH = 13, GS = NW < 2 ? NW : 2;
+  static_assert(NW % GS == 0, "words are taken two at a time");
   static constexpr int N_OPS = NW * PH;
   uint32_t ws[GS];   // the word shifted by 8
   half2_t d[GS];     // (q - z) pair in flight
+  __device__ inline void set_group(int, const GroupConst<ACT_F16>&) {}
   __device__ inline void op(int idx, const u32x4_t (&wq)[NW], int j, const GroupConst<ACT_F16> (&g)[NW],
                             u32x4_t (&out)[NW]) {
     const int r_ = idx % (GS * PH), c = r_ % GS, w = (idx / (GS * PH)) * GS + c, ph = r_ / GS;

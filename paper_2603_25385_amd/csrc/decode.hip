@@ -39,11 +39,12 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArg
   __shared__ float lds[DEC_WAVES * TBK * 4 * 64];
   __shared__ __attribute__((aligned(16))) uint16_t r_lds[16 * TBK * GLOWQ_MAX_RANK];
   __shared__ uint32_t r_flag;
+  __shared__ __attribute__((aligned(1024))) uint32_t lds_af[DEC_WAVES * DEC_RG * 256];
   if ((int)blockIdx.x < n_prod) {
     proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds);
     return;
   }
-  decode_workgroup<ACT, TBK>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds, r_lds, &r_flag);
+  decode_workgroup<ACT, TBK>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds, r_lds, &r_flag, lds_af);
 }
 
 // Up to NB units of the same kind (activation type, token class) in one launch: the grid
@@ -65,9 +66,14 @@ constexpr bool decode_small_merged(int tm) { return tm > 2; }
 
 template <int ACT, int TM, int NB>
 __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeBatch<NB> b) {
-  __shared__ float lds[DEC_WAVES * 4 * 64];
+  __shared__ __attribute__((aligned(1024))) float lds[DEC_WAVES * 4 * 64];
   __shared__ __attribute__((aligned(64))) char lds_x[DEC_WAVES * DecX<TM>::WAVE_BYTES];
   __shared__ __attribute__((aligned(16))) uint32_t lds_rf[DEC_WAVES * TM * DEC_MAX_PARTS * 64];
+  // the A_i fragments land in the fold area: wave w's 1 KiB row is exactly the part of it
+  // that wave w itself overwrites, and it does so only after it has taken its fragment
+  uint32_t* lds_af = (uint32_t*)lds;
+  // (a one-unit launch reads its descriptor at fixed offsets of the kernel argument: one
+  // batch of scalar loads instead of a chain through the unit lookup)
   int ui = 0;
 #pragma unroll
   for (int i = 1; i < NB; ++i)
@@ -82,14 +88,12 @@ __global__ void __launch_bounds__(DEC_WAVES * 64) k_decode_small(DecodeBatch<NB>
   // resident from the start and no row block waits for a projection workgroup's slot.
   constexpr bool MERGED = decode_small_merged(TM);
   if (local < n_prod) {
-    GLOWQ_STAMP(0);
     proj_wave_direct<ACT>(p, local * DEC_WAVES + (int)(threadIdx.x >> 6), (int)(threadIdx.x & 63));
-    GLOWQ_STAMP(1);
     if (!MERGED) return;
   }
   const int blk = MERGED ? local : local - n_prod;
   if (MERGED && blk >= a.mod[a.n_modules - 1].blk_start + a.mod[a.n_modules - 1].rows16) return;
-  decode_workgroup_small<ACT, TM>(a, p, blk, lds, lds_x, lds_rf);
+  decode_workgroup_small<ACT, TM>(a, p, blk, lds, lds_x, lds_rf, lds_af);
 }
 
 int fill_decode_args(const glowq_unit& u, const UnitWorkspace& ws, bool restore, DecodeArgs& a) {
@@ -184,6 +188,7 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
   const bool f16 = (u0.act_dtype == GLOWQ_F16);
   dim3 block(DEC_WAVES * 64);
   if (u0.T <= DEC_SMALL_T) {
+    if (n == 1) return launch_decode_small<1>(units, ws, restore, n, st);
     if (n <= 2) return launch_decode_small<2>(units, ws, restore, n, st);
     if (n <= 8) return launch_decode_small<8>(units, ws, restore, n, st);
     return launch_decode_small<DEC_MAX_BATCH>(units, ws, restore, n, st);
@@ -217,3 +222,4 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
 }  // namespace glowq
 
 GLOWQ_TRACE_EXPORT(glowq_debug_trace)
+GLOWQ_WTRACE_EXPORT(glowq_debug_wtrace)

@@ -401,7 +401,6 @@ __device__ inline bool r_fetch_finish(const ProjArgs& p, RFetch& f, u32x4_t& rf)
     if (!f.on) ok = true;
     if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) {
       done = true;
-      GLOWQ_TRACE_VALUE(5, spin + 1);
       break;
     }
     __builtin_amdgcn_s_sleep(32);
@@ -430,15 +429,18 @@ __device__ inline bool r_fetch_finish(const ProjArgs& p, RFetch& f, u32x4_t& rf)
 }
 
 // A_i fragments of this wave's correction steps (32 ranks each; wave w takes steps
-// w, w + 4, ...: at most one step per wave up to rank 128).  Loaded before the weight
-// stream so that their latency is hidden behind it.
+// w, w + 4, ...: at most one step per wave up to rank 128).  They are asked for before the
+// weight stream and travel global -> LDS directly, 16 bytes per lane into a 1 KiB row of
+// the wave's own: a load into registers inside the `if (restored)` would make the wave
+// wait for it at the end of that block, one memory round trip before it has asked for a
+// single weight.  The row is read back after the stream (correction_take).
 struct CorrFrag {
   u32x4_t af;
   int j0c;
   bool active, ok;
 };
 __device__ inline CorrFrag correction_prefetch(const DecodeArgs& a, const ModuleArgs& M, int rb,
-                                               int wave, int lane) {
+                                               int wave, int lane, uint32_t* lds_row) {
   CorrFrag c;
   const int n = lane & 15, kq = lane >> 4;
   c.active = a.restore && wave * 32 < a.r;
@@ -448,10 +450,16 @@ __device__ inline CorrFrag correction_prefetch(const DecodeArgs& a, const Module
   c.af = u32x4_t{0u, 0u, 0u, 0u};
   if (c.active) {
     const int row = min(rb * 16 + n, M.d_out - 1);
-    c.af = *(const u32x4_t*)(M.A + (size_t)row * a.r + c.j0c);
-    if (!c.ok) c.af = u32x4_t{0u, 0u, 0u, 0u};
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(M.A + (size_t)row * a.r + c.j0c),
+        (__attribute__((address_space(3))) void*)lds_row, 16, 0, 0);
   }
   return c;
+}
+// after every load of the wave has completed (s_waitcnt vmcnt(0)); lanes whose ranks lie
+// past r get zeros
+__device__ inline void correction_take(CorrFrag& c, const uint32_t* lds_row, int lane) {
+  if (c.active && c.ok) c.af = *(const u32x4_t*)(lds_row + 4 * lane);
 }
 
 // Correction R A_i^T as r more channels of the contraction (4 < T <= 32).  R comes from
@@ -563,12 +571,32 @@ __device__ inline const ModuleArgs& find_module(const DecodeArgs& a, int blk) {
     if (i < a.n_modules && blk >= a.mod[i].blk_start) mi = i;
   return a.mod[mi];
 }
+// The scalars of a unit's descriptor, copied out of the kernel argument in one place: the
+// scalar loads then go out together at the head of the kernel instead of one by one, each
+// with a wait of its own, wherever a field happens to be needed first.  (mod[] is left
+// out: a workgroup copies the one module it works on.)
+__device__ inline DecodeArgs decode_scalars(const DecodeArgs& a) {
+  DecodeArgs l;
+  l.n_modules = a.n_modules;
+  l.X = a.X;
+  l.T = a.T;
+  l.K = a.K;
+  l.r = a.r;
+  l.G = a.G;
+  l.restore = a.restore;
+  l.out_f32 = a.out_f32;
+  l.ctl = a.ctl;
+  return l;
+}
 
 // grp: index of the workgroup's group of DEC_RG row blocks; n_blocks: row blocks of the unit
 // lds: DEC_WAVES * TBK * 256 floats (fold); r_lds: act dtype [16 TBK][GLOWQ_MAX_RANK]; flag: one word
+// lds_af: DEC_WAVES * DEC_RG rows of 256 words (the A_i fragments' landing place)
 template <int ACT, int TBK>
-__device__ inline void decode_workgroup(const DecodeArgs& a, const ProjArgs& p, int grp, int n_blocks,
-                                        float* lds, uint16_t* r_lds, uint32_t* flag) {
+__device__ inline void decode_workgroup(const DecodeArgs& a_arg, const ProjArgs& p_arg, int grp, int n_blocks,
+                                        float* lds, uint16_t* r_lds, uint32_t* flag, uint32_t* lds_af) {
+  const DecodeArgs a = decode_scalars(a_arg);
+  const ProjArgs p = p_arg;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ktiles = a.K >> 7;
@@ -583,10 +611,10 @@ __device__ inline void decode_workgroup(const DecodeArgs& a, const ProjArgs& p, 
     for (int tb = 0; tb < TBK; ++tb) acc[g][tb] = float4_t{0.f, 0.f, 0.f, 0.f};
     // a group past the unit's last block repeats it (computed, not stored)
     const int blk = min(grp * DEC_RG + g, n_blocks - 1);
-    const ModuleArgs& M = find_module(a, blk);
+    const ModuleArgs M = find_module(a_arg, blk);
     const int rb = blk - M.blk_start;
     recb[g] = M.rec + ((size_t)rb * ktiles + wave) * rw;
-    cf[g] = correction_prefetch(a, M, rb, wave, lane);
+    cf[g] = correction_prefetch(a, M, rb, wave, lane, lds_af + (wave * DEC_RG + g) * 256);
   }
   GLOWQ_STAMP(0);
   if (a.G == 128) decode_stream_rows<ACT, TBK, true>(a, recb, wave, lane, acc);
@@ -598,7 +626,9 @@ __device__ inline void decode_workgroup(const DecodeArgs& a, const ProjArgs& p, 
   for (int tb = 0; tb < TBK; ++tb) rf[tb] = u32x4_t{0u, 0u, 0u, 0u};
   bool have_r = false;
   if (a.restore && a.r > 0) {                      // uniform
-    have_r = fetch_r_coop<ACT, TBK>(a, p, r_lds, flag);
+    have_r = fetch_r_coop<ACT, TBK>(a, p, r_lds, flag);   // (waits for all the wave's loads)
+#pragma unroll
+    for (int g = 0; g < DEC_RG; ++g) correction_take(cf[g], lds_af + (wave * DEC_RG + g) * 256, lane);
     if (have_r && cf[0].active && cf[0].ok) {
 #pragma unroll
       for (int tb = 0; tb < TBK; ++tb) {
@@ -611,7 +641,7 @@ __device__ inline void decode_workgroup(const DecodeArgs& a, const ProjArgs& p, 
   for (int g = 0; g < DEC_RG; ++g) {
     const int blk = grp * DEC_RG + g;
     if (blk >= n_blocks) break;                    // uniform
-    const ModuleArgs& M = find_module(a, blk);
+    const ModuleArgs M = find_module(a_arg, blk);
     if (cf[g].active && have_r) {
 #pragma unroll
       for (int tb = 0; tb < TBK; ++tb) acc[g][tb] = mfma16<ACT>(rf[tb], cf[g].af, acc[g][tb]);
@@ -623,23 +653,28 @@ __device__ inline void decode_workgroup(const DecodeArgs& a, const ProjArgs& p, 
 }
 
 // T <= 4.  lds: DEC_WAVES * 256 floats for the fold; lds_x: DEC_WAVES * DecX<TM>::WAVE_BYTES;
-// lds_rf: DEC_WAVES * TM * DEC_MAX_PARTS rows of 64 words.
+// lds_rf: DEC_WAVES * TM * DEC_MAX_PARTS rows of 64 words; lds_af: DEC_WAVES rows of 256 words.
 template <int ACT, int TM>
-__device__ inline void decode_workgroup_small(const DecodeArgs& a, const ProjArgs& p, int blk,
-                                              float* lds, char* lds_x, uint32_t* lds_rf) {
-  const ModuleArgs& M = find_module(a, blk);
+__device__ inline void decode_workgroup_small(const DecodeArgs& a_arg, const ProjArgs& p_arg, int blk,
+                                              float* lds, char* lds_x, uint32_t* lds_rf, uint32_t* lds_af) {
+  const ModuleArgs M = find_module(a_arg, blk);      // by value, like the scalars
+  const DecodeArgs a = decode_scalars(a_arg);
+  const ProjArgs p = p_arg;
   const int rb = blk - M.blk_start;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
   float4_t acc[1] = {float4_t{0.f, 0.f, 0.f, 0.f}};
-  GLOWQ_STAMP(0);
-  GLOWQ_TRACE_HWID(7);
-  const CorrFrag cf = correction_prefetch(a, M, rb, wave, lane);
+  GLOWQ_WTRACE_DECL;
+  GLOWQ_WSTAMP(0);
+  CorrFrag cf = correction_prefetch(a, M, rb, wave, lane, lds_af + wave * 256);
   RFetch rfetch;
   r_fetch_plan(a, p, cf.j0c, a.restore && cf.active && cf.ok, lane, rfetch);
   uint32_t* lds_rf_wave = lds_rf + wave * (TM * DEC_MAX_PARTS * 64);
-  auto mid = [&]() { if (a.restore && cf.active) r_fetch_issue(a, p, wave, lane, lds_rf_wave); };
+  auto mid = [&]() {
+    GLOWQ_WSTAMP(1);
+    if (a.restore && cf.active) r_fetch_issue(a, p, wave, lane, lds_rf_wave);
+  };
   char* lds_wave = lds_x + wave * DecX<TM>::WAVE_BYTES;
   if (a.G == 128) {
     if constexpr (TM == 1) decode_stream_small<ACT, true, 1, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);
@@ -647,15 +682,18 @@ __device__ inline void decode_workgroup_small(const DecodeArgs& a, const ProjArg
   } else {
     decode_stream_small<ACT, false, 4, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);
   }
-  GLOWQ_STAMP(1);
+  GLOWQ_WSTAMP(2);
   if (a.restore && cf.active) {
     u32x4_t rf;
-    r_fetch_take(a, p, lane, lds_rf_wave, rfetch);
+    r_fetch_take(a, p, lane, lds_rf_wave, rfetch);   // (waits for all the wave's loads)
+    GLOWQ_WSTAMP(3);
+    correction_take(cf, lds_af + wave * 256, lane);
     if (r_fetch_finish<ACT>(p, rfetch, rf)) acc[0] = mfma16<ACT>(rf, cf.af, acc[0]);
-    GLOWQ_STAMP(3);
+    GLOWQ_WSTAMP(4);
   }
   decode_reduce_store<ACT, 1>(a, M, rb, wave, lane, acc, lds);
-  GLOWQ_STAMP(4);
+  GLOWQ_WSTAMP(6);
+  GLOWQ_WTRACE_FLUSH();
 }
 
 }  // namespace glowq

@@ -467,6 +467,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
 #pragma unroll
   for (int b = 0; b < RB; ++b) {
     g[b].set(szcur[b][0]);
+    dq.set_group(b, g[b]);
     wf[0][b] = dequant_word<ACT>(wcur[b][0], g[b]);
   }
   __builtin_amdgcn_s_barrier();
@@ -538,7 +539,10 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
           {
             constexpr int NS = RB * MB;
             constexpr int NO = DQ::N_OPS;
-            if (i < RB && new_group) g[i].set(szcur[i][G128 ? 0 : (jn >> 1)]);
+            if (i < RB && new_group) {
+              g[i].set(szcur[i][G128 ? 0 : (jn >> 1)]);
+              dq.set_group(i, g[i]);
+            }
             // the first RB slots carry the group constants when a new group starts; the
             // recipe's instructions are spread evenly over the slots after them
             const int lo = i < RB ? 0 : ((i - RB) * NO) / (NS - RB);

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_every_declared_symbol_is_exported():
-    text = open(os.path.join(ROOT, "include", "glowq.h")).read()
+    text = open(os.path.join(ROOT, "include", "glowq.h")).read() + \
+        open(os.path.join(ROOT, "include", "glowq_probe.h")).read()
     declared = set(re.findall(r"\b(glowq_[a-z_0-9]+)\s*\(", text))
     assert declared, "no declarations found"
     lib = ctypes.CDLL(os.path.join(ROOT, "paper_2603_25385_amd", "lib", "libglowq.so"))
