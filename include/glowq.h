@@ -171,6 +171,20 @@ glowq_status glowq_shared_proj(const glowq_unit* u, float* R_out, void* workspac
 glowq_status glowq_group_forward(const glowq_unit* u, int32_t restore, void* workspace,
                                  size_t workspace_bytes, void* stream);
 
+/* glowq_group_forward_static: glowq_group_forward for callers that cannot allocate
+ * device memory or carry a workspace around (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc).  Same arguments without the
+ * workspace: the scratch is a file-scope device array of GLOWQ_STATIC_SCRATCH_BYTES
+ * inside the library, one per GPU, held until the process ends.  The call allocates
+ * nothing (no hipMalloc / hipFree, no allocating library routine) and never
+ * synchronises; a unit whose scratch need (glowq_workspace_bytes) exceeds the array is
+ * refused with GLOWQ_ERR_WORKSPACE.  Every call on a GPU shares that GPU's array:
+ * calls that may overlap in time on one GPU race (use glowq_group_forward with
+ * separate workspaces for those), and the unit's status word is not observable.
+ * Results are those of glowq_group_forward. */
+#define GLOWQ_STATIC_SCRATCH_BYTES (16u << 20)
+glowq_status glowq_group_forward_static(const glowq_unit* u, int32_t restore, void* stream);
+
 /* glowq_block_forward: the same for `n_units` independent units (for example
  * the four units of one decoder block, or a whole stack), unit i restored iff
  * restore_mask[i] != 0 (HOST, one byte per unit; NULL = restore every unit).

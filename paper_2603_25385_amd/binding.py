@@ -15,6 +15,7 @@ from typing import Optional, Sequence
 GLOWQ_F16, GLOWQ_BF16, GLOWQ_F32 = 0, 1, 2
 GLOWQ_MAX_MODULES = 8
 GLOWQ_MAX_RANK = 128
+GLOWQ_STATIC_SCRATCH_BYTES = 16 << 20
 GLOWQ_OK = 0
 GLOWQ_ERR_NULL, GLOWQ_ERR_SHAPE, GLOWQ_ERR_ALIGN, GLOWQ_ERR_DTYPE = -1, -2, -3, -4
 GLOWQ_ERR_UNSUPPORTED, GLOWQ_ERR_WORKSPACE, GLOWQ_ERR_HIP = -5, -6, -7
@@ -71,6 +72,7 @@ def _load():
         "glowq_workspace_status": (ctypes.c_int, [up, i32, vp, sz, vp, vp]),
         "glowq_shared_proj": (ctypes.c_int, [up, vp, vp, sz, vp]),
         "glowq_group_forward": (ctypes.c_int, [up, i32, vp, sz, vp]),
+        "glowq_group_forward_static": (ctypes.c_int, [up, i32, vp]),
         "glowq_block_forward": (ctypes.c_int, [up, i32, vp, vp, sz, vp]),
         "glowq_debug_unpack": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
         "glowq_debug_dequant": (ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]),
@@ -191,6 +193,11 @@ def glowq_group_forward(unit: glowq_unit, restore: bool, workspace: int, workspa
                         stream: int = 0) -> None:
     _check(_lib.glowq_group_forward(ctypes.byref(unit), 1 if restore else 0, workspace or None,
                                     workspace_bytes, stream or None), "glowq_group_forward")
+
+
+def glowq_group_forward_static(unit: glowq_unit, restore: bool, stream: int = 0) -> None:
+    _check(_lib.glowq_group_forward_static(ctypes.byref(unit), 1 if restore else 0,
+                                           stream or None), "glowq_group_forward_static")
 
 
 def glowq_block_forward(units: Sequence[glowq_unit], restore_mask: Optional[bytes],

@@ -1,10 +1,38 @@
 // C ABI of the GlowQ group forward (declared in include/glowq.h): host-side
 // argument checks, workspace planning and dispatch to the HIP kernels.  Nothing in
 // this file allocates, synchronises or keeps state.
+#include <mutex>
 #include "common.hpp"
 #include "launch.hpp"
 
 namespace glowq {
+
+// Scratch of glowq_group_forward_static: one array per GPU, held until the process ends.
+// In host code the array's name is only a stand-in; its device address comes from
+// hipGetSymbolAddress, once per device, and is what every launch is given.
+static __device__ __align__(256) unsigned char g_static_scratch[GLOWQ_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_static_scratch_ptr[MAX_DEVICES];
+static std::mutex g_static_scratch_mutex;
+
+// device address of the current device's scratch array (null + error code on failure)
+static hipError_t static_scratch(void** out) {
+  *out = nullptr;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+  if (!g_static_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_scratch_ptr[dev] = p;
+  }
+  *out = g_static_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
@@ -269,6 +297,25 @@ glowq_status glowq_group_forward(const glowq_unit* u, int32_t restore, void* wor
                                  size_t workspace_bytes, void* stream) {
   uint8_t mask = restore ? 1 : 0;
   return glowq_block_forward(u, 1, &mask, workspace, workspace_bytes, stream);
+}
+
+glowq_status glowq_group_forward_static(const glowq_unit* u, int32_t restore, void* stream) {
+  const bool corrected = u && u->r > 0 && restore;
+  glowq_status s = validate(u, true, corrected);
+  if (s != GLOWQ_OK) return s;
+  uint8_t mask = restore ? 1 : 0;
+  if (!corrected) return forward_all(u, 1, &mask, nullptr, (hipStream_t)stream);
+  const UnitWorkspace plan = plan_unit_workspace(*u, nullptr);
+  if (plan.bytes > (size_t)GLOWQ_STATIC_SCRATCH_BYTES) return GLOWQ_ERR_WORKSPACE;
+  void* scratch = nullptr;
+  hipError_t e = static_scratch(&scratch);
+  if (e != hipSuccess) return hip_status(e);
+  // the array keeps the last call's contents, laid out for that call's unit: the control
+  // and flag words of THIS unit's layout must start at zero (a fill kernel, not a memset
+  // node, so that the call can be captured into a graph)
+  e = launch_fill_zero(scratch, plan.ctl_bytes, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_status(e);
+  return forward_all(u, 1, &mask, (char*)scratch, (hipStream_t)stream);
 }
 
 glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,
