@@ -78,7 +78,7 @@ def _load():
         "glowq_debug_dequant": (ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]),
         # include/glowq_probe.h
         "glowq_probe_stream_read": (ctypes.c_int32, [vp, sz, vp, vp]),
-        "glowq_probe_mfma": (ctypes.c_int32, [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]),
+        "glowq_probe_mfma": (ctypes.c_int32, [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)          # AttributeError if a declared symbol is not exported
@@ -230,11 +230,11 @@ def glowq_probe_stream_read(src: int, nbytes: int, sink: int, stream: int = 0) -
         raise GlowqError(rc, "glowq_probe_stream_read")
 
 
-def glowq_probe_mfma(iters: int, bf16: bool, sink: int, stream: int = 0) -> float:
+def glowq_probe_mfma(iters: int, bf16: bool, waves_per_simd: int, sink: int, stream: int = 0) -> float:
     """Returns the floating-point operations of the launch."""
     fl = ctypes.c_double(0.0)
-    rc = _lib.glowq_probe_mfma(iters, 1 if bf16 else 0, sink or None, ctypes.byref(fl),
-                               stream or None)
+    rc = _lib.glowq_probe_mfma(iters, 1 if bf16 else 0, waves_per_simd, sink or None,
+                               ctypes.byref(fl), stream or None)
     if rc != 0:
         raise GlowqError(rc, "glowq_probe_mfma")
     return fl.value

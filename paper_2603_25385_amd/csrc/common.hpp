@@ -119,6 +119,20 @@ __device__ inline u32x4_t q_minus_z_f16(uint32_t w, half2_t nb2, half2_t nb2b) {
   return out;
 }
 
+// The eight nibbles of a prepared word as binary16 pairs WITHOUT the subtraction: pairs 0
+// and 2 hold 1024 + q, pairs 1 and 3 hold 64 + q (five instructions).  For callers that
+// take the offsets and the zero-point out of the contraction's result instead:
+// sum_k x_k (off_k + q_k) - sum_k x_k off_k - z sum_k x_k = sum_k x_k (q_k - z).
+__device__ inline u32x4_t nibble_forms_f16(uint32_t w) {
+  const uint32_t ws = w >> 8;
+  u32x4_t out;
+  out[0] = and_or(w, 0x000F000Fu, 0x64006400u);
+  out[1] = and_or(w, 0x00F000F0u, 0x54005400u);
+  out[2] = and_or(ws, 0x000F000Fu, 0x64006400u);
+  out[3] = and_or(ws, 0x00F000F0u, 0x54005400u);
+  return out;
+}
+
 template <>
 __device__ inline u32x4_t dequant_word<ACT_F16>(uint32_t w, const GroupConst<ACT_F16>& g) {
   u32x4_t d = q_minus_z_f16(w, g.nb2, g.nb2b);

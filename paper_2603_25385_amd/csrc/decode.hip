@@ -33,18 +33,18 @@ namespace glowq {
 static_assert(GLOWQ_MAX_RANK <= DEC_WAVES * 32, "one 32-rank correction step per wave");
 
 // Grid: [n_prod projection workgroups][one workgroup per DEC_RG 16-row blocks].
-template <int ACT, int TBK>
-__global__ void __launch_bounds__(DEC_WAVES * 64) k_decode(DecodeArgs a, ProjArgs p, int n_prod,
-                                                          int n_blocks) {
-  __shared__ float lds[DEC_WAVES * TBK * 4 * 64];
+template <int ACT, int TBK, int NW>
+__global__ void __launch_bounds__(NW * 64) k_decode(DecodeArgs a, ProjArgs p, int n_prod,
+                                                   int n_blocks) {
+  __shared__ float lds[NW * TBK * 4 * 64];
   __shared__ __attribute__((aligned(16))) uint16_t r_lds[16 * TBK * GLOWQ_MAX_RANK];
   __shared__ uint32_t r_flag;
-  __shared__ __attribute__((aligned(1024))) uint32_t lds_af[DEC_WAVES * DEC_RG * 256];
+  __shared__ __attribute__((aligned(1024))) uint32_t lds_af[NW * DEC_RG * 256];
   if ((int)blockIdx.x < n_prod) {
     proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds);
     return;
   }
-  decode_workgroup<ACT, TBK>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds, r_lds, &r_flag, lds_af);
+  decode_workgroup<ACT, TBK, NW>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds, r_lds, &r_flag, lds_af);
 }
 
 // Up to NB units of the same kind (activation type, token class) in one launch: the grid
@@ -206,12 +206,14 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
       n_prod = ((u.T + 15) / 16) * ws[i].ksplit;
     }
     dim3 grid((unsigned)(n_prod + (blocks + DEC_RG - 1) / DEC_RG));
+    // (eight waves per workgroup, i.e. twice the tiles in flight per compute unit, were
+    // measured for up to 16 tokens: the stream took as long and the correction longer)
     if (u.T <= 16) {
-      if (f16) k_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
-      else k_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
+      if (f16) k_decode<ACT_F16, 1, DEC_WAVES><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
+      else k_decode<ACT_BF16, 1, DEC_WAVES><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
     } else {
-      if (f16) k_decode<ACT_F16, 2><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
-      else k_decode<ACT_BF16, 2><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
+      if (f16) k_decode<ACT_F16, 2, DEC_WAVES><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
+      else k_decode<ACT_BF16, 2, DEC_WAVES><<<grid, block, 0, st>>>(a, p, n_prod, blocks);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

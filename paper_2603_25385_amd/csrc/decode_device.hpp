@@ -73,65 +73,40 @@ __device__ inline void decode_tile(const u32x4_t w, uint32_t sz0, uint32_t sz1, 
   }
 }
 
-template <int ACT, int TBK, bool G128>
-__device__ inline void decode_stream(const DecodeArgs& a, const ModuleArgs& M, int rb, int wave,
-                                     int lane, float4_t (&acc)[TBK]) {
-  const int n = lane & 15, kq = lane >> 4;
-  const int ktiles = a.K >> 7;
-  const int rw = G128 ? 272 : 288;             // words per tile record
-  // this wave's tiles: kb = wave + DEC_WAVES * t, t = 0 .. ntw - 1
-  const int ntw = (ktiles - wave + DEC_WAVES - 1) / DEC_WAVES;
-  const uint32_t* rec0 = M.rec + ((size_t)rb * ktiles + wave) * rw;
-  // tokens past T read the last valid token: their rows of D are never stored
-  const uint16_t* xrow[TBK];
+// One token, binary16, group size 128, with the offsets and the zero-point taken out of
+// the contraction's result: the word's nibbles go to the matrix cores as 1024 + q and
+// 64 + q (five instructions per word instead of nine), and
+//   sum_k x_k (q_k - z) = tmp - c1 - z S,   c1 = sum_k x_k off_k,   S = sum_k x_k.
+// c1 and S come from the matrix cores as well, which have time to spare here: a second
+// product of the same X fragment with a constant operand whose column 0 holds the offsets
+// and whose column 1 holds ones (offsets_operand), accumulated exactly like tmp, so that
+// what the two sums lose to rounding (2^-24 at the magnitude of 1024 sum |x|) is largely
+// the same on both sides of the subtraction; nothing is lost when X is a row of the
+// identity.  Token 0 sits in element 0 of lanes 0..15, so c1 is lane 0's and S lane 1's.
+__device__ inline u32x4_t offsets_operand(int lane) {
+  const int n = lane & 15;
+  const uint32_t p1024 = 0x64006400u, p64 = 0x54005400u, ones = 0x3C003C00u;
+  if (n == 0) return u32x4_t{p1024, p64, p1024, p64};
+  if (n == 1) return u32x4_t{ones, ones, ones, ones};
+  return u32x4_t{0u, 0u, 0u, 0u};
+}
+template <class XF>
+__device__ inline void decode_tile_offsets(const u32x4_t w, uint32_t sz, XF xfrag, const u32x4_t offc,
+                                           float4_t (&acc)[1]) {
+  float4_t tmp, off;
 #pragma unroll
-  for (int tb = 0; tb < TBK; ++tb)
-    xrow[tb] = a.X + (size_t)min(16 * tb + n, a.T - 1) * a.K + 8 * kq + 128 * wave;
-
-  u32x4_t wA[DEC_CHUNK], wB[DEC_CHUNK];
-  uint32_t sA[DEC_CHUNK][2], sB[DEC_CHUNK][2];
-
-  auto load_chunk = [&](int t0, u32x4_t (&w)[DEC_CHUNK], uint32_t (&s)[DEC_CHUNK][2]) {
-#pragma unroll
-    for (int c = 0; c < DEC_CHUNK; ++c) {
-      const int t = min(t0 + c, ntw - 1);          // clamped: a duplicate tile is never used
-      const uint32_t* rec = rec0 + (size_t)t * (DEC_WAVES * rw);
-      w[c] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
-      s[c][0] = __builtin_nontemporal_load(rec + 256 + n);
-      if constexpr (G128) s[c][1] = s[c][0];
-      else s[c][1] = __builtin_nontemporal_load(rec + 272 + n);
-    }
-  };
-  auto run_chunk = [&](int t0, const u32x4_t (&w)[DEC_CHUNK], const uint32_t (&s)[DEC_CHUNK][2]) {
-    if (t0 + DEC_CHUNK <= ntw) {
-#pragma unroll
-      for (int c = 0; c < DEC_CHUNK; ++c) {
-        const size_t xo = (size_t)(t0 + c) * (128 * DEC_WAVES);
-        decode_tile<ACT, TBK, G128>(w[c], s[c][0], s[c][1], [&](int tb, int j) {
-          return *(const u32x4_t*)(xrow[tb] + xo + 32 * j); }, acc);
-      }
-    } else {
-#pragma unroll
-      for (int c = 0; c < DEC_CHUNK; ++c) {
-        if (t0 + c < ntw) {
-          const size_t xo = (size_t)(t0 + c) * (128 * DEC_WAVES);
-          decode_tile<ACT, TBK, G128>(w[c], s[c][0], s[c][1], [&](int tb, int j) {
-            return *(const u32x4_t*)(xrow[tb] + xo + 32 * j); }, acc);
-        }
-      }
-    }
-  };
-
-  if (ntw <= 0) return;
-  load_chunk(0, wA, sA);
-  for (int t0 = 0; t0 < ntw; t0 += 2 * DEC_CHUNK) {
-    if (t0 + DEC_CHUNK < ntw) load_chunk(t0 + DEC_CHUNK, wB, sB);
-    run_chunk(t0, wA, sA);
-    if (t0 + DEC_CHUNK < ntw) {
-      if (t0 + 2 * DEC_CHUNK < ntw) load_chunk(t0 + 2 * DEC_CHUNK, wA, sA);
-      run_chunk(t0 + DEC_CHUNK, wB, sB);
-    }
+  for (int j = 0; j < 4; ++j) {
+    const u32x4_t wf = nibble_forms_f16(w[j]);
+    const u32x4_t xf = xfrag(0, j);
+    tmp = mfma16<ACT_F16>(xf, wf, j == 0 ? float4_t{0.f, 0.f, 0.f, 0.f} : tmp);     // D[token][row]
+    off = mfma16<ACT_F16>(xf, offc, j == 0 ? float4_t{0.f, 0.f, 0.f, 0.f} : off);   // D[token][0 | 1]
   }
+  const float c1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, off[0]), 0));
+  const float S = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, off[0]), 1));
+  const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)(sz & 0xffffu));
+  const float z = (float)__builtin_bit_cast(_Float16, (uint16_t)(sz >> 16));
+  const float u = __builtin_fmaf(z, S, c1);
+  acc[0][0] = __builtin_fmaf(s, tmp[0] - u, acc[0][0]);
 }
 
 // T <= 4: the same stream with X staged through LDS.  Each wave owns the K tiles it
@@ -153,14 +128,14 @@ __host__ __device__ constexpr int dec_xbuf_bytes(int T) { return (T * DEC_XROW +
 constexpr int DEC_RG = 3;
 constexpr int DEC_RCH = 2;
 
-template <int ACT, int TBK, bool G128>
+template <int ACT, int TBK, bool G128, int NW>
 __device__ inline void decode_stream_rows(const DecodeArgs& a, const uint32_t* const (&recb)[DEC_RG],
                                           int wave, int lane, float4_t (&acc)[DEC_RG][TBK]) {
   const int n = lane & 15, kq = lane >> 4;
   const int ktiles = a.K >> 7;
   const int rw = G128 ? 272 : 288;             // words per tile record
-  // this wave's tiles: kb = wave + DEC_WAVES * t, t = 0 .. ntw - 1
-  const int ntw = (ktiles - wave + DEC_WAVES - 1) / DEC_WAVES;
+  // this wave's tiles: kb = wave + NW * t, t = 0 .. ntw - 1
+  const int ntw = (ktiles - wave + NW - 1) / NW;
   if (ntw <= 0) return;
   // tokens past T read the last valid token: their rows of D are never stored
   const uint16_t* xrow[TBK];
@@ -182,10 +157,10 @@ __device__ inline void decode_stream_rows(const DecodeArgs& a, const uint32_t* c
       for (int tb = 0; tb < TBK; ++tb)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          b.x[c][tb][j] = *(const u32x4_t*)(xrow[tb] + (size_t)t * (128 * DEC_WAVES) + 32 * j);
+          b.x[c][tb][j] = *(const u32x4_t*)(xrow[tb] + (size_t)t * (128 * NW) + 32 * j);
 #pragma unroll
       for (int g = 0; g < DEC_RG; ++g) {
-        const uint32_t* rec = recb[g] + (size_t)t * (DEC_WAVES * rw);
+        const uint32_t* rec = recb[g] + (size_t)t * (NW * rw);
         b.w[c][g] = __builtin_nontemporal_load((const u32x4_t*)rec + lane);
         b.s[c][g][0] = __builtin_nontemporal_load(rec + 256 + n);
         if constexpr (G128) b.s[c][g][1] = b.s[c][g][0];
@@ -231,7 +206,7 @@ template <int TM> struct DecX {
   static constexpr int WAVE_BYTES = NBUF * dec_xbuf_bytes(TM);
 };
 
-template <int ACT, bool G128, int NV, int TM, class MID>
+template <int ACT, bool G128, int NV, int TM, bool OFFS, class MID>
 __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs& M, int rb,
                                            int wave, int lane, float4_t (&acc)[1],
                                            char* lds_wave, MID mid) {
@@ -278,6 +253,7 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
     }
   };
   uint32_t landed = 0;   // a word of a load issued after the X that is read next
+  const u32x4_t offc = offsets_operand(lane);   // (OFFS only)
   auto run_chunk = [&](int idx, const u32x4_t (&w)[DEC_CHUNK], const uint32_t (&s)[DEC_CHUNK][2]) {
     const int t0 = idx * DEC_CHUNK;
     const uint32_t w00 = w[0][0];
@@ -298,8 +274,13 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xf[c & 1][0]), "+v"(xf[c & 1][1]), "+v"(xf[c & 1][2]),
                      "+v"(xf[c & 1][3]) : : "memory");
       }
-      if (t0 + c < ntw)
-        decode_tile<ACT, 1, G128, NV>(w[c], s[c][0], s[c][1], [&](int, int j) { return xf[c & 1][j]; }, acc);
+      if (t0 + c < ntw) {
+        if constexpr (OFFS) {
+          decode_tile_offsets(w[c], s[c][0], [&](int, int j) { return xf[c & 1][j]; }, offc, acc);
+        } else {
+          decode_tile<ACT, 1, G128, NV>(w[c], s[c][0], s[c][1], [&](int, int j) { return xf[c & 1][j]; }, acc);
+        }
+      }
     }
     landed = w00;   // the next chunk's X went out before this chunk's weights (EARLY)
   };
@@ -479,7 +460,7 @@ __device__ inline void correction_take(CorrFrag& c, const uint32_t* lds_row, int
 __device__ inline void vm_load_dev(u32x4_t& v, const void* p) {
   asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
 }
-template <int ACT, int TBK>
+template <int ACT, int TBK, int NW>
 __device__ inline bool fetch_r_coop(const DecodeArgs& a, const ProjArgs& p, uint16_t* r_lds, uint32_t* flag) {
   const int tid = threadIdx.x;
   const int hp = a.r >> 1;                     // rank pairs (16-byte units) per token and part
@@ -492,12 +473,12 @@ __device__ inline bool fetch_r_coop(const DecodeArgs& a, const ProjArgs& p, uint
   __syncthreads();
   for (int spin = 0; spin < (1 << 12); ++spin) {
     bool ok = true;
-    for (int e0 = 0; e0 < n_el; e0 += EPR * DEC_WAVES * 64) {
+    for (int e0 = 0; e0 < n_el; e0 += EPR * NW * 64) {
       u32x4_t v[EPR][MAXP];
       int el[EPR];
 #pragma unroll
       for (int k = 0; k < EPR; ++k) {
-        el[k] = e0 + k * DEC_WAVES * 64 + tid;
+        el[k] = e0 + k * NW * 64 + tid;
         const int ec = min(el[k], n_el - 1);   // clamped: loaded again, not used
         const int tok = ec / hp, rp = ec - tok * hp;
         const u32x4_t* q = units + (size_t)tok * p.ksplit * hp + rp;
@@ -538,8 +519,9 @@ __device__ inline bool fetch_r_coop(const DecodeArgs& a, const ProjArgs& p, uint
   return false;
 }
 
-// lds: DEC_WAVES * TBK * 256 floats
-template <int ACT, int TBK>
+// Folds the NW waves' fp32 tiles of one row block through LDS and stores the result.
+// lds: NW * TBK * 256 floats
+template <int ACT, int TBK, int NW = DEC_WAVES>
 __device__ inline void decode_reduce_store(const DecodeArgs& a, const ModuleArgs& M, int rb,
                                            int wave, int lane, const float4_t (&acc)[TBK],
                                            float* lds) {
@@ -548,6 +530,7 @@ __device__ inline void decode_reduce_store(const DecodeArgs& a, const ModuleArgs
 #pragma unroll
     for (int v = 0; v < 4; ++v) lds[((wave * TBK + tb) * 4 + v) * 64 + lane] = acc[tb][v];
   __syncthreads();
+  if (wave >= 4) return;                         // (uniform per wave; no barrier follows in here)
   const int v = wave, ln = lane;                 // 256 threads <-> (v, lane) of one token block
   const int row = rb * 16 + (ln & 15);
 #pragma unroll
@@ -556,7 +539,7 @@ __device__ inline void decode_reduce_store(const DecodeArgs& a, const ModuleArgs
     if (t < a.T && row < M.d_out) {
       float s = 0.f;
 #pragma unroll
-      for (int w = 0; w < DEC_WAVES; ++w) s += lds[((w * TBK + tb) * 4 + v) * 64 + ln];
+      for (int w = 0; w < NW; ++w) s += lds[((w * TBK + tb) * 4 + v) * 64 + ln];
       const size_t off = (size_t)t * M.ldy + row;
       if (a.out_f32) ((float*)M.Y)[off] = s;
       else ((uint16_t*)M.Y)[off] = to_act16<ACT>(s);
@@ -590,9 +573,10 @@ __device__ inline DecodeArgs decode_scalars(const DecodeArgs& a) {
 }
 
 // grp: index of the workgroup's group of DEC_RG row blocks; n_blocks: row blocks of the unit
-// lds: DEC_WAVES * TBK * 256 floats (fold); r_lds: act dtype [16 TBK][GLOWQ_MAX_RANK]; flag: one word
-// lds_af: DEC_WAVES * DEC_RG rows of 256 words (the A_i fragments' landing place)
-template <int ACT, int TBK>
+// NW: waves of the workgroup (they take the K tiles round robin).
+// lds: NW * TBK * 256 floats (fold); r_lds: act dtype [16 TBK][GLOWQ_MAX_RANK]; flag: one word
+// lds_af: NW * DEC_RG rows of 256 words (the A_i fragments' landing place)
+template <int ACT, int TBK, int NW>
 __device__ inline void decode_workgroup(const DecodeArgs& a_arg, const ProjArgs& p_arg, int grp, int n_blocks,
                                         float* lds, uint16_t* r_lds, uint32_t* flag, uint32_t* lds_af) {
   const DecodeArgs a = decode_scalars(a_arg);
@@ -617,8 +601,8 @@ __device__ inline void decode_workgroup(const DecodeArgs& a_arg, const ProjArgs&
     cf[g] = correction_prefetch(a, M, rb, wave, lane, lds_af + (wave * DEC_RG + g) * 256);
   }
   GLOWQ_STAMP(0);
-  if (a.G == 128) decode_stream_rows<ACT, TBK, true>(a, recb, wave, lane, acc);
-  else decode_stream_rows<ACT, TBK, false>(a, recb, wave, lane, acc);
+  if (a.G == 128) decode_stream_rows<ACT, TBK, true, NW>(a, recb, wave, lane, acc);
+  else decode_stream_rows<ACT, TBK, false, NW>(a, recb, wave, lane, acc);
   GLOWQ_STAMP(1);
   // R, once per workgroup (all row blocks of the group use the same fragments)
   u32x4_t rf[TBK];
@@ -626,7 +610,7 @@ __device__ inline void decode_workgroup(const DecodeArgs& a_arg, const ProjArgs&
   for (int tb = 0; tb < TBK; ++tb) rf[tb] = u32x4_t{0u, 0u, 0u, 0u};
   bool have_r = false;
   if (a.restore && a.r > 0) {                      // uniform
-    have_r = fetch_r_coop<ACT, TBK>(a, p, r_lds, flag);   // (waits for all the wave's loads)
+    have_r = fetch_r_coop<ACT, TBK, NW>(a, p, r_lds, flag);   // (waits for all the wave's loads)
 #pragma unroll
     for (int g = 0; g < DEC_RG; ++g) correction_take(cf[g], lds_af + (wave * DEC_RG + g) * 256, lane);
     if (have_r && cf[0].active && cf[0].ok) {
@@ -647,7 +631,7 @@ __device__ inline void decode_workgroup(const DecodeArgs& a_arg, const ProjArgs&
       for (int tb = 0; tb < TBK; ++tb) acc[g][tb] = mfma16<ACT>(rf[tb], cf[g].af, acc[g][tb]);
     }
     if (g > 0) __syncthreads();                    // the fold area is free again
-    decode_reduce_store<ACT, TBK>(a, M, blk - M.blk_start, wave, lane, acc[g], lds);
+    decode_reduce_store<ACT, TBK, NW>(a, M, blk - M.blk_start, wave, lane, acc[g], lds);
   }
   GLOWQ_STAMP(4);
 }
@@ -677,10 +661,15 @@ __device__ inline void decode_workgroup_small(const DecodeArgs& a_arg, const Pro
   };
   char* lds_wave = lds_x + wave * DecX<TM>::WAVE_BYTES;
   if (a.G == 128) {
-    if constexpr (TM == 1) decode_stream_small<ACT, true, 1, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);
-    else decode_stream_small<ACT, true, 4, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    if constexpr (TM == 1 && ACT == ACT_F16) {
+      decode_stream_small<ACT, true, 1, TM, true>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    } else if constexpr (TM == 1) {
+      decode_stream_small<ACT, true, 1, TM, false>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    } else {
+      decode_stream_small<ACT, true, 4, TM, false>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    }
   } else {
-    decode_stream_small<ACT, false, 4, TM>(a, M, rb, wave, lane, acc, lds_wave, mid);
+    decode_stream_small<ACT, false, 4, TM, false>(a, M, rb, wave, lane, acc, lds_wave, mid);
   }
   GLOWQ_WSTAMP(2);
   if (a.restore && cf.active) {

@@ -34,7 +34,7 @@ __global__ void __launch_bounds__(READ_WAVES * 64) k_probe_stream_read(const pu3
 
 constexpr int MFMA_CHAINS = 8;     // independent accumulators per wave
 constexpr int MFMA_WAVES = 4;
-constexpr int MFMA_WGS = 512;      // two workgroups per compute unit: two waves per SIMD
+constexpr int MFMA_CUS = 256;      // workgroups per "wave per SIMD" of the whole chip
 
 // every wave issues iters x MFMA_CHAINS 16x16x32 matrix instructions on operands that
 // never leave its registers
@@ -79,12 +79,14 @@ int32_t glowq_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, v
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
-int32_t glowq_probe_mfma(int32_t iters, int32_t bf16, float* sink, double* flops, void* stream) {
+int32_t glowq_probe_mfma(int32_t iters, int32_t bf16, int32_t waves_per_simd, float* sink, double* flops,
+                         void* stream) {
   if (!sink || !flops) return -1;
-  if (iters < 1 || iters > (1 << 24)) return -2;
-  if (bf16) k_probe_mfma<true><<<dim3(MFMA_WGS), dim3(MFMA_WAVES * 64), 0, (hipStream_t)stream>>>(iters, sink);
-  else k_probe_mfma<false><<<dim3(MFMA_WGS), dim3(MFMA_WAVES * 64), 0, (hipStream_t)stream>>>(iters, sink);
-  *flops = (double)MFMA_WGS * MFMA_WAVES * (double)iters * MFMA_CHAINS * (2.0 * 16 * 16 * 32);
+  if (iters < 1 || iters > (1 << 24) || waves_per_simd < 1 || waves_per_simd > 8) return -2;
+  const int wgs = MFMA_CUS * waves_per_simd;
+  if (bf16) k_probe_mfma<true><<<dim3(wgs), dim3(MFMA_WAVES * 64), 0, (hipStream_t)stream>>>(iters, sink);
+  else k_probe_mfma<false><<<dim3(wgs), dim3(MFMA_WAVES * 64), 0, (hipStream_t)stream>>>(iters, sink);
+  *flops = (double)wgs * MFMA_WAVES * (double)iters * MFMA_CHAINS * (2.0 * 16 * 16 * 32);
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 

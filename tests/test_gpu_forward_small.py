@@ -32,7 +32,7 @@ def test_tiny_workload(T):
 
 
 @pytest.mark.parametrize("act", ["f16", "bf16"])
-@pytest.mark.parametrize("T", [3, 9, 20, 70, 257])
+@pytest.mark.parametrize("T", [1, 3, 9, 20, 70, 257])
 def test_ragged_group(act, T):
     # rows not a multiple of 32, three module sizes, two quantisation groups; 26 row blocks:
     # the three-block groups of the 4 < T <= 32 path straddle the modules and end ragged
