@@ -315,12 +315,17 @@ def block_forward(units: Sequence[dict], restore_mask: Sequence[int]) -> List[Li
 
 
 def layerwise_forward(unit: dict) -> List[np.ndarray]:
-    """The same outputs with the projection recomputed per module (what the
-    paper's layer-wise baseline does, Sec. 4.3), here with B_i := B_shared."""
+    """The layer-wise comparison point of the latency study (Sec. 4.3): nothing is
+    shared, every module i computes a projection of its own, R_i = X B_i^T, and then
+    Y_i = X What_i^T + R_i A_i^T.  B_i is the module's own right factor `module["B"]`
+    when the unit was set up layer-wise (`build_unit_layerwise`); a module without one
+    takes the unit's shared B, which must reproduce `group_forward` exactly (Prop. 1:
+    the shared projection serves every module)."""
     act, G = unit["act"], unit["G"]
     out = []
     for m in unit["modules"]:
-        R_i = shared_proj(unit["X"], unit["B"], act)
+        B_i = m["B"] if "B" in m else unit["B"]
+        R_i = shared_proj(unit["X"], B_i, act) if unit["r"] > 0 else None
         out.append(module_forward(m, unit["X"], R_i, G, act))
     return out
 
@@ -356,4 +361,24 @@ def build_unit(W_list: Sequence[np.ndarray], X_bits: np.ndarray, r: int, G: int,
             m["A"] = np.zeros((m["d_out"], 0), np.uint16)
         B_bits = np.zeros((0, d), np.uint16)
     return dict(X=np.asarray(X_bits, np.uint16), B=B_bits, modules=modules,
+                act=act, G=G, r=r, d_in=d, T=X_bits.shape[0])
+
+
+def build_unit_layerwise(W_list: Sequence[np.ndarray], X_bits: np.ndarray, r: int, G: int,
+                         act: str) -> dict:
+    """The same quantised modules with layer-wise factors: each error block E_i gets the
+    truncated SVD of its own, E_i ~ A_i B_i (the independent per-layer correction the
+    paper compares against, Sec. 2 and Sec. 4.3), both factors rounded to the activation
+    type.  The unit carries no shared B."""
+    if r <= 0:
+        raise ValueError("layer-wise factors need r > 0")
+    modules = []
+    for W in W_list:
+        qv, s_bits, z_bits = quantize_rtn(W, G)
+        What = dequant(qv, s_bits, z_bits, G, act)
+        A_i, B_i, _ = factors_svd(stack_errors([W], [What]), r)
+        modules.append(dict(wq=pack_int4(qv), scales=s_bits, zeros=z_bits, d_out=W.shape[0],
+                            A=f64_to_bits(A_i, act), B=f64_to_bits(B_i, act)))
+    d = W_list[0].shape[1]
+    return dict(X=np.asarray(X_bits, np.uint16), B=np.zeros((0, d), np.uint16), modules=modules,
                 act=act, G=G, r=r, d_in=d, T=X_bits.shape[0])

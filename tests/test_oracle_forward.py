@@ -135,6 +135,67 @@ def test_rank_r_correction_removes_the_leading_error_energy():
         assert np.linalg.norm(y1 - ref) < 0.97 * np.linalg.norm(y0 - ref)
 
 
+def _tiny_layerwise_unit(seed=11, T=4, d=32, d_outs=(8, 16, 8), r=4, G=16, act="f16"):
+    rng = np.random.default_rng(seed)
+    W = [(rng.standard_normal((o, d)) * 0.02).astype(np.float32) for o in d_outs]
+    X = O.f64_to_bits(rng.standard_normal((T, d)) * np.exp(0.5 * rng.standard_normal(d)), act)
+    u = O.build_unit_layerwise(W, X, r, G, act)
+    u["W"] = W
+    return u
+
+
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+def test_layerwise_forward_uses_each_modules_own_factors(act):
+    # brute force, module by module, with that module's B_i in the place of the shared B
+    u = _tiny_layerwise_unit(act=act)
+    got = O.layerwise_forward(u)
+    assert len({m["B"].tobytes() for m in u["modules"]}) == len(u["modules"])
+    for m, y in zip(u["modules"], got):
+        solo = dict(u, B=m["B"], modules=[m])
+        (ref,) = _brute_force(solo, True)
+        assert y.shape == ref.shape
+        assert np.allclose(y, ref, rtol=1e-13, atol=1e-15)
+        # a solo unit's group forward is the same thing
+        assert np.array_equal(O.group_forward(solo, True)[0], y)
+
+
+def test_layerwise_factors_are_each_blocks_best_rank_r():
+    # Eckart-Young per block: ||E_i - A_i B_i||_F^2 is the tail energy of E_i's spectrum,
+    # and no shared right factor does better on any block (Prop. 1 bounds the stack, the
+    # per-block optimum bounds each block)
+    r, G, act = 4, 16, "f16"
+    u = _tiny_layerwise_unit(r=r, G=G, act=act)
+    shared = O.build_unit(u["W"], u["X"], r, G, act)
+    Bs = O.bits_to_f64(shared["B"], act)
+    for W, m, ms in zip(u["W"], u["modules"], shared["modules"]):
+        What = O.dequant(O.unpack_int4(m["wq"]), m["scales"], m["zeros"], G, act)
+        E = W.astype(np.float64) - What
+        sv = np.linalg.svd(E, compute_uv=False)
+        tail = float(np.sum(sv[r:] ** 2))
+        A_i, B_i = O.bits_to_f64(m["A"], act), O.bits_to_f64(m["B"], act)
+        own = float(np.linalg.norm(E - A_i @ B_i) ** 2)
+        assert abs(own - tail) <= 2e-3 * float(np.sum(sv ** 2))      # 16-bit storage of the factors
+        sh = float(np.linalg.norm(E - O.bits_to_f64(ms["A"], act) @ Bs) ** 2)
+        assert own <= sh * (1 + 1e-3)
+        # balanced split (Eq. 7): both factors carry the square roots of the singular values
+        assert np.allclose(np.linalg.norm(A_i, axis=0), np.sqrt(sv[:r]), rtol=2e-3)
+        assert np.allclose(np.linalg.norm(B_i, axis=1), np.sqrt(sv[:r]), rtol=2e-3)
+
+
+def test_layerwise_setup_of_a_single_module_is_the_shared_setup():
+    rng = np.random.default_rng(5)
+    W = [(rng.standard_normal((24, 64)) * 0.02).astype(np.float32)]
+    X = O.f64_to_bits(rng.standard_normal((3, 64)), "f16")
+    a = O.build_unit(W, X, 8, 32, "f16")
+    b = O.build_unit_layerwise(W, X, 8, 32, "f16")
+    # (singular vectors are fixed up to a sign per rank; the products are unique)
+    Pa = O.bits_to_f64(a["modules"][0]["A"], "f16") @ O.bits_to_f64(a["B"], "f16")
+    Pb = O.bits_to_f64(b["modules"][0]["A"], "f16") @ O.bits_to_f64(b["modules"][0]["B"], "f16")
+    assert np.allclose(Pa, Pb, rtol=0, atol=1e-12)
+    for ya, yb in zip(O.group_forward(a), O.layerwise_forward(b)):
+        assert np.allclose(ya, yb, rtol=1e-12, atol=1e-14)
+
+
 def test_shared_projection_equals_per_module_projection(naive):
     u = _tiny_unit(seed=4, T=5, d=64, d_outs=(16, 8, 8), r=8, G=32)
     shared = O.group_forward(u, True)
