@@ -374,6 +374,8 @@ def build_unit_layerwise(W_list: Sequence[np.ndarray], X_bits: np.ndarray, r: in
         raise ValueError("layer-wise factors need r > 0")
     modules = []
     for W in W_list:
+        if r > min(W.shape):
+            raise ValueError("rank above the size of an error block")
         qv, s_bits, z_bits = quantize_rtn(W, G)
         What = dequant(qv, s_bits, z_bits, G, act)
         A_i, B_i, _ = factors_svd(stack_errors([W], [What]), r)

@@ -27,7 +27,7 @@ def stream() -> int:
 
 
 class DeviceModule:
-    def __init__(self, module: dict, d_in: int, Gs: int):
+    def __init__(self, module: dict, d_in: int, Gs: int, r: int = 0):
         self.d_out = int(module["wq"].shape[0])
         self.wq = dev_words(module["wq"]) if not torch.is_tensor(module["wq"]) else module["wq"]
         self.scales = _as_dev16(module["scales"])
@@ -38,6 +38,7 @@ class DeviceModule:
                                 self.d_out, d_in, Gs, self.prepared.data_ptr(), stream())
         A = module.get("A")
         self.A = None if A is None or A.shape[1] == 0 else _as_dev16(A)
+        assert self.A is None or r == 0 or tuple(self.A.shape) == (self.d_out, r), "A_i must be [d_out][r]"
 
 
 def _as_dev16(x):
@@ -55,7 +56,8 @@ class DeviceUnit:
         self.X = _as_dev16(unit["X"])
         self.T = int(self.X.shape[0])
         self.B = None if self.r == 0 else _as_dev16(unit["B"])
-        self.modules = [DeviceModule(m, self.d_in, self.Gs) for m in unit["modules"]]
+        assert self.B is None or tuple(self.B.shape) == (self.r, self.d_in), "B must be [r][d_in]"
+        self.modules = [DeviceModule(m, self.d_in, self.Gs, self.r) for m in unit["modules"]]
         self.out = self.act if out == "act" else out
         # every output buffer carries canaries: `ldy_pad` columns to the right of the rows
         # and GUARD_ROWS rows below them, all NaN, which no call may touch

@@ -145,6 +145,21 @@ static void abi_checks(void) {
   CHECK(glowq_group_forward_static(&bad, 1, NULL) == GLOWQ_ERR_ALIGN);
   uint32_t word;
   CHECK(glowq_workspace_status(&u, 1, (void*)0x9000, 16, &word, NULL) == GLOWQ_ERR_WORKSPACE);
+  {
+    /* layer-wise mode: the modules become one-module units on the callee's stack */
+    glowq_unit lw = make_unit(ms, 4, 256, 16, 128);
+    lw.n_modules = GLOWQ_MAX_MODULES;
+    const void* Bs[GLOWQ_MAX_MODULES];
+    for (int i = 0; i < GLOWQ_MAX_MODULES; ++i) Bs[i] = (void*)(uintptr_t)(0x2000 + 0x100 * i);
+    size_t solo = 0, all = 0;
+    glowq_unit one = lw; one.n_modules = 1;
+    CHECK(glowq_workspace_bytes(&one, 1, &solo) == GLOWQ_OK);
+    CHECK(glowq_layerwise_workspace_bytes(&lw, 1, &all) == GLOWQ_OK && all == GLOWQ_MAX_MODULES * solo);
+    CHECK(glowq_layerwise_forward(&lw, 1, Bs, (void*)0x9000, all - 16, NULL) == GLOWQ_ERR_WORKSPACE);
+    Bs[GLOWQ_MAX_MODULES - 1] = NULL;
+    CHECK(glowq_layerwise_forward(&lw, 1, Bs, (void*)0x9000, all, NULL) == GLOWQ_ERR_NULL);
+    CHECK(glowq_layerwise_forward(&lw, 1, NULL, (void*)0x9000, all, NULL) == GLOWQ_ERR_NULL);
+  }
   CHECK(glowq_prepared_bytes(40, 128, 128, &bytes) == GLOWQ_OK && bytes == 3 * 272 * 4);
   CHECK(glowq_prepared_bytes(40, 100, 128, &bytes) == GLOWQ_ERR_SHAPE);
   CHECK(glowq_prepare_weights(NULL, NULL, NULL, 64, 256, 64, NULL, NULL) == GLOWQ_ERR_NULL);

@@ -110,3 +110,27 @@ def test_workspace_status_argument_checks():
         with pytest.raises(G.GlowqError) as e:
             G.glowq_workspace_status([u], *args)
         assert e.value.status == status
+
+
+def test_layerwise_argument_checks():
+    """The layer-wise mode forwards the unit's modules as one-module units: its workspace
+    is the sum of theirs, and every module needs a right factor of its own."""
+    u = _unit(n=3)
+    solo = G.glowq_workspace_bytes([_unit(n=1)])
+    need = G.glowq_layerwise_workspace_bytes([u, u])
+    assert need == 6 * solo
+    with pytest.raises(G.GlowqError) as e:                       # a rank-0 unit has nothing to compare
+        G.glowq_layerwise_workspace_bytes([u, _unit(r=0, B=0, A=0)])
+    assert e.value.status == G.GLOWQ_ERR_SHAPE
+    ok = [0x2000, 0x2100, 0x2200, 0x2300, 0x2400, 0x2500]
+    cases = [((ok[:4] + [0] + ok[5:], 0x9000, need), G.GLOWQ_ERR_NULL),
+             ((ok[:5] + [0x2504], 0x9000, need), G.GLOWQ_ERR_ALIGN),
+             ((ok, 0x9000, need - 16), G.GLOWQ_ERR_WORKSPACE),
+             ((ok, 0, need), G.GLOWQ_ERR_WORKSPACE)]
+    for args, status in cases:
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_layerwise_forward([u, u], *args, 0)
+        assert e.value.status == status, args
+    with pytest.raises(G.GlowqError) as e:                       # unsupported shapes stay unsupported
+        G.glowq_layerwise_forward([_unit(n=2, d_in=192)], [0x2000, 0x2100], 0x9000, 1 << 20, 0)
+    assert e.value.status == G.GLOWQ_ERR_UNSUPPORTED
