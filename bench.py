@@ -129,7 +129,8 @@ def run_workload(name, args, torch, want_cpu_baseline):
     import numpy as np
 
     import paper_2603_25385_amd as G
-    from glowq_inputs import CONFIGS, config_units, gen_direct_unit, gen_restore_mask
+    from glowq_inputs import (CONFIGS, config_units, gen_direct_layerwise_B, gen_direct_unit,
+                              gen_restore_mask)
 
     dev = "cuda"
     cfg_id, T, bound = WORKLOADS[name]
@@ -162,18 +163,27 @@ def run_workload(name, args, torch, want_cpu_baseline):
     keep = []               # device buffers stay alive here
     host_unit0 = None       # host copy of unit 0, rotation 0, for the oracle
     y_unit0 = None          # its output buffers
+    compare = args.compare and r > 0
+    lw_B = []               # per rotation: device addresses of the per-module right factors
 
     def build_rotation(rot):
         nonlocal host_unit0, y_unit0
-        descs = []
+        descs, b_ptrs = [], []
+        b16 = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
         for ui, shape in enumerate(shapes):
             src = gen_direct_unit(cfg["seed"], ui, shape, T, r, Gs, act, device=dev)
+            if compare:
+                own = gen_direct_layerwise_B(cfg["seed"] + 1000 * rot, ui, shape, r, act, device=dev)
+                keep.extend(own)
+                b_ptrs.extend(b.data_ptr() for b in own)
             if rot == 0 and ui == 0:
-                b16 = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
                 host_unit0 = dict(
                     X=b16(src["X"]), B=b16(src["B"]), act=act, G=Gs, r=r, d_in=shape.d_in, T=T,
                     modules=[dict(wq=m["wq"].cpu().numpy().view(np.uint32), scales=b16(m["scales"]),
                                   zeros=b16(m["zeros"]), A=b16(m["A"])) for m in src["modules"]])
+                if compare:
+                    for m, b in zip(host_unit0["modules"], own):
+                        m["B"] = b16(b)
             mods, ys = [], []
             for m in src["modules"]:
                 nb = G.glowq_prepared_bytes(m["d_out"], shape.d_in, Gs)
@@ -192,6 +202,8 @@ def run_workload(name, args, torch, want_cpu_baseline):
             descs.append(G.make_unit(src["X"].data_ptr(), src["B"].data_ptr(), mods, T,
                                      shape.d_in, r, Gs, act_code, act_code))
             torch.cuda.synchronize()      # canonical arrays of this unit can go now
+        if compare:
+            lw_B.append(G.pack_pointers(b_ptrs))
         return descs
 
     rotations = []
@@ -231,6 +243,11 @@ def run_workload(name, args, torch, want_cpu_baseline):
     n_failed = int(failed.item())
     parity = check_against_oracle(host_unit0, y_unit0, shapes[0], T, bool(mask[0]), decode, act)
 
+    comparison = None
+    if compare:
+        comparison = run_comparison(torch, G, np, args, steps, rotations, lw_B, n_rot, n_units, cfg,
+                                    ws, ws_bytes, host_unit0, y_unit0, shapes[0], T, decode, act)
+
     gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
     tfs = alg_flops / (ms_per_step * 1e-3) / 1e12
     if decode:
@@ -267,6 +284,11 @@ def run_workload(name, args, torch, want_cpu_baseline):
         "roofline": roof,
         "checks": {"units_that_dropped_their_correction": n_failed, "parity": parity},
     }
+    if comparison is not None:
+        out["comparison"] = comparison
+        if not args.no_checks and not comparison["layerwise_parity"]["ok"]:
+            raise SystemExit("bench.py: layer-wise output of unit 0 does not match the oracle: "
+                             f"{comparison['layerwise_parity']}")
     if args.no_checks:
         pass
     elif n_failed:
@@ -277,6 +299,76 @@ def run_workload(name, args, torch, want_cpu_baseline):
     if want_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host_unit0, shapes[0], T, r, Gs, decode)
     return out
+
+
+# Table 3 of the paper, average change against its Layerwise rows (LLaMA-2 7B and 13B, whole
+# model, end to end on the authors' GPU): context for `comparison`, not a target
+PAPER_TABLE3 = {"decode_ms_per_token_pct": {"GlowQ": -6.61, "GlowQ-S": -27.01},
+                "prefill_ms_pct": {"GlowQ": -3.37, "GlowQ-S": -22.44}}
+
+
+def run_comparison(torch, G, np, args, steps, rotations, lw_B, n_rot, n_units, cfg, ws, ws_bytes,
+                   host_unit0, y_unit0, shape0, T, decode, act):
+    """The same operands three ways (Sec. 4.3): layer-wise (a projection and a right factor
+    per module), GlowQ (one per unit, every unit restored) and GlowQ-S (half of the units
+    restored; a single-unit workload: its one unit not restored)."""
+    from glowq_inputs import gen_restore_mask
+
+    dev = "cuda"
+    cur = lambda: torch.cuda.current_stream().cuda_stream
+    lw_bytes = G.glowq_layerwise_workspace_bytes(rotations[0])
+    lw_ws = torch.empty(lw_bytes, dtype=torch.uint8, device=dev)
+    G.glowq_workspace_init(lw_ws.data_ptr(), lw_bytes, cur())
+    if n_units > 1:
+        half = gen_restore_mask(cfg.get("mask_seed", cfg["seed"]), n_units, 0.5)
+    else:
+        half = np.zeros(1, np.uint8)
+    m_all, m_half = G.pack_mask([1] * n_units), G.pack_mask(half.tolist())
+
+    def step_lw(i):
+        G.glowq_layerwise_forward(rotations[i % n_rot], lw_B[i % n_rot], lw_ws.data_ptr(), lw_bytes, cur())
+
+    def step_all(i):
+        G.glowq_block_forward(rotations[i % n_rot], m_all, ws.data_ptr(), ws_bytes, cur())
+
+    def step_half(i):
+        G.glowq_block_forward(rotations[i % n_rot], m_half, ws.data_ptr(), ws_bytes, cur())
+
+    res = {}
+    for key, fn in (("layerwise", step_lw), ("glowq", step_all), ("glowq_s", step_half)):
+        fn(0)
+        torch.cuda.synchronize()
+        ms, _ = time_steps(torch, fn, steps, args.mode, REPLAYS)
+        res[key] = float(np.median(ms)) * 1e3
+    # the layer-wise outputs of unit 0 against the oracle, module by module (each module is a
+    # one-module unit with its own B)
+    for y in y_unit0:
+        y.fill_(float("nan"))
+    G.glowq_layerwise_forward(rotations[0], lw_B[0], lw_ws.data_ptr(), lw_bytes, cur())
+    torch.cuda.synchronize()
+    worst, tol = 0.0, TOL + ULP[act]
+    rows, sampled = sample_rows(shape0, T, decode)
+    from oracle import naive
+    naive.load()
+    for i, (m, y) in enumerate(zip(host_unit0["modules"], y_unit0)):
+        solo = dict(host_unit0, B=m["B"], modules=[m])
+        (ref,) = naive.group_forward(solo, True, rows=None if rows is None else [rows[i]])
+        got = y.double().cpu().numpy()
+        if rows is not None:
+            got = got[:, rows[i]]
+        worst = max(worst, rel_err(got, ref) if np.isfinite(got).all() else float("inf"))
+    pct = lambda a, b: 100.0 * (a - b) / b
+    return {
+        "us_per_step": res,
+        "restored_units": {"layerwise": n_units, "glowq": n_units, "glowq_s": int(half.sum())},
+        "glowq_vs_layerwise_pct": pct(res["glowq"], res["layerwise"]),
+        "glowq_s_vs_layerwise_pct": pct(res["glowq_s"], res["layerwise"]),
+        "layerwise_parity": {"max_rel_err": worst, "tolerance": tol, "ok": bool(worst <= tol),
+                             "checked": f"unit 0 ({shape0.name}), {sampled} of {shape0.rows} output rows"},
+        "paper_table3_avg_pct": PAPER_TABLE3,
+        "note": "time of the linear layers of the workload only; the paper's table is whole-model "
+                "latency on other hardware",
+    }
 
 
 def sample_rows(shape, T, decode):
@@ -359,6 +451,9 @@ def main() -> int:
     ap.add_argument("--no-checks", action="store_true",
                     help="report the status / parity checks but do not fail on them (tuning runs "
                          "of deliberately incomplete kernels only)")
+    ap.add_argument("--compare", action=argparse.BooleanOptionalAction, default=None,
+                    help="(default: on for the default run, off with --workload) also time the layer-wise mode (a right factor per module), GlowQ with "
+                         "every unit restored and GlowQ-S with half of them, on the same operands")
     ap.add_argument("--restore", default="workload", choices=["workload", "none", "all"],
                     help="restore mask: the workload's own (default), no unit, or every unit "
                          "(to price the correction; the JSON line says how many units were restored)")
@@ -373,6 +468,8 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.compare is None:
+        args.compare = args.workload is None
     if args.workload is not None:
         bound = WORKLOADS[args.workload][2]
         if bound == "copy":
@@ -390,7 +487,8 @@ def main() -> int:
     pf = run_workload("cfg3", args, torch, False)
     out["prefill"] = {k: pf[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "dtype",
                                          "config", "timing", "algorithmic_bytes",
-                                         "algorithmic_flops", "roofline", "checks")}
+                                         "algorithmic_flops", "roofline", "checks", "comparison")
+                      if k in pf}
     out["peaks"] = {"hbm_GBps": HBM_PEAK_GBS, "mfma_f16_bf16_TFLOPs": MFMA_PEAK_TFLOPS}
     print(json.dumps(out))
     return 0

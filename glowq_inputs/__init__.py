@@ -13,6 +13,7 @@ from .synth import (  # noqa: F401
     gen_activations,
     gen_restore_mask,
     gen_direct_unit,
+    gen_direct_layerwise_B,
     to_act_bits,
     from_act_bits,
 )

@@ -194,3 +194,23 @@ def gen_direct_unit(seed: int, unit: int, shape: UnitShape, T: int, r: int,
     out["B"] = B.to(tdt)
     out["X"] = X.to(tdt)
     return out
+
+
+def gen_direct_layerwise_B(seed: int, unit: int, shape: UnitShape, r: int, act: str,
+                           device: str = "cpu") -> list:
+    """One right factor per module, [r][d_in] each, drawn like the shared B of
+    `gen_direct_unit` (same scale, different stream per module): the operands the
+    layer-wise comparison mode reads in the place of the shared factor."""
+    import torch
+
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[act]
+    d_in = shape.d_in
+    e_std = 0.0073 / np.sqrt(12.0)
+    out = []
+    for i, d_out in enumerate(shape.d_outs):
+        gen = torch.Generator(device=device)
+        gen.manual_seed(((int(seed) * 1000003 + int(unit)) * 7919 + 505) * 31 + i)
+        sigma = e_std * (np.sqrt(d_out) + np.sqrt(d_in))
+        B = torch.randn(r, d_in, generator=gen, device=device) * float(np.sqrt(sigma / d_in))
+        out.append(B.to(tdt))
+    return out

@@ -195,6 +195,26 @@ glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,
                                  const uint8_t* restore_mask, void* workspace,
                                  size_t workspace_bytes, void* stream);
 
+/* glowq_layerwise_forward: the comparison point of the latency study (Sec. 4.3,
+ * the table's "Layerwise" rows): nothing is shared.  Every module of every unit has
+ * a right factor of its own, the projection is computed once PER MODULE,
+ * R_i = X B_i^T, and Y_i = X dequant(W_q,i)^T + R_i A_i^T.  B_modules is a HOST array
+ * with one DEVICE pointer per module, unit after unit in module order (the sum of the
+ * units' n_modules entries; each [r][d_in], activation type, 16-byte aligned); the
+ * units' own B is ignored.  The same kernels run: the call treats every module as a
+ * unit of its own and forwards all of them as one block, so launches are shared as
+ * in glowq_block_forward, and only the projections and the reads of B multiply.
+ * Every unit needs r > 0; all units are corrected (no restore mask).  The workspace
+ * holds one slice per module, in the same order, each as long as
+ * glowq_workspace_bytes of that one-module unit: size it with
+ * glowq_layerwise_workspace_bytes, zero it with glowq_workspace_init.  Status words:
+ * word 3 of each slice, as described above. */
+glowq_status glowq_layerwise_workspace_bytes(const glowq_unit* units, int32_t n_units,
+                                             size_t* bytes);
+glowq_status glowq_layerwise_forward(const glowq_unit* units, int32_t n_units,
+                                     const void* const* B_modules, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
 /* ---- inspection hooks (bit-exactness checks of the storage format) ---------
  * Both read the prepared layout of one module (the buffer the forward kernels
  * stream) with small kernels of their own.

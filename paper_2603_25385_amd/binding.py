@@ -74,6 +74,8 @@ def _load():
         "glowq_group_forward": (ctypes.c_int, [up, i32, vp, sz, vp]),
         "glowq_group_forward_static": (ctypes.c_int, [up, i32, vp]),
         "glowq_block_forward": (ctypes.c_int, [up, i32, vp, vp, sz, vp]),
+        "glowq_layerwise_workspace_bytes": (ctypes.c_int, [up, i32, ctypes.POINTER(sz)]),
+        "glowq_layerwise_forward": (ctypes.c_int, [up, i32, ctypes.POINTER(vp), vp, sz, vp]),
         "glowq_debug_unpack": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
         "glowq_debug_dequant": (ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]),
         # include/glowq_probe.h
@@ -210,6 +212,29 @@ def glowq_block_forward(units: Sequence[glowq_unit], restore_mask: Optional[byte
         mask = pack_mask(restore_mask)
     _check(_lib.glowq_block_forward(arr, len(units), mask, workspace or None, workspace_bytes,
                                     stream or None), "glowq_block_forward")
+
+
+def glowq_layerwise_workspace_bytes(units: Sequence[glowq_unit]) -> int:
+    n = ctypes.c_size_t(0)
+    arr = _units_array(units)
+    _check(_lib.glowq_layerwise_workspace_bytes(arr, len(units), ctypes.byref(n)),
+           "glowq_layerwise_workspace_bytes")
+    return n.value
+
+
+def pack_pointers(addresses: Sequence[int]):
+    """A host array of device addresses (one call's B_modules)."""
+    return (ctypes.c_void_p * len(addresses))(*[a or None for a in addresses])
+
+
+def glowq_layerwise_forward(units: Sequence[glowq_unit], B_modules, workspace: int,
+                            workspace_bytes: int, stream: int = 0) -> None:
+    """B_modules: one device address per module, unit after unit (a sequence of ints or
+    the result of pack_pointers)."""
+    arr = _units_array(units)
+    ptrs = B_modules if isinstance(B_modules, ctypes.Array) else pack_pointers(B_modules)
+    _check(_lib.glowq_layerwise_forward(arr, len(units), ptrs, workspace or None,
+                                        workspace_bytes, stream or None), "glowq_layerwise_forward")
 
 
 def glowq_debug_unpack(w_prepared: int, d_out: int, d_in: int, group_size: int, q_out: int,

@@ -2,6 +2,7 @@
 // argument checks, workspace planning and dispatch to the HIP kernels.  Nothing in
 // this file allocates, synchronises or keeps state.
 #include <mutex>
+#include <vector>
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -339,6 +340,54 @@ glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,
     if (workspace_bytes < need) return GLOWQ_ERR_WORKSPACE;
   }
   return forward_all(units, n_units, restore_mask, (char*)workspace, (hipStream_t)stream);
+}
+
+// Every module of the units as a one-module unit, module j (counted over all units) with
+// B_modules[j], or with its unit's own B when B_modules is null (sizing only).
+static glowq_status split_into_solo_units(const glowq_unit* units, int n_units,
+                                          const void* const* B_modules,
+                                          std::vector<glowq_unit>& solo) {
+  for (int i = 0; i < n_units; ++i) {
+    // the shape first, so that n_modules can be trusted
+    glowq_status s = validate(&units[i], false, false);
+    if (s != GLOWQ_OK) return s;
+    if (units[i].r < 1) return GLOWQ_ERR_SHAPE;
+    for (int m = 0; m < units[i].n_modules; ++m) {
+      glowq_unit v = units[i];
+      v.modules = units[i].modules ? &units[i].modules[m] : nullptr;
+      v.n_modules = 1;
+      if (B_modules) {
+        v.B = B_modules[solo.size()];
+        if (!v.B) return GLOWQ_ERR_NULL;
+      }
+      solo.push_back(v);
+    }
+  }
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_layerwise_workspace_bytes(const glowq_unit* units, int32_t n_units,
+                                             size_t* bytes) {
+  if (!units || !bytes) return GLOWQ_ERR_NULL;
+  if (n_units < 1) return GLOWQ_ERR_SHAPE;
+  std::vector<glowq_unit> solo;
+  glowq_status s = split_into_solo_units(units, n_units, nullptr, solo);
+  if (s != GLOWQ_OK) return s;
+  return glowq_workspace_bytes(solo.data(), (int32_t)solo.size(), bytes);
+}
+
+glowq_status glowq_layerwise_forward(const glowq_unit* units, int32_t n_units,
+                                     const void* const* B_modules, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  if (!units || !B_modules) return GLOWQ_ERR_NULL;
+  if (n_units < 1) return GLOWQ_ERR_SHAPE;
+  for (int i = 0; i < n_units; ++i)
+    if (!units[i].modules) return GLOWQ_ERR_NULL;
+  std::vector<glowq_unit> solo;
+  glowq_status s = split_into_solo_units(units, n_units, B_modules, solo);
+  if (s != GLOWQ_OK) return s;
+  return glowq_block_forward(solo.data(), (int32_t)solo.size(), nullptr, workspace,
+                             workspace_bytes, stream);
 }
 
 glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d_in,
