@@ -45,11 +45,11 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   w.off_counters = sizeof(Control);
   // (one word more than blocks: the arrival counter of a last tile of a single block)
   w.ctl_bytes = align_up(w.off_counters + (size_t)(tblocks + 1) * 4, 256);
-  // K slices of the projection: decode spreads B over many compute units; prefill
-  // already has T / 16 token blocks and only needs enough slices to fill the chip
+  // K slices of the projection: prefill already has T / 16 token blocks and only needs
+  // enough slices to fill the chip
   // (a handful of tokens: one wave per (rank, part) and parts of about 2048 channels, so
-  // that a wave has all its loads in flight at once, at most four parts; the consumers
-  // add the parts themselves)
+  // that a wave has all its loads in flight at once, at most four parts; up to 32 tokens:
+  // eight slices, one workgroup each; the consumers add the parts themselves)
   const bool direct = u.T <= 4;
   int ksplit = direct ? (u.d_in + 2047) / 2048 : is_decode(u.T) ? 8 : (256 + tblocks - 1) / tblocks;
   if (direct && ksplit > 4) ksplit = 4;

@@ -311,6 +311,27 @@ template <int ACT> __device__ inline uint16_t to_act16(float v) {
   else return __builtin_bit_cast(uint16_t, (__bf16)v);
 }
 
+// Direct global -> LDS loads issued as assembly: lane l's BYTES land at lds_base + BYTES l
+// (lds_base: byte address in LDS, the same in every lane).  As assembly because the
+// compiler treats the builtin form as an access of unknown kind: while one is in flight
+// EVERY wait it places for any load becomes "wait for all loads", which undoes any
+// double buffering around it.  Issued like this the compiler does not know the load exists:
+// its own waits only ever turn out stricter than needed (an unknown load in flight makes a
+// wait for "all but the last N" cover one load more), and whoever reads the landed bytes
+// places the wait (s_waitcnt vmcnt) by hand; loads of a wave complete in issue order.
+__device__ inline void lds_dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+__device__ inline void lds_dma4(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+__device__ inline uint32_t lds_address(const void* p) {
+  return __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p);
+}
+
 // LDS reads issued as assembly (the result is pending until an lds_wait that names it)
 __device__ inline void lds_read(u32x4_t& v, uint32_t addr, int imm) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(imm) : "memory");

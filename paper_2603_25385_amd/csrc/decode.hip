@@ -20,10 +20,16 @@
 //
 // The correction is r more channels of the same contraction: operand [A_i]
 // against [R].  R = X B^T is produced inside the same launch: the first workgroups
-// of the grid run the projection (K slices, last arrival reduces), everyone else
-// streams weights in the meantime and only polls a ready counter right before the
-// correction -- a kernel boundary would cost as much as the whole weight stream.
+// of the grid run the projection and publish every partial sum as a self-validating
+// 8-byte slot {fp32 bits, launch tag}; everyone else streams weights in the meantime and
+// fetches the slots (adding the K parts) without any flag or counter in between -- a
+// kernel boundary would cost as much as the whole weight stream.
 // The four waves' fp32 tiles are folded through LDS and stored.
+//
+// Waits: every global -> LDS load of these kernels is issued as assembly (lds_dma16 /
+// lds_dma4), and no load the compiler knows of sits behind a branch between a buffer's
+// loads and their use; otherwise the compiler makes each buffer's first use wait for ALL
+// loads in flight, the next buffer's included, and nothing overlaps.
 #include "decode_device.hpp"
 #include "proj_device.hpp"
 #include "launch.hpp"
@@ -36,7 +42,7 @@ static_assert(GLOWQ_MAX_RANK <= DEC_WAVES * 32, "one 32-rank correction step per
 template <int ACT, int TBK, int NW>
 __global__ void __launch_bounds__(NW * 64) k_decode(DecodeArgs a, ProjArgs p, int n_prod,
                                                    int n_blocks) {
-  __shared__ float lds[NW * TBK * 4 * 64];
+  __shared__ float lds[DEC_RG * NW * TBK * 4 * 64];
   __shared__ __attribute__((aligned(16))) uint16_t r_lds[16 * TBK * GLOWQ_MAX_RANK];
   __shared__ uint32_t r_flag;
   __shared__ __attribute__((aligned(1024))) uint32_t lds_af[NW * DEC_RG * 256];

@@ -9,6 +9,11 @@ namespace glowq {
 
 constexpr int DEC_WAVES = 4;
 constexpr int DEC_CHUNK = 4;   // tiles per register buffer; two buffers are in flight
+// `mid` (the fetch of R) is issued behind this tile of the wave's first chunk: measured,
+// one token, 7B-sized group: 9.5 / 9.2 / 9.5 us behind tile 0 / 1 / 3 (earlier, more
+// waves read R before it is published and pay a second fetch; later, the fetch itself
+// ends after the wave's stream)
+constexpr int DEC_MID_TILE = 1;
 
 struct ModuleArgs {
   const uint32_t* rec;   // tile records (see common.hpp)
@@ -126,11 +131,15 @@ __host__ __device__ constexpr int dec_xbuf_bytes(int T) { return (T * DEC_XROW +
 // registers: X is read once per workgroup instead of once per row block.  Two tiles per
 // register buffer, two buffers in flight.
 constexpr int DEC_RG = 3;
-constexpr int DEC_RCH = 2;
+#ifndef GLOWQ_DEC_RCH
+#define GLOWQ_DEC_RCH 2
+#endif
+constexpr int DEC_RCH = GLOWQ_DEC_RCH;
 
-template <int ACT, int TBK, bool G128, int NW>
+// `mark(n)` runs after the n-th buffer has been consumed.
+template <int ACT, int TBK, bool G128, int NW, typename MARK>
 __device__ inline void decode_stream_rows(const DecodeArgs& a, const uint32_t* const (&recb)[DEC_RG],
-                                          int wave, int lane, float4_t (&acc)[DEC_RG][TBK]) {
+                                          int wave, int lane, float4_t (&acc)[DEC_RG][TBK], MARK mark) {
   const int n = lane & 15, kq = lane >> 4;
   const int ktiles = a.K >> 7;
   const int rw = G128 ? 272 : 288;             // words per tile record
@@ -179,14 +188,41 @@ __device__ inline void decode_stream_rows(const DecodeArgs& a, const uint32_t* c
       }
     }
   };
+  // Between the issue of a buffer's loads and its use every load is issued unconditionally:
+  // the compiler can then count, at the wait, how many younger loads may stay in flight
+  // (a load behind a branch in between makes it wait for ALL loads, the next buffer's
+  // included, and the double buffering is gone).  Hence the peeled tail.
+  // (and the scheduler may not move a buffer's first use up into the previous buffer's
+  // run, behind which that buffer's loads have only just been issued)
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+  int done = 0;                                    // buffers consumed; `mark` hears of each
   load(0, A);
-  for (int t0 = 0; t0 < ntw; t0 += 2 * DEC_RCH) {
-    if (t0 + DEC_RCH < ntw) load(t0 + DEC_RCH, B);
+  int t0 = 0;
+  while (t0 + 2 * DEC_RCH < ntw) {                 // both next buffers hold at least one tile
+    load(t0 + DEC_RCH, B);
+    fence();
     run(t0, A);
-    if (t0 + DEC_RCH < ntw) {
-      if (t0 + 2 * DEC_RCH < ntw) load(t0 + 2 * DEC_RCH, A);
-      run(t0 + DEC_RCH, B);
-    }
+    mark(++done);
+    fence();
+    load(t0 + 2 * DEC_RCH, A);
+    fence();
+    run(t0 + DEC_RCH, B);
+    mark(++done);
+    fence();
+    t0 += 2 * DEC_RCH;
+  }
+  if (t0 + DEC_RCH < ntw) {
+    load(t0 + DEC_RCH, B);
+    fence();
+    run(t0, A);
+    mark(++done);
+    fence();
+    run(t0 + DEC_RCH, B);
+    mark(++done);
+  } else {
+    fence();
+    run(t0, A);
+    mark(++done);
   }
 }
 
@@ -198,7 +234,7 @@ __device__ inline void decode_stream_rows(const DecodeArgs& a, const uint32_t* c
 // here.  The operand reads are issued as assembly, one tile ahead of their use, behind a
 // register dependency on such a "later" load, so that neither the compiler's scheduler
 // nor its own bookkeeping of LDS-bound loads has a say in the order.
-// `mid` runs once, after the wave's first chunk has been consumed (or right away if the
+// `mid` runs once, behind tile DEC_MID_TILE of the wave's first chunk (or right away if the
 // wave has no tiles).
 template <int TM> struct DecX {
   static constexpr bool EARLY = TM <= 2;
@@ -223,6 +259,7 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
   const uint16_t* xsrc = a.X + 128 * wave + 8 * lp;
   // reading: lane (i, kq) -> token min(i, T - 1), piece 4 j + kq
   constexpr int xbuf = dec_xbuf_bytes(TM);
+  const uint32_t lds_wave_addr = lds_address(lds_wave);
   const uint32_t xrd = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave +
                        (uint32_t)(min(n, a.T - 1) * DEC_XROW + kq * 16);
 
@@ -232,11 +269,8 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
   auto load_x = [&](int idx) {   // X of chunk idx -> ring buffer idx % NBUF
     const int tx = min(idx * DEC_CHUNK + lc, ntw - 1);
     const uint16_t* src = xsrc + (size_t)tx * (128 * DEC_WAVES);
-    char* dst = lds_wave + (idx % NBUF) * xbuf;
-    for (int tok = 0; tok < a.T; ++tok)
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src + (size_t)tok * a.K),
-          (__attribute__((address_space(3))) void*)(dst + tok * DEC_XROW), 16, 0, 0);
+    const uint32_t dst = lds_wave_addr + (uint32_t)((idx % NBUF) * xbuf);
+    for (int tok = 0; tok < a.T; ++tok) lds_dma16(src + (size_t)tok * a.K, dst + tok * DEC_XROW);
   };
   auto load_chunk = [&](int idx, u32x4_t (&w)[DEC_CHUNK], uint32_t (&s)[DEC_CHUNK][2]) {
     // X first: a tile needs its X before anything else
@@ -281,21 +315,40 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
           decode_tile<ACT, 1, G128, NV>(w[c], s[c][0], s[c][1], [&](int, int j) { return xf[c & 1][j]; }, acc);
         }
       }
+      if (c == DEC_MID_TILE && idx == 0) mid();
     }
     landed = w00;   // the next chunk's X went out before this chunk's weights (EARLY)
   };
 
+  // Between the issue of a chunk's loads and their use every load the compiler knows of is
+  // issued unconditionally (peeled tail), and the scheduler is kept from moving a chunk's
+  // first use up into the previous chunk's run: then each run waits for its own chunk only,
+  // with the next one in flight.
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
   const int nchunks = (ntw + DEC_CHUNK - 1) / DEC_CHUNK;
   if (EARLY) load_x(0);
   load_chunk(0, wA, sA);
-  for (int idx = 0; idx < nchunks; idx += 2) {
-    if (idx + 1 < nchunks) load_chunk(idx + 1, wB, sB);
+  int idx = 0;
+  while (idx + 2 < nchunks) {
+    load_chunk(idx + 1, wB, sB);
+    fence();
     run_chunk(idx, wA, sA);
-    if (idx == 0) mid();
-    if (idx + 1 < nchunks) {
-      if (idx + 2 < nchunks) load_chunk(idx + 2, wA, sA);
-      run_chunk(idx + 1, wB, sB);
-    }
+    fence();
+    load_chunk(idx + 2, wA, sA);
+    fence();
+    run_chunk(idx + 1, wB, sB);
+    fence();
+    idx += 2;
+  }
+  if (idx + 1 < nchunks) {
+    load_chunk(idx + 1, wB, sB);
+    fence();
+    run_chunk(idx, wA, sA);
+    fence();
+    run_chunk(idx + 1, wB, sB);
+  } else {
+    fence();
+    run_chunk(idx, wA, sA);
   }
 }
 
@@ -335,13 +388,10 @@ __device__ inline void r_fetch_issue(const DecodeArgs& a, const ProjArgs& p, int
                                      uint32_t* lds_rf_wave) {
   const bool in = 32 * wave + (lane >> 1) < a.r;
   const uint32_t* src = (const uint32_t*)p.Rpart + (size_t)64 * wave + lane;
+  const uint32_t dst = lds_address(lds_rf_wave);
   for (int t = 0; t < a.T; ++t)
     for (int part = 0; part < p.ksplit; ++part)
-      if (in)
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(src + (size_t)(t * p.ksplit + part) * a.r * 2),
-            (__attribute__((address_space(3))) void*)(lds_rf_wave + (t * DEC_MAX_PARTS + part) * 64),
-            4, 0, 0);
+      if (in) lds_dma4(src + (size_t)(t * p.ksplit + part) * a.r * 2, dst + (t * DEC_MAX_PARTS + part) * 256);
 }
 __device__ inline void r_fetch_take(const DecodeArgs& a, const ProjArgs& p, int lane,
                                     const uint32_t* lds_rf_wave, RFetch& f) {
@@ -431,9 +481,7 @@ __device__ inline CorrFrag correction_prefetch(const DecodeArgs& a, const Module
   c.af = u32x4_t{0u, 0u, 0u, 0u};
   if (c.active) {
     const int row = min(rb * 16 + n, M.d_out - 1);
-    __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(M.A + (size_t)row * a.r + c.j0c),
-        (__attribute__((address_space(3))) void*)lds_row, 16, 0, 0);
+    lds_dma16(M.A + (size_t)row * a.r + c.j0c, lds_address(lds_row));
   }
   return c;
 }
@@ -481,10 +529,11 @@ __device__ inline bool fetch_r_coop(const DecodeArgs& a, const ProjArgs& p, uint
         el[k] = e0 + k * NW * 64 + tid;
         const int ec = min(el[k], n_el - 1);   // clamped: loaded again, not used
         const int tok = ec / hp, rp = ec - tok * hp;
-        const u32x4_t* q = units + (size_t)tok * p.ksplit * hp + rp;
+        const size_t u0 = (size_t)tok * p.ksplit * hp + rp;
 #pragma unroll
-        for (int part = 0; part < MAXP; ++part)
-          vm_load_dev(v[k][part], q + (size_t)min(part, p.ksplit - 1) * hp);
+        for (int part = 0; part < MAXP; ++part) {
+          vm_load_dev(v[k][part], units + u0 + (size_t)min(part, p.ksplit - 1) * hp);
+        }
       }
       vm_wait<0>();
 #pragma unroll
@@ -574,8 +623,8 @@ __device__ inline DecodeArgs decode_scalars(const DecodeArgs& a) {
 
 // grp: index of the workgroup's group of DEC_RG row blocks; n_blocks: row blocks of the unit
 // NW: waves of the workgroup (they take the K tiles round robin).
-// lds: NW * TBK * 256 floats (fold); r_lds: act dtype [16 TBK][GLOWQ_MAX_RANK]; flag: one word
-// lds_af: NW * DEC_RG rows of 256 words (the A_i fragments' landing place)
+// lds: DEC_RG * NW * TBK * 256 floats (fold); r_lds: act dtype [16 TBK][GLOWQ_MAX_RANK];
+// flag: one word; lds_af: NW * DEC_RG rows of 256 words (the A_i fragments' landing place)
 template <int ACT, int TBK, int NW>
 __device__ inline void decode_workgroup(const DecodeArgs& a_arg, const ProjArgs& p_arg, int grp, int n_blocks,
                                         float* lds, uint16_t* r_lds, uint32_t* flag, uint32_t* lds_af) {
@@ -600,17 +649,24 @@ __device__ inline void decode_workgroup(const DecodeArgs& a_arg, const ProjArgs&
     recb[g] = M.rec + ((size_t)rb * ktiles + wave) * rw;
     cf[g] = correction_prefetch(a, M, rb, wave, lane, lds_af + (wave * DEC_RG + g) * 256);
   }
-  GLOWQ_STAMP(0);
-  if (a.G == 128) decode_stream_rows<ACT, TBK, true, NW>(a, recb, wave, lane, acc);
-  else decode_stream_rows<ACT, TBK, false, NW>(a, recb, wave, lane, acc);
-  GLOWQ_STAMP(1);
+  const bool corr = a.restore && a.r > 0;                       // uniform
+  GLOWQ_WTRACE_DECL;
+  GLOWQ_WSTAMP(0);
+  GLOWQ_WTRACE_HWID(7);
+  auto mark = [&](int done) {
+    if (done == 1) GLOWQ_WSTAMP(1);
+  };
+  if (a.G == 128) decode_stream_rows<ACT, TBK, true, NW>(a, recb, wave, lane, acc, mark);
+  else decode_stream_rows<ACT, TBK, false, NW>(a, recb, wave, lane, acc, mark);
+  GLOWQ_WSTAMP(2);
   // R, once per workgroup (all row blocks of the group use the same fragments)
   u32x4_t rf[TBK];
 #pragma unroll
   for (int tb = 0; tb < TBK; ++tb) rf[tb] = u32x4_t{0u, 0u, 0u, 0u};
   bool have_r = false;
-  if (a.restore && a.r > 0) {                      // uniform
-    have_r = fetch_r_coop<ACT, TBK, NW>(a, p, r_lds, flag);   // (waits for all the wave's loads)
+  if (corr) {                                      // uniform
+    // (waits for all the wave's loads)
+    have_r = fetch_r_coop<ACT, TBK, NW>(a, p, r_lds, flag);
 #pragma unroll
     for (int g = 0; g < DEC_RG; ++g) correction_take(cf[g], lds_af + (wave * DEC_RG + g) * 256, lane);
     if (have_r && cf[0].active && cf[0].ok) {
@@ -621,19 +677,45 @@ __device__ inline void decode_workgroup(const DecodeArgs& a_arg, const ProjArgs&
       }
     }
   }
+  GLOWQ_WSTAMP(3);
+  // all row blocks' tiles go through LDS together: one barrier for the group
 #pragma unroll
   for (int g = 0; g < DEC_RG; ++g) {
-    const int blk = grp * DEC_RG + g;
-    if (blk >= n_blocks) break;                    // uniform
-    const ModuleArgs M = find_module(a_arg, blk);
     if (cf[g].active && have_r) {
 #pragma unroll
       for (int tb = 0; tb < TBK; ++tb) acc[g][tb] = mfma16<ACT>(rf[tb], cf[g].af, acc[g][tb]);
     }
-    if (g > 0) __syncthreads();                    // the fold area is free again
-    decode_reduce_store<ACT, TBK, NW>(a, M, blk - M.blk_start, wave, lane, acc[g], lds);
+#pragma unroll
+    for (int tb = 0; tb < TBK; ++tb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) lds[(((g * NW + wave) * TBK + tb) * 4 + v) * 64 + lane] = acc[g][tb][v];
   }
-  GLOWQ_STAMP(4);
+  __syncthreads();
+  GLOWQ_WSTAMP(4);
+  if (wave < 4) {                                  // 256 threads <-> (v, lane) of one token block
+#pragma unroll
+    for (int g = 0; g < DEC_RG; ++g) {
+      const int blk = grp * DEC_RG + g;
+      if (blk >= n_blocks) break;                  // uniform
+      const ModuleArgs M = find_module(a_arg, blk);
+      const int v = wave;
+      const int row = (blk - M.blk_start) * 16 + (lane & 15);
+#pragma unroll
+      for (int tb = 0; tb < TBK; ++tb) {
+        const int t = 16 * tb + 4 * (lane >> 4) + v;
+        if (t < a.T && row < M.d_out) {
+          float s = 0.f;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) s += lds[(((g * NW + w) * TBK + tb) * 4 + v) * 64 + lane];
+          const size_t off = (size_t)t * M.ldy + row;
+          if (a.out_f32) ((float*)M.Y)[off] = s;
+          else ((uint16_t*)M.Y)[off] = to_act16<ACT>(s);
+        }
+      }
+    }
+  }
+  GLOWQ_WSTAMP(6);
+  GLOWQ_WTRACE_FLUSH();
 }
 
 // T <= 4.  lds: DEC_WAVES * 256 floats for the fold; lds_x: DEC_WAVES * DecX<TM>::WAVE_BYTES;

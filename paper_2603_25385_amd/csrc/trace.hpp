@@ -39,6 +39,9 @@ static __device__ unsigned long long g_wtrace[2048][4][8];
 }
 #define GLOWQ_WTRACE_DECL unsigned long long glowq_wt_[8] = {0, 0, 0, 0, 0, 0, 0, 0}
 #define GLOWQ_WSTAMP(slot) glowq_wt_[slot] = __builtin_amdgcn_s_memrealtime()
+#define GLOWQ_WTRACE_HWID(slot)                                                                     \
+  glowq_wt_[slot] = ((unsigned long long)__builtin_amdgcn_s_getreg((20 << 0) | (31 << 11)) << 32) | \
+                    __builtin_amdgcn_s_getreg((4 << 0) | (31 << 11))
 #define GLOWQ_WTRACE_FLUSH()                                                      \
   do {                                                                            \
     const unsigned b_ = blockIdx.x, w_ = threadIdx.x >> 6;                        \
@@ -62,6 +65,7 @@ static __device__ unsigned long long g_wtrace[2048][4][8];
 #define GLOWQ_TRACE_EXPORT(name)
 #define GLOWQ_WTRACE_DECL
 #define GLOWQ_WSTAMP(slot) do { } while (0)
+#define GLOWQ_WTRACE_HWID(slot) do { } while (0)
 #define GLOWQ_WTRACE_FLUSH() do { } while (0)
 #define GLOWQ_WTRACE_EXPORT(name)
 #endif
