@@ -320,12 +320,14 @@ template <int ACT> __device__ inline uint16_t to_act16(float v) {
 // wait for "all but the last N" cover one load more), and whoever reads the landed bytes
 // places the wait (s_waitcnt vmcnt) by hand; loads of a wave complete in issue order.
 __device__ inline void lds_dma16(const void* gptr, uint32_t lds_base) {
+  const uint32_t m = __builtin_amdgcn_readfirstlane(lds_base);   // (a scalar register, whatever the compiler believes)
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+               : : "v"(gptr), "s"(m) : "memory", "m0");
 }
 __device__ inline void lds_dma4(const void* gptr, uint32_t lds_base) {
+  const uint32_t m = __builtin_amdgcn_readfirstlane(lds_base);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-               : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+               : : "v"(gptr), "s"(m) : "memory", "m0");
 }
 __device__ inline uint32_t lds_address(const void* p) {
   return __builtin_amdgcn_readfirstlane(

@@ -47,15 +47,15 @@ __global__ void __launch_bounds__(MFMA_WAVES * 64) k_probe_mfma(int iters, float
   pfloat4 acc[MFMA_CHAINS];
 #pragma unroll
   for (int c = 0; c < MFMA_CHAINS; ++c) acc[c] = pfloat4{0.f, 0.f, 0.f, 0.f};
+  // (as assembly, accumulators tied in place: left to the compiler the loop rotates its
+  // accumulators through a dozen register moves per matrix instruction)
   for (int i = 0; i < iters; ++i) {
 #pragma unroll
     for (int c = 0; c < MFMA_CHAINS; ++c) {
       if constexpr (BF16)
-        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(pbf16x8, a),
-                                                         __builtin_bit_cast(pbf16x8, b), acc[c], 0, 0, 0);
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[c]) : "v"(a), "v"(b));
       else
-        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(phalf8, a),
-                                                        __builtin_bit_cast(phalf8, b), acc[c], 0, 0, 0);
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc[c]) : "v"(a), "v"(b));
     }
   }
   float s = 0.f;
