@@ -18,8 +18,9 @@ activation type, and the setup that manufactures the stored operands:
 round-to-nearest asymmetric INT4 (W4A16, group size G along d; Sec. 4.1),
 errors E_i = W_i - What_i stacked by rows (App. A.0), the truncated SVD of the
 stack (Sec. 3.1.1, Prop. 1; App. A.1.2) split into balanced factors
-(Eq. 7 / Eqs. A.1.9a-c), the least-squares block recovery (Eq. A.1.10), and the
-QR-reduced randomised variant (Alg. 1).
+(Eq. 7 / Eqs. A.1.9a-c), the least-squares block recovery (Eq. A.1.10), the
+QR-reduced randomised variant (Alg. 1), and the importance scores and top-k selection
+of GlowQ-S (Eqs. 10-11).
 
 Every operand of the forward is the *stored* 16-bit value widened to float64;
 all accumulation is float64; R is never re-rounded.  Pins for every function
@@ -328,6 +329,48 @@ def layerwise_forward(unit: dict) -> List[np.ndarray]:
         R_i = shared_proj(unit["X"], B_i, act) if unit["r"] > 0 else None
         out.append(module_forward(m, unit["X"], R_i, G, act))
     return out
+
+
+# --------------------------------------------------------------------------
+# importance of a unit and the GlowQ-S selection  (Sec. 3.3, Eqs. 10-11)
+# --------------------------------------------------------------------------
+def importance_ner(W_list: Sequence[np.ndarray], What_list: Sequence[np.ndarray]) -> float:
+    """g_ner(u) = ||E_u||_F^2 / ||W_u||_F^2 over all modules of the unit (Eq. 11);
+    E_u is the stacked error, W_u the stacked full-precision weight."""
+    e = sum(float(np.sum((np.asarray(W, np.float64) - np.asarray(Wh, np.float64)) ** 2))
+            for W, Wh in zip(W_list, What_list))
+    w = sum(float(np.sum(np.asarray(W, np.float64) ** 2)) for W in W_list)
+    return e / w
+
+
+def importance_ec(M_u: np.ndarray, r: int) -> float:
+    """g_ec(u) = sum_{j<=r} sigma_j(M_u)^2 / ||M_u||_F^2 (Eq. 10): the share of the
+    aligned error's energy that r ranks capture.  M_u is the stacked error after
+    covariance alignment; with Sigma_x = I (the reading the workloads use) M_u = E_u."""
+    sv = np.linalg.svd(np.asarray(M_u, np.float64), compute_uv=False)
+    return float(np.sum(sv[:r] ** 2) / np.sum(sv ** 2))
+
+
+def importance_ec_from_factors(A_bits_list: Sequence[np.ndarray], B_bits: np.ndarray, act: str,
+                               error_energy: float) -> float:
+    """The same share read off the STORED balanced factors: the columns of A = U S^(1/2)
+    and the rows of B = S^(1/2) V^T are orthogonal with ||a_j||^2 = ||b_j||^2 = sigma_j
+    (Eqs. A.1.9a-b), so sum_j ||a_j||^2 ||b_j||^2 = sum_j sigma_j^2.  This is what can be
+    evaluated where only the stored operands are at hand; it differs from importance_ec
+    by the 16-bit rounding of the factors."""
+    A = np.concatenate([bits_to_f64(a, act) for a in A_bits_list], axis=0)
+    B = bits_to_f64(B_bits, act)
+    return float(np.sum(np.sum(A ** 2, axis=0) * np.sum(B ** 2, axis=1)) / error_energy)
+
+
+def select_units(scores: Sequence[float], k: int) -> np.ndarray:
+    """GlowQ-S: the k units with the highest score are restored (Sec. 3.3); among equal
+    scores the unit with the lower index comes first.  Returns the 0/1 mask."""
+    scores = np.asarray(scores, np.float64)
+    order = np.argsort(-scores, kind="stable")
+    mask = np.zeros(len(scores), np.uint8)
+    mask[order[:max(0, min(int(k), len(scores)))]] = 1
+    return mask
 
 
 # --------------------------------------------------------------------------
