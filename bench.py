@@ -55,6 +55,8 @@ WORKLOADS = {
     "stream24": (0, 0, "stream"),
     "mfma_f16": (0, 0, "mfma_probe"),
     "mfma_bf16": (0, 0, "mfma_probe"),
+    # offline side of GlowQ-S: the importance scores of the Llama-2-7B-shaped QKV unit
+    "cfg2_scores": (2, 0, "scores"),
 }
 METRIC = "grouped W4+low-rank forward: decode HBM GB/s & us/group; prefill TFLOP/s"
 
@@ -478,6 +480,8 @@ def main() -> int:
             return stream_ceiling(torch, args)
         if bound == "mfma_probe":
             return mfma_ceiling(torch, args, args.workload.endswith("bf16"))
+        if bound == "scores":
+            return importance_scores(torch, args)
         out = run_workload(args.workload, args, torch, not args.no_cpu_baseline)
         out["peaks"] = {"hbm_GBps": HBM_PEAK_GBS, "mfma_f16_bf16_TFLOPs": MFMA_PEAK_TFLOPS}
         print(json.dumps(out))
@@ -491,6 +495,85 @@ def main() -> int:
                       if k in pf}
     out["peaks"] = {"hbm_GBps": HBM_PEAK_GBS, "mfma_f16_bf16_TFLOPs": MFMA_PEAK_TFLOPS}
     print(json.dumps(out))
+    return 0
+
+
+def importance_scores(torch, args):
+    """glowq_unit_importance (Sec. 3.3, Eqs. 10-11) on the QKV unit of workload 2: fp32
+    weights, prepared weights and stored factors in, two float64 scores out; bound by the
+    bytes of the fp32 weights.  Checked against the oracle on the first operand set."""
+    import numpy as np
+
+    import paper_2603_25385_amd as G
+    from glowq_inputs import CONFIGS, config_units, gen_direct_unit
+    from oracle import glowq_oracle as O
+
+    cfg = CONFIGS[2]
+    shape = config_units(2)[0]
+    r, Gs, act = cfg["r"], cfg["G"], cfg["act"]
+    steps = args.steps or 20
+    st = torch.cuda.current_stream().cuda_stream
+    act_code = {"f16": G.GLOWQ_F16, "bf16": G.GLOWQ_BF16}[act]
+    sets, keep, host0 = [], [], None
+    gen = torch.Generator(device="cuda")
+    for rot in range(3):
+        src = gen_direct_unit(cfg["seed"] + rot, 0, shape, 1, r, Gs, act, device="cuda")
+        mods, Ws = [], []
+        for i, m in enumerate(src["modules"]):
+            nb = G.glowq_prepared_bytes(m["d_out"], shape.d_in, Gs)
+            prep = torch.empty(nb, dtype=torch.uint8, device="cuda")
+            G.glowq_prepare_weights(m["wq"].data_ptr(), m["scales"].data_ptr(), m["zeros"].data_ptr(),
+                                    m["d_out"], shape.d_in, Gs, prep.data_ptr(), st)
+            gen.manual_seed(1000 * rot + i)
+            W = torch.randn(m["d_out"], shape.d_in, generator=gen, device="cuda") * 0.02
+            keep.extend([prep, m["A"], W])
+            Ws.append(W)
+            mods.append(G.make_module(prep.data_ptr(), m["A"].data_ptr(), 0, m["d_out"], m["d_out"]))
+        keep.append(src["B"])
+        unit = G.make_unit(0, src["B"].data_ptr(), mods, 1, shape.d_in, r, Gs, act_code, act_code)
+        sets.append((unit, G.pack_pointers([w.data_ptr() for w in Ws])))
+        if rot == 0:
+            b16 = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+            host0 = dict(W=[w.cpu().numpy() for w in Ws], B=b16(src["B"]),
+                         modules=[dict(wq=m["wq"].cpu().numpy().view(np.uint32), scales=b16(m["scales"]),
+                                       zeros=b16(m["zeros"]), A=b16(m["A"])) for m in src["modules"]])
+        torch.cuda.synchronize()
+    scratch = torch.empty(G.GLOWQ_IMPORTANCE_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+    scores = torch.zeros(2, dtype=torch.float64, device="cuda")
+
+    def step(i):
+        u, w = sets[i % len(sets)]
+        G.glowq_unit_importance(u, w, scratch.data_ptr(), scores.data_ptr(),
+                                torch.cuda.current_stream().cuda_stream)
+
+    for i in range(3):
+        step(i)
+    torch.cuda.synchronize()
+    ms, _ = time_steps(torch, step, steps, args.mode, REPLAYS)
+    med = float(np.median(ms))
+    step(0)
+    torch.cuda.synchronize()
+    got = scores.cpu().numpy()
+    What = [O.dequant(O.unpack_int4(m["wq"]), m["scales"], m["zeros"], Gs, act) for m in host0["modules"]]
+    ner = O.importance_ner(host0["W"], What)
+    energy = sum(float(np.sum((w.astype(np.float64) - wh) ** 2)) for w, wh in zip(host0["W"], What))
+    ec = O.importance_ec_from_factors([m["A"] for m in host0["modules"]], host0["B"], act, energy)
+    err = max(abs(got[0] - ner) / ner, abs(got[1] - ec) / ec)
+    by = shape.rows * shape.d_in * 4 + shape.rows * shape.d_in // 2 + shape.rows * (shape.d_in // Gs) * 4 \
+        + shape.rows * r * 2 + r * shape.d_in * 2
+    gbs = by / (med * 1e-3) / 1e9
+    out = {"metric": "importance scores of one unit (GlowQ-S, Eqs. 10-11): HBM GB/s", "value": gbs, "unit": "GB/s",
+           "steps": steps, "ms_per_step": med, "us_per_step_min": min(ms) * 1e3, "dtype": "f64",
+           "data": "synthetic", "config": {"workload": f"{cfg['name']} importance scores (cfg2_scores)",
+                                           "launch": args.mode},
+           "algorithmic_bytes": by,
+           "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": gbs / HBM_PEAK_GBS, "traffic": None},
+           "checks": {"parity": {"max_rel_err": float(err), "tolerance": 1e-9, "ok": bool(err <= 1e-9),
+                                 "scores": [float(got[0]), float(got[1])]}}}
+    print(json.dumps(out))
+    if not args.no_checks and err > 1e-9:
+        raise SystemExit(f"bench.py: importance scores do not match the oracle: {out['checks']}")
     return 0
 
 

@@ -215,6 +215,30 @@ glowq_status glowq_layerwise_forward(const glowq_unit* units, int32_t n_units,
                                      const void* const* B_modules, void* workspace,
                                      size_t workspace_bytes, void* stream);
 
+/* ---- importance of a unit and the GlowQ-S selection (Sec. 3.3, Eqs. 10-11) ----
+ * glowq_unit_importance: the two scores by which units are ranked for selective
+ * restore, from the unit's full-precision weights, its prepared weights and its stored
+ * factors (offline work, no part of the forward):
+ *   scores[0] = g_ner = ||E_u||_F^2 / ||W_u||_F^2   (Eq. 11), E_u = W_u - dequant(W_q,u),
+ *               the dequantised weight being the stored 16-bit value, all modules stacked;
+ *   scores[1] = g_ec  = sum_{j<=r} sigma_j^2 / ||E_u||_F^2 (Eq. 10 with Sigma_x = I), the
+ *               numerator read off the balanced factors as sum_j ||A[:,j]||^2 ||B[j,:]||^2
+ *               (exact for factors that come from the stack's SVD, Eqs. A.1.9a-b, up to
+ *               their 16-bit storage); 0 for r == 0.
+ * W_modules: HOST array of u->n_modules DEVICE pointers, fp32 [d_out][d_in] each, 16-byte
+ * aligned.  Of `u` the call reads modules[i].w_prepared / A / d_out, B, r, d_in,
+ * group_size and act_dtype (X, Y, T are ignored).  scratch: DEVICE, 8-byte aligned,
+ * GLOWQ_IMPORTANCE_SCRATCH_BYTES, any contents (cleared by the call).  scores: DEVICE
+ * double[2].  All sums are float64; their order varies from run to run (atomic adds), so
+ * results agree to rounding, not to the bit.
+ * glowq_select_units: the restore mask of the k highest scores (HOST in, HOST out; among
+ * equal scores the lower index first); mask[i] = 1 for selected units. */
+#define GLOWQ_IMPORTANCE_SCRATCH_BYTES 4096
+glowq_status glowq_unit_importance(const glowq_unit* u, const float* const* W_modules,
+                                   void* scratch, double* scores, void* stream);
+glowq_status glowq_select_units(const double* scores, int32_t n_units, int32_t k,
+                                uint8_t* restore_mask);
+
 /* ---- inspection hooks (bit-exactness checks of the storage format) ---------
  * Both read the prepared layout of one module (the buffer the forward kernels
  * stream) with small kernels of their own.

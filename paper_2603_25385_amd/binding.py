@@ -76,6 +76,9 @@ def _load():
         "glowq_block_forward": (ctypes.c_int, [up, i32, vp, vp, sz, vp]),
         "glowq_layerwise_workspace_bytes": (ctypes.c_int, [up, i32, ctypes.POINTER(sz)]),
         "glowq_layerwise_forward": (ctypes.c_int, [up, i32, ctypes.POINTER(vp), vp, sz, vp]),
+        "glowq_unit_importance": (ctypes.c_int, [up, ctypes.POINTER(vp), vp, vp, vp]),
+        "glowq_select_units": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), i32, i32,
+                                              ctypes.POINTER(ctypes.c_uint8)]),
         "glowq_debug_unpack": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
         "glowq_debug_dequant": (ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]),
         # include/glowq_probe.h
@@ -235,6 +238,24 @@ def glowq_layerwise_forward(units: Sequence[glowq_unit], B_modules, workspace: i
     ptrs = B_modules if isinstance(B_modules, ctypes.Array) else pack_pointers(B_modules)
     _check(_lib.glowq_layerwise_forward(arr, len(units), ptrs, workspace or None,
                                         workspace_bytes, stream or None), "glowq_layerwise_forward")
+
+
+GLOWQ_IMPORTANCE_SCRATCH_BYTES = 4096
+
+
+def glowq_unit_importance(unit: glowq_unit, W_modules, scratch: int, scores: int, stream: int = 0) -> None:
+    """W_modules: one device address (fp32 [d_out][d_in]) per module; scores: device double[2]."""
+    ptrs = W_modules if isinstance(W_modules, ctypes.Array) else pack_pointers(W_modules)
+    _check(_lib.glowq_unit_importance(ctypes.byref(unit), ptrs, scratch or None, scores or None,
+                                      stream or None), "glowq_unit_importance")
+
+
+def glowq_select_units(scores: Sequence[float], k: int) -> list:
+    n = len(scores)
+    arr = (ctypes.c_double * n)(*scores)
+    mask = (ctypes.c_uint8 * n)()
+    _check(_lib.glowq_select_units(arr, n, k, mask), "glowq_select_units")
+    return list(mask)
 
 
 def glowq_debug_unpack(w_prepared: int, d_out: int, d_in: int, group_size: int, q_out: int,

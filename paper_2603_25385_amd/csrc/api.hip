@@ -1,6 +1,7 @@
 // C ABI of the GlowQ group forward (declared in include/glowq.h): host-side
 // argument checks, workspace planning and dispatch to the HIP kernels.  Nothing in
 // this file allocates, synchronises or keeps state.
+#include <algorithm>
 #include <mutex>
 #include <vector>
 #include "common.hpp"
@@ -388,6 +389,37 @@ glowq_status glowq_layerwise_forward(const glowq_unit* units, int32_t n_units,
   if (s != GLOWQ_OK) return s;
   return glowq_block_forward(solo.data(), (int32_t)solo.size(), nullptr, workspace,
                              workspace_bytes, stream);
+}
+
+glowq_status glowq_unit_importance(const glowq_unit* u, const float* const* W_modules,
+                                   void* scratch, double* scores, void* stream) {
+  if (!u || !W_modules || !scratch || !scores) return GLOWQ_ERR_NULL;
+  glowq_status s = validate(u, false, false);
+  if (s != GLOWQ_OK) return s;
+  if (!u->modules) return GLOWQ_ERR_NULL;
+  static_assert(GLOWQ_IMPORTANCE_SCRATCH_BYTES >= (2 + 3 * GLOWQ_MAX_RANK) * sizeof(double), "scratch layout");
+  if (((uintptr_t)scratch & 7u) || ((uintptr_t)scores & 7u)) return GLOWQ_ERR_ALIGN;
+  if (u->r > 0 && (!u->B || misaligned(u->B))) return u->B ? GLOWQ_ERR_ALIGN : GLOWQ_ERR_NULL;
+  for (int i = 0; i < u->n_modules; ++i) {
+    const glowq_module& m = u->modules[i];
+    if (!W_modules[i] || !m.w_prepared || (u->r > 0 && !m.A)) return GLOWQ_ERR_NULL;
+    if (misaligned(W_modules[i]) || misaligned(m.w_prepared) || (u->r > 0 && misaligned(m.A)))
+      return GLOWQ_ERR_ALIGN;
+  }
+  return hip_status(launch_importance(*u, W_modules, (double*)scratch, scores, (hipStream_t)stream));
+}
+
+glowq_status glowq_select_units(const double* scores, int32_t n_units, int32_t k,
+                                uint8_t* restore_mask) {
+  if (!scores || !restore_mask) return GLOWQ_ERR_NULL;
+  if (n_units < 1 || k < 0) return GLOWQ_ERR_SHAPE;
+  std::vector<int> order(n_units);
+  for (int i = 0; i < n_units; ++i) order[i] = i;
+  // highest score first; equal scores keep their index order
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return scores[a] > scores[b]; });
+  for (int i = 0; i < n_units; ++i) restore_mask[i] = 0;
+  for (int i = 0; i < k && i < n_units; ++i) restore_mask[order[i]] = 1;
+  return GLOWQ_OK;
 }
 
 glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d_in,

@@ -34,6 +34,8 @@ hipError_t launch_debug_unpack(const void* prepared, int d_out, int d_in, int G,
 hipError_t launch_debug_dequant(const void* prepared, int d_out, int d_in, int G, int act,
                                 void* w_out, hipStream_t st);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_importance(const glowq_unit& u, const float* const* W_modules, double* scratch,
+                             double* scores, hipStream_t st);
 // slices' start offsets in units of 256 bytes (every slice is 256-byte aligned)
 constexpr int STATUS_BATCH = 256;
 struct StatusBatch {

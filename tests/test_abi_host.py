@@ -134,3 +134,30 @@ def test_layerwise_argument_checks():
     with pytest.raises(G.GlowqError) as e:                       # unsupported shapes stay unsupported
         G.glowq_layerwise_forward([_unit(n=2, d_in=192)], [0x2000, 0x2100], 0x9000, 1 << 20, 0)
     assert e.value.status == G.GLOWQ_ERR_UNSUPPORTED
+
+
+def test_select_units_is_the_oracles_selection():
+    from oracle import glowq_oracle as O
+    import numpy as np
+    rng = np.random.default_rng(3)
+    for n in (1, 2, 7, 40):
+        s = np.round(rng.random(n), 1)                # many ties
+        for k in (0, 1, n // 2, n, n + 3):
+            assert G.glowq_select_units(s.tolist(), k) == O.select_units(s, k).tolist()
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_select_units([0.5], -1)
+    assert e.value.status == G.GLOWQ_ERR_SHAPE
+
+
+def test_unit_importance_argument_checks():
+    u = _unit(n=2)
+    for args, status in [(([0x7000, 0], 0x9000, 0xA000), G.GLOWQ_ERR_NULL),
+                         (([0x7000, 0x7100], 0, 0xA000), G.GLOWQ_ERR_NULL),
+                         (([0x7000, 0x7100], 0x9004, 0xA000), G.GLOWQ_ERR_ALIGN),
+                         (([0x7000, 0x7104], 0x9000, 0xA000), G.GLOWQ_ERR_ALIGN)]:
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_unit_importance(u, *args, 0)
+        assert e.value.status == status, args
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_unit_importance(_unit(B=0), [0x7000], 0x9000, 0xA000, 0)
+    assert e.value.status == G.GLOWQ_ERR_NULL
