@@ -239,6 +239,42 @@ glowq_status glowq_unit_importance(const glowq_unit* u, const float* const* W_mo
 glowq_status glowq_select_units(const double* scores, int32_t n_units, int32_t k,
                                 uint8_t* restore_mask);
 
+/* ---- the shared factors of a unit, computed on the GPU (offline) ------------
+ * glowq_factorize_unit: balanced rank-r factors of the unit's stacked quantisation error
+ * by the randomised, covariance-aligned procedure of Alg. 1 (App. A.3-A.4), from the
+ * unit's full-precision weights and its prepared weights:
+ *   E_cat = [W_i - dequant(W_q,i)]_i stacked by rows (m = sum of d_out rows),
+ *   M     = E_cat diag(sigma_x)^(1/2)                      (sigma_x_diag NULL: identity),
+ *   Y     = M Omega, then q times Y <- M (M^T Y);  Q = orth(Y);  Q^T M = U~ S V^T,
+ *   A     = Q U~_r S_r^(1/2)  (rows split by module),  B = S_r^(1/2) V_r^T diag(sigma_x)^(-1/2)
+ * (a zero variance gets a zero in the inverse root).  The products run on the stack itself
+ * instead of on the triangular factor of its thin QR: with M_core = Q_e^T M every quantity
+ * is the same or Q_e times the core's, so A and B are those of Alg. 1 up to rounding and up
+ * to the sign of each rank (the pair (A[:,j], B[j,:]) may come out negated).
+ * u: n_modules, modules[i].w_prepared / d_out, d_in, group_size and act_dtype are read
+ * (X, Y, T, r, A, B are ignored).  r: the rank, a multiple of 8 up to GLOWQ_MAX_RANK and
+ * at most m; p >= 0 the oversampling, r + p <= GLOWQ_MAX_SKETCH and <= d_in; q the power
+ * steps, at most GLOWQ_MAX_POWER_STEPS.  W_modules: HOST array of n_modules DEVICE pointers, fp32
+ * [d_out][d_in], 16-byte aligned.  sigma_x_diag: DEVICE double [d_in] or NULL.  Omega:
+ * DEVICE double [d_in][r + p] row-major, the Gaussian test matrix, drawn by the caller.
+ * workspace: DEVICE, 256-byte aligned, glowq_factorize_workspace_bytes(u, r, p) bytes, any
+ * contents.  A_out: HOST array of n_modules DEVICE pointers, act dtype [d_out][r]; B_out:
+ * DEVICE act dtype [r][d_in]; both rounded to the activation type, ties to even, from
+ * float64.  sigma_out: DEVICE double [r + p] or NULL, the singular values of Q^T M in
+ * descending order (the first r are those of the factors: |A[:,j]|^2 = |B[j,:]|^2 =
+ * sigma_j for sigma_x = 1).  All arithmetic is float64 with sums in a fixed order: the
+ * same inputs give the same bits.  The call enqueues a few thousand small launches on
+ * `stream` and returns; it allocates nothing. */
+#define GLOWQ_MAX_SKETCH 256
+#define GLOWQ_MAX_POWER_STEPS 8
+glowq_status glowq_factorize_workspace_bytes(const glowq_unit* u, int32_t r, int32_t p,
+                                             size_t* bytes);
+glowq_status glowq_factorize_unit(const glowq_unit* u, const float* const* W_modules,
+                                  const double* sigma_x_diag, int32_t r, int32_t p, int32_t q,
+                                  const double* Omega, void* workspace, size_t workspace_bytes,
+                                  void* const* A_out, void* B_out, double* sigma_out,
+                                  void* stream);
+
 /* ---- inspection hooks (bit-exactness checks of the storage format) ---------
  * Both read the prepared layout of one module (the buffer the forward kernels
  * stream) with small kernels of their own.

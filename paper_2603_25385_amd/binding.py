@@ -79,6 +79,9 @@ def _load():
         "glowq_unit_importance": (ctypes.c_int, [up, ctypes.POINTER(vp), vp, vp, vp]),
         "glowq_select_units": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), i32, i32,
                                               ctypes.POINTER(ctypes.c_uint8)]),
+        "glowq_factorize_workspace_bytes": (ctypes.c_int, [up, i32, i32, ctypes.POINTER(sz)]),
+        "glowq_factorize_unit": (ctypes.c_int, [up, ctypes.POINTER(vp), vp, i32, i32, i32, vp, vp, sz,
+                                                ctypes.POINTER(vp), vp, vp, vp]),
         "glowq_debug_unpack": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
         "glowq_debug_dequant": (ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]),
         # include/glowq_probe.h
@@ -256,6 +259,30 @@ def glowq_select_units(scores: Sequence[float], k: int) -> list:
     mask = (ctypes.c_uint8 * n)()
     _check(_lib.glowq_select_units(arr, n, k, mask), "glowq_select_units")
     return list(mask)
+
+
+GLOWQ_MAX_SKETCH = 256
+GLOWQ_MAX_POWER_STEPS = 8
+
+
+def glowq_factorize_workspace_bytes(unit: glowq_unit, r: int, p: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.glowq_factorize_workspace_bytes(ctypes.byref(unit), r, p, ctypes.byref(n)),
+           "glowq_factorize_workspace_bytes")
+    return n.value
+
+
+def glowq_factorize_unit(unit: glowq_unit, W_modules, sigma_x_diag: int, r: int, p: int, q: int,
+                         Omega: int, workspace: int, workspace_bytes: int, A_out, B_out: int,
+                         sigma_out: int = 0, stream: int = 0) -> None:
+    """W_modules / A_out: one device address per module (fp32 weights in, act-dtype [d_out][r]
+    out); sigma_x_diag: device double[d_in] or 0; Omega: device double[d_in][r + p]."""
+    w = W_modules if isinstance(W_modules, ctypes.Array) else pack_pointers(W_modules)
+    a = A_out if isinstance(A_out, ctypes.Array) else pack_pointers(A_out)
+    _check(_lib.glowq_factorize_unit(ctypes.byref(unit), w, sigma_x_diag or None, r, p, q,
+                                     Omega or None, workspace or None, workspace_bytes, a,
+                                     B_out or None, sigma_out or None, stream or None),
+           "glowq_factorize_unit")
 
 
 def glowq_debug_unpack(w_prepared: int, d_out: int, d_in: int, group_size: int, q_out: int,

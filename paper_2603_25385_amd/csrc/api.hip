@@ -422,6 +422,48 @@ glowq_status glowq_select_units(const double* scores, int32_t n_units, int32_t k
   return GLOWQ_OK;
 }
 
+static glowq_status check_factorize(const glowq_unit* u, int32_t r, int32_t p, int32_t q) {
+  glowq_status s = validate(u, false, false);
+  if (s != GLOWQ_OK) return s;
+  if (!u->modules) return GLOWQ_ERR_NULL;
+  if (r < 1 || p < 0 || q < 0) return GLOWQ_ERR_SHAPE;
+  long long m = 0;
+  for (int i = 0; i < u->n_modules; ++i) m += u->modules[i].d_out;
+  if (r > m || r + p > u->d_in) return GLOWQ_ERR_SHAPE;      // more directions than the stack has
+  if (r > GLOWQ_MAX_RANK || r % 8 || r + p > GLOWQ_MAX_SKETCH || q > GLOWQ_MAX_POWER_STEPS ||
+      m > (1 << 20))
+    return GLOWQ_ERR_UNSUPPORTED;
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_factorize_workspace_bytes(const glowq_unit* u, int32_t r, int32_t p, size_t* bytes) {
+  if (!u || !bytes) return GLOWQ_ERR_NULL;
+  glowq_status s = check_factorize(u, r, p, 0);
+  if (s != GLOWQ_OK) return s;
+  *bytes = plan_factorize(*u, r, p).bytes;
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_factorize_unit(const glowq_unit* u, const float* const* W_modules,
+                                  const double* sigma_x_diag, int32_t r, int32_t p, int32_t q,
+                                  const double* Omega, void* workspace, size_t workspace_bytes,
+                                  void* const* A_out, void* B_out, double* sigma_out, void* stream) {
+  if (!u || !W_modules || !Omega || !A_out || !B_out) return GLOWQ_ERR_NULL;
+  glowq_status s = check_factorize(u, r, p, q);
+  if (s != GLOWQ_OK) return s;
+  if (!workspace || workspace_bytes < plan_factorize(*u, r, p).bytes) return GLOWQ_ERR_WORKSPACE;
+  if (((uintptr_t)workspace & 255u) || ((uintptr_t)Omega & 7u) || ((uintptr_t)sigma_x_diag & 7u) ||
+      ((uintptr_t)sigma_out & 7u) || misaligned(B_out))
+    return GLOWQ_ERR_ALIGN;
+  for (int i = 0; i < u->n_modules; ++i) {
+    if (!W_modules[i] || !u->modules[i].w_prepared || !A_out[i]) return GLOWQ_ERR_NULL;
+    if (misaligned(W_modules[i]) || misaligned(u->modules[i].w_prepared) || misaligned(A_out[i]))
+      return GLOWQ_ERR_ALIGN;
+  }
+  return hip_status(launch_factorize(*u, W_modules, sigma_x_diag, r, p, q, Omega, (char*)workspace,
+                                     A_out, B_out, sigma_out, (hipStream_t)stream));
+}
+
 glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d_in,
                                 int32_t group_size, uint8_t* q_out, void* stream) {
   if (!w_prepared || !q_out) return GLOWQ_ERR_NULL;

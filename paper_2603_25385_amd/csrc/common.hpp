@@ -54,6 +54,17 @@ __host__ __device__ inline PreparedView prepared_view(const void* p, int d_out, 
   return v;
 }
 
+// the 16-row x 128-channel tile record (rb, kb) of a prepared weight
+__device__ inline const uint32_t* tile_record(const PreparedView& v, int rb, int kb) {
+  return v.base + ((size_t)rb * v.ktiles + kb) * v.rec_words;
+}
+
+// value of a 16-bit pattern of the activation type, exactly
+template <int ACT> __device__ inline double act16_value(uint32_t bits16) {
+  if (ACT == ACT_F16) return (double)(float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+  return (double)__builtin_bit_cast(float, bits16 << 16);
+}
+
 // Per (row, group) constants of the dequantiser, derived once from an sz word.
 template <int ACT> struct GroupConst;
 template <> struct GroupConst<ACT_F16> {

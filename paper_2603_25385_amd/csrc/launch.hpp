@@ -36,6 +36,20 @@ hipError_t launch_debug_dequant(const void* prepared, int d_out, int d_in, int G
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_importance(const glowq_unit& u, const float* const* W_modules, double* scratch,
                              double* scores, hipStream_t st);
+// Workspace of the factorisation of one unit's stacked error (byte offsets, 256-aligned).
+struct FactorizePlan {
+  long long m;        // rows of the stack
+  int d, l, l16, r16; // channels; sketch width r + p; both widths rounded up to 16
+  int n_groups, rpw;  // row groups of the orthonormalisation and rows per group
+  size_t off_ms, off_y, off_z, off_bs, off_ut, off_lift, off_a64, off_slices, off_root,
+      off_inv_root, off_c1, off_c2, off_norm, off_norm0, off_sig2, off_sigma, off_perm,
+      off_counters;
+  size_t bytes;
+};
+FactorizePlan plan_factorize(const glowq_unit& u, int r, int p);
+hipError_t launch_factorize(const glowq_unit& u, const float* const* W_modules, const double* sigma_x,
+                            int r, int p, int q, const double* Omega, char* ws, void* const* A_out,
+                            void* B_out, double* sigma_out, hipStream_t st);
 // slices' start offsets in units of 256 bytes (every slice is 256-byte aligned)
 constexpr int STATUS_BATCH = 256;
 struct StatusBatch {

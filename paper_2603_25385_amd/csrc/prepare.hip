@@ -50,10 +50,6 @@ __global__ void k_prepare(const uint32_t* __restrict__ wq, const uint16_t* __res
   out[idx] = w;
 }
 
-__device__ inline const uint32_t* tile_record(const PreparedView& v, int rb, int kb) {
-  return v.base + ((size_t)rb * v.ktiles + kb) * v.rec_words;
-}
-
 __device__ inline uint32_t load_prepared_word(const PreparedView& v, int row, int k) {
   const int lane = (row & 15) + 16 * ((k >> 3) & 3);
   const int j = (k >> 5) & 3;
@@ -96,12 +92,6 @@ __global__ void k_debug_dequant(const void* prepared, int d_out, int d_in, int G
   g.set(load_prepared_sz(v, row, k, G));
   u32x4_t d = dequant_word<ACT>(w, g);
   *(u32x4_t*)(w_out + (long long)row * d_in + k) = d;
-}
-
-// value of a 16-bit pattern of the activation type, exactly
-template <int ACT> __device__ inline double act16_value(uint32_t bits16) {
-  if (ACT == ACT_F16) return (double)(float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
-  return (double)__builtin_bit_cast(float, bits16 << 16);
 }
 
 // adds the block's two partial sums to out[0], out[1]
