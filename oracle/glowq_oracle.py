@@ -129,7 +129,7 @@ def quantize_rtn(W: np.ndarray, G: int) -> Tuple[np.ndarray, np.ndarray, np.ndar
         s = np.maximum((hi - lo) / 15.0, 2.0 ** -14)
         s_bits = f64_to_bits(s, "f16")
         s_hat = bits_to_f64(s_bits, "f16")
-        z = np.clip(np.rint(-lo / s_hat), 0, 15)
+        z = np.clip(np.rint(-lo / s_hat), 0, 15) + 0.0      # (+ 0.0: a zero-point of zero is +0, never -0)
         q = np.clip(np.rint(Wg / s_hat[:, :, None]) + z[:, :, None], 0, 15)
         return q.reshape(hi_r - lo_r, d).astype(np.uint8), s_bits, f64_to_bits(z, "f16")
 

@@ -138,6 +138,10 @@ def test_rtn_bounds_and_ranges():
         assert q.min() >= 0 and q.max() <= 15
         assert np.all((z >= 0) & (z <= 15) & (z == np.rint(z)))
         assert np.all(s >= 2.0 ** -14)        # normal fp16, never zero
+        # the zero-point is an unsigned 4-bit integer stored as binary16: its patterns are
+        # those of 0.0 .. 15.0, the sign bit never set (a one-sided positive group has z = +0)
+        assert set(np.unique(z_bits)) <= {int(np.float16(v).view(np.uint16)) for v in range(16)}
+        assert z_bits[4, 0] == 0 and z_bits[3, 128 // G] == 0
         what = O.dequant(q, s_bits, z_bits, G, "f16")
         unclamped = (q > 0) & (q < 15)
         err = np.abs(W.astype(np.float64) - what)
