@@ -239,6 +239,18 @@ glowq_status glowq_unit_importance(const glowq_unit* u, const float* const* W_mo
 glowq_status glowq_select_units(const double* scores, int32_t n_units, int32_t k,
                                 uint8_t* restore_mask);
 
+/* ---- the quantiser (offline) ------------------------------------------------
+ * glowq_quantize_rtn: round-to-nearest asymmetric INT4 of one module's full-precision
+ * weights, per (row, group of group_size input channels) (Sec. 4.1: INT4 weights with
+ * grouped scales; the paper fixes no more than that).  For each group: the range [lo, hi]
+ * widened to contain 0; s = binary16(max((hi - lo) / 15, 2^-14)); z = clamp(rint(-lo / s),
+ * 0, 15); q = clamp(rint(w / s) + z, 0, 15), rint to even, divisions in float64 on the
+ * rounded s.  W: DEVICE fp32 [d_out][d_in].  Outputs are the canonical arrays that
+ * glowq_prepare_weights takes: wq DEVICE uint32 [d_out][d_in/8], scales and zeros DEVICE
+ * binary16 [d_out][d_in/G].  Same shape limits as glowq_prepare_weights. */
+glowq_status glowq_quantize_rtn(const float* W, int32_t d_out, int32_t d_in, int32_t group_size,
+                                uint32_t* wq, uint16_t* scales, uint16_t* zeros, void* stream);
+
 /* ---- the shared factors of a unit, computed on the GPU (offline) ------------
  * glowq_factorize_unit: balanced rank-r factors of the unit's stacked quantisation error
  * by the randomised, covariance-aligned procedure of Alg. 1 (App. A.3-A.4), from the

@@ -79,6 +79,7 @@ def _load():
         "glowq_unit_importance": (ctypes.c_int, [up, ctypes.POINTER(vp), vp, vp, vp]),
         "glowq_select_units": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), i32, i32,
                                               ctypes.POINTER(ctypes.c_uint8)]),
+        "glowq_quantize_rtn": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp]),
         "glowq_factorize_workspace_bytes": (ctypes.c_int, [up, i32, i32, ctypes.POINTER(sz)]),
         "glowq_factorize_unit": (ctypes.c_int, [up, ctypes.POINTER(vp), vp, i32, i32, i32, vp, vp, sz,
                                                 ctypes.POINTER(vp), vp, vp, vp]),
@@ -259,6 +260,12 @@ def glowq_select_units(scores: Sequence[float], k: int) -> list:
     mask = (ctypes.c_uint8 * n)()
     _check(_lib.glowq_select_units(arr, n, k, mask), "glowq_select_units")
     return list(mask)
+
+
+def glowq_quantize_rtn(W: int, d_out: int, d_in: int, group_size: int, wq: int, scales: int,
+                       zeros: int, stream: int = 0) -> None:
+    _check(_lib.glowq_quantize_rtn(W or None, d_out, d_in, group_size, wq or None, scales or None,
+                                   zeros or None, stream or None), "glowq_quantize_rtn")
 
 
 GLOWQ_MAX_SKETCH = 256

@@ -422,6 +422,15 @@ glowq_status glowq_select_units(const double* scores, int32_t n_units, int32_t k
   return GLOWQ_OK;
 }
 
+glowq_status glowq_quantize_rtn(const float* W, int32_t d_out, int32_t d_in, int32_t group_size,
+                                uint32_t* wq, uint16_t* scales, uint16_t* zeros, void* stream) {
+  if (!W || !wq || !scales || !zeros) return GLOWQ_ERR_NULL;
+  glowq_status s = check_weights_shape(d_out, d_in, group_size);
+  if (s != GLOWQ_OK) return s;
+  if (misaligned(W) || misaligned(wq) || misaligned(scales) || misaligned(zeros)) return GLOWQ_ERR_ALIGN;
+  return hip_status(launch_quantize_rtn(W, d_out, d_in, group_size, wq, scales, zeros, (hipStream_t)stream));
+}
+
 static glowq_status check_factorize(const glowq_unit* u, int32_t r, int32_t p, int32_t q) {
   glowq_status s = validate(u, false, false);
   if (s != GLOWQ_OK) return s;

@@ -65,6 +65,30 @@ template <int ACT> __device__ inline double act16_value(uint32_t bits16) {
   return (double)__builtin_bit_cast(float, bits16 << 16);
 }
 
+// round a float64 to the activation type, ties to even, one rounding; returns the bits
+template <int ACT> __device__ inline uint32_t act16_round(double x) {
+  constexpr int FB = ACT == ACT_F16 ? 10 : 7;          // fraction bits
+  constexpr int EMIN = ACT == ACT_F16 ? -14 : -126;    // exponent of the smallest normal
+  constexpr int BIAS = ACT == ACT_F16 ? 15 : 127;
+  constexpr uint32_t INF = ACT == ACT_F16 ? 0x7c00u : 0x7f80u;
+  const uint64_t u = __builtin_bit_cast(uint64_t, x);
+  const uint32_t sign = (uint32_t)(u >> 48) & 0x8000u;
+  const uint64_t mag = u & 0x7fffffffffffffffull;
+  if (mag > 0x7ff0000000000000ull) return sign | INF | (1u << (FB - 1));
+  const double ax = __builtin_bit_cast(double, mag);
+  uint32_t out;
+  if (ax < __builtin_ldexp(1.0, EMIN)) {
+    // below the normal range the grid is uniform: scale (exact), round once
+    out = (uint32_t)__builtin_rint(ax * __builtin_ldexp(1.0, FB - EMIN));
+  } else {
+    constexpr int SH = 52 - FB;
+    const uint64_t r = mag + ((1ull << (SH - 1)) - 1) + ((mag >> SH) & 1);   // carry may reach the exponent
+    const long long e = (long long)(r >> 52) - 1023 + BIAS;
+    out = e >= 2 * BIAS + 1 ? INF : ((uint32_t)e << FB) | ((uint32_t)(r >> SH) & ((1u << FB) - 1));
+  }
+  return sign | out;
+}
+
 // Per (row, group) constants of the dequantiser, derived once from an sz word.
 template <int ACT> struct GroupConst;
 template <> struct GroupConst<ACT_F16> {

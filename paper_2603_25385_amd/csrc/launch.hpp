@@ -29,6 +29,8 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base);
 
 hipError_t launch_prepare(const uint32_t* wq, const uint16_t* scales, const uint16_t* zeros,
                           int d_out, int d_in, int G, void* prepared, hipStream_t st);
+hipError_t launch_quantize_rtn(const float* W, int d_out, int d_in, int G, uint32_t* wq, uint16_t* scales,
+                               uint16_t* zeros, hipStream_t st);
 hipError_t launch_debug_unpack(const void* prepared, int d_out, int d_in, int G, uint8_t* q_out,
                                hipStream_t st);
 hipError_t launch_debug_dequant(const void* prepared, int d_out, int d_in, int G, int act,

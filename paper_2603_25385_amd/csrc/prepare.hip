@@ -1,5 +1,6 @@
 // Weight preparation, the two inspection hooks, and the importance scores of GlowQ-S.
 //
+// quantize_rtn:  fp32 weights -> canonical W4A16 arrays (round to nearest, asymmetric)
 // prepare:       canonical W4A16 arrays -> tiled layout the forward kernels read
 // debug_unpack:  tiled layout -> q[d_out][d_in] bytes
 // debug_dequant: tiled layout -> round_to_act((q - z) * s) through dequant_word(), the
@@ -48,6 +49,53 @@ __global__ void k_prepare(const uint32_t* __restrict__ wq, const uint16_t* __res
           ((uint32_t)zeros[(long long)row * n_groups + g] << 16);
   }
   out[idx] = w;
+}
+
+// Round-to-nearest asymmetric INT4 per (row, group of G channels) (Sec. 4.1: INT4 weights,
+// group size 128 or 64).  One thread per packed word (8 channels); the G / 8 threads of a
+// group are neighbouring lanes.  Range widened to contain 0; s = fp16(max((hi - lo) / 15,
+// 2^-14)); z = clamp(rint(-lo / s), 0, 15); q = clamp(rint(w / s) + z, 0, 15); float64
+// arithmetic on the fp16-rounded s, rint to even.
+__global__ void __launch_bounds__(256) k_quantize_rtn(const float* __restrict__ W, int d_out, int d_in, int G,
+                                                      uint32_t* __restrict__ wq, uint16_t* __restrict__ scales,
+                                                      uint16_t* __restrict__ zeros) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int words = d_in / 8;
+  // (whole waves stay in the loop-free path: the total is a multiple of 16 words per row,
+  // and lanes past the end only take part in the shuffles)
+  const bool live = idx < (long long)d_out * words;
+  const long long row = live ? idx / words : 0;
+  const int j = live ? (int)(idx - row * words) : 0;
+  const float4_t* src = (const float4_t*)(W + row * d_in + 8 * j);
+  const float4_t w0 = src[0], w1 = src[1];
+  const float w[8] = {w0[0], w0[1], w0[2], w0[3], w1[0], w1[1], w1[2], w1[3]};
+  float lo = 0.f, hi = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    lo = fminf(lo, w[e]);
+    hi = fmaxf(hi, w[e]);
+  }
+  for (int o = 1; o < G / 8; o <<= 1) {
+    lo = fminf(lo, __shfl_xor(lo, o, 64));
+    hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+  }
+  const double s = fmax(((double)hi - (double)lo) / 15.0, 0x1p-14);
+  const uint32_t s_bits = act16_round<ACT_F16>(s);
+  const double s_hat = act16_value<ACT_F16>(s_bits);
+  const double z = fmin(fmax(__builtin_rint(-(double)lo / s_hat), 0.0), 15.0) + 0.0;   // (+0, never -0)
+  uint32_t word = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const double q = fmin(fmax(__builtin_rint((double)w[e] / s_hat) + z, 0.0), 15.0);
+    word |= (uint32_t)q << (4 * e);
+  }
+  if (!live) return;
+  wq[idx] = word;
+  if ((j & (G / 8 - 1)) == 0) {
+    const long long g = row * (d_in / G) + (8 * j) / G;
+    scales[g] = (uint16_t)s_bits;
+    zeros[g] = (uint16_t)act16_round<ACT_F16>(z);
+  }
 }
 
 __device__ inline uint32_t load_prepared_word(const PreparedView& v, int row, int k) {
@@ -227,6 +275,13 @@ hipError_t launch_prepare(const uint32_t* wq, const uint16_t* scales, const uint
   long long n_words = (long long)(prepared_total_bytes(d_out, d_in, G) / 4);
   k_prepare<<<dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st>>>(
       wq, scales, zeros, (uint32_t*)prepared, d_out, d_in, G, n_words);
+  return hipGetLastError();
+}
+
+hipError_t launch_quantize_rtn(const float* W, int d_out, int d_in, int G, uint32_t* wq, uint16_t* scales,
+                               uint16_t* zeros, hipStream_t st) {
+  const long long n = (long long)d_out * (d_in / 8);
+  k_quantize_rtn<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(W, d_out, d_in, G, wq, scales, zeros);
   return hipGetLastError();
 }
 
