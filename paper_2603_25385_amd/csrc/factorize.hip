@@ -309,6 +309,28 @@ __device__ inline double block_sum(double v, double* lds4) {
   return lds4[0] + lds4[1] + lds4[2] + lds4[3];
 }
 
+// dot[t] = sum over the rows [r0, r1) of Y[k][t] * ycol[k - r0] for every column t < j, by all 256
+// threads: the rows are dealt to 256 / CW thread groups of CW >= j columns, whose partial sums
+// meet in `part` (256 doubles of LDS); thread t < j returns the sum, in group order
+__device__ inline double cgs_dots(const double* __restrict__ Y, long long ld, int r0, int r1, int j,
+                                  const double* ycol, double* part) {
+  const int t = threadIdx.x;
+  const int CW = j <= 64 ? 64 : (j <= 128 ? 128 : 256), n_sub = 256 / CW;
+  const int col = t & (CW - 1), sub = t / CW;
+  double dot = 0.0;
+  if (col < j) {
+#pragma unroll 8
+    for (int k = r0 + sub; k < r1; k += n_sub) dot += Y[(long long)k * ld + col] * ycol[k - r0];
+  }
+  __syncthreads();
+  part[t] = dot;
+  __syncthreads();
+  double sum = 0.0;
+  if (t < j)
+    for (int sgrp = 0; sgrp < n_sub; ++sgrp) sum += part[sgrp * CW + t];
+  return sum;
+}
+
 __global__ void __launch_bounds__(256) k_cgs(double* __restrict__ Y, long long ld, int m, int l, int rpw,
                                              int n_groups, int j, int phase, CgsBuffers cb) {
   __shared__ double c[256];
@@ -318,12 +340,14 @@ __global__ void __launch_bounds__(256) k_cgs(double* __restrict__ Y, long long l
   const int r0 = b * rpw, r1 = min(m, r0 + rpw);
   if (phase == 0) {
     if (j > 0) {
-      // finish column j - 1
+      // finish column j - 1 (every workgroup adds the partial norms in the same order)
       double n2 = 0.0, n0 = 0.0;
-      for (int gq = 0; gq < n_groups; ++gq) {
+      for (int gq = t; gq < n_groups; gq += 256) {
         n2 += cb.norm[gq];
         n0 += cb.norm0[(size_t)((j - 1) & 1) * n_groups + gq];
       }
+      n2 = block_sum(n2, red);
+      n0 = block_sum(n0, red);
       const double scale = (n2 > FZ_RANK_TOL2 * n0 && n2 > 0.0) ? 1.0 / sqrt(n2) : 0.0;
       for (int k = r0 + t; k < r1; k += 256) Y[(long long)k * ld + (j - 1)] *= scale;
       __syncthreads();       // (the scaled column is read below, by other threads)
@@ -331,9 +355,8 @@ __global__ void __launch_bounds__(256) k_cgs(double* __restrict__ Y, long long l
     if (j >= l) return;
     for (int k = r0 + t; k < r1; k += 256) ycol[k - r0] = Y[(long long)k * ld + j];
     __syncthreads();
-    double dot = 0.0, nn = 0.0;
-    if (t < j)
-      for (int k = r0; k < r1; ++k) dot += Y[(long long)k * ld + t] * ycol[k - r0];
+    double nn = 0.0;
+    const double dot = cgs_dots(Y, ld, r0, r1, j, ycol, c);
     cb.c1[(size_t)b * 256 + t] = dot;
     for (int k = r0 + t; k < r1; k += 256) nn += ycol[k - r0] * ycol[k - r0];
     nn = block_sum(nn, red);
@@ -343,17 +366,23 @@ __global__ void __launch_bounds__(256) k_cgs(double* __restrict__ Y, long long l
   // phases 1 and 2: coefficients, in workgroup order
   const double* part = phase == 1 ? cb.c1 : cb.c2;
   double ct = 0.0;
-  if (t < j)
+  if (t < j) {
+#pragma unroll 16
     for (int gq = 0; gq < n_groups; ++gq) ct += part[(size_t)gq * 256 + t];
+  }
   c[t] = ct;
   __syncthreads();
-  // one wave per row: y_k -= sum_i Q[k][i] c[i]
-  const int w = t >> 6, lane = t & 63;
-  for (int k = r0 + w; k < r1; k += 4) {
+  // sixteen lanes per row: y_k -= sum_i Q[k][i] c[i]   (every lane runs the same number of
+  // rounds, so that the shuffles below see whole waves)
+  const int slot = t >> 4, sub = t & 15;
+  for (int kb = r0; kb < r1; kb += 16) {
+    const int k = kb + slot;
     double sum = 0.0;
-    for (int i = lane; i < j; i += 64) sum += Y[(long long)k * ld + i] * c[i];
-    sum = wave_sum(sum);
-    if (lane == 0) {
+    if (k < r1)
+      for (int i = sub; i < j; i += 16) sum += Y[(long long)k * ld + i] * c[i];
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (sub == 0 && k < r1) {
       const double y = Y[(long long)k * ld + j] - sum;
       Y[(long long)k * ld + j] = y;
       ycol[k - r0] = y;
@@ -361,9 +390,7 @@ __global__ void __launch_bounds__(256) k_cgs(double* __restrict__ Y, long long l
   }
   __syncthreads();
   if (phase == 1) {
-    double dot = 0.0;
-    if (t < j)
-      for (int k = r0; k < r1; ++k) dot += Y[(long long)k * ld + t] * ycol[k - r0];
+    const double dot = cgs_dots(Y, ld, r0, r1, j, ycol, c);     // (c is free again: barrier inside)
     cb.c2[(size_t)b * 256 + t] = dot;
   } else {
     double nn = 0.0;
@@ -376,18 +403,21 @@ __global__ void __launch_bounds__(256) k_cgs(double* __restrict__ Y, long long l
 // ---------------------------------------------------------------------------------------
 // SVD of Bs [l][d] by one-sided Jacobi rotations of its rows (Hestenes): a rotation of rows
 // (a, b) makes them orthogonal; at convergence row a is sigma_a v_a^T and the accumulated
-// rotations, applied to the rows of Ut (identity at the start), leave U~[:, a] in row a of
-// Ut.  One launch per round of a round-robin schedule over n = l rounded up to even players
+// rotations, applied to the columns of Um, leave U~ in Um.  One launch per round of a round-robin schedule over n = l rounded up to even players
 // (n / 2 disjoint pairs, a workgroup each); a sweep is n - 1 rounds.  counters[w] counts the
 // rotations of sweep w; once a sweep made none, the launches of later sweeps return at once.
 // ---------------------------------------------------------------------------------------
 constexpr int FZ_MAX_SWEEPS = 16;
+constexpr int FZ_POLISH_SWEEPS = 8;     // after the rotation by the Gram matrix's eigenvectors
 constexpr double FZ_JACOBI_TOL2 = 1e-28;     // rotate while (a.b)^2 > tol^2 |a|^2 |b|^2, tol = 1e-14
 
-__global__ void __launch_bounds__(256) k_jacobi_round(double* __restrict__ Bs, long long ldb, int d,
-                                                      double* __restrict__ Ut, long long ldu, int l, int n,
-                                                      int round, int sweep, int* counters) {
-  __shared__ double red[3][4];
+constexpr int FZ_JT = 1024;       // threads of a Jacobi workgroup
+constexpr int FZ_JC = 4;          // elements of each row a thread keeps in registers
+
+__global__ void __launch_bounds__(FZ_JT) k_jacobi_round(double* __restrict__ Bs, long long ldb, int d,
+                                                        double* __restrict__ Um, long long ldu, int l, int n,
+                                                        int round, int sweep, int* counters) {
+  __shared__ double red[3][FZ_JT / 64];
   if (sweep > 0 && counters[sweep - 1] == 0) return;
   const int k = blockIdx.x, t = threadIdx.x;
   int a, b;
@@ -396,33 +426,144 @@ __global__ void __launch_bounds__(256) k_jacobi_round(double* __restrict__ Bs, l
   if (a >= l || b >= l) return;      // the odd player out
   double* ra = Bs + (long long)a * ldb;
   double* rb = Bs + (long long)b * ldb;
+  double xa[FZ_JC], xb[FZ_JC];
   double aa = 0.0, bb = 0.0, ab = 0.0;
-  for (int i = t; i < d; i += 256) {
+#pragma unroll
+  for (int c = 0; c < FZ_JC; ++c) {
+    const int i = t + c * FZ_JT;
+    xa[c] = i < d ? ra[i] : 0.0;
+    xb[c] = i < d ? rb[i] : 0.0;
+    aa += xa[c] * xa[c]; bb += xb[c] * xb[c]; ab += xa[c] * xb[c];
+  }
+  for (int i = t + FZ_JC * FZ_JT; i < d; i += FZ_JT) {
     const double x = ra[i], y = rb[i];
     aa += x * x; bb += y * y; ab += x * y;
   }
   aa = wave_sum(aa); bb = wave_sum(bb); ab = wave_sum(ab);
   if ((t & 63) == 0) { red[0][t >> 6] = aa; red[1][t >> 6] = bb; red[2][t >> 6] = ab; }
   __syncthreads();
-  aa = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-  bb = red[1][0] + red[1][1] + red[1][2] + red[1][3];
-  ab = red[2][0] + red[2][1] + red[2][2] + red[2][3];
+  aa = bb = ab = 0.0;
+#pragma unroll
+  for (int w = 0; w < FZ_JT / 64; ++w) { aa += red[0][w]; bb += red[1][w]; ab += red[2][w]; }
   if (!(ab * ab > FZ_JACOBI_TOL2 * aa * bb)) return;
   if (t == 0) atomicAdd(&counters[sweep], 1);
   const double zeta = (bb - aa) / (2.0 * ab);
   const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
   const double cs = 1.0 / sqrt(1.0 + tt * tt), sn = cs * tt;
-  for (int i = t; i < d; i += 256) {
+#pragma unroll
+  for (int c = 0; c < FZ_JC; ++c) {
+    const int i = t + c * FZ_JT;
+    if (i < d) {
+      ra[i] = cs * xa[c] - sn * xb[c];
+      rb[i] = sn * xa[c] + cs * xb[c];
+    }
+  }
+  for (int i = t + FZ_JC * FZ_JT; i < d; i += FZ_JT) {
     const double x = ra[i], y = rb[i];
     ra[i] = cs * x - sn * y;
     rb[i] = sn * x + cs * y;
   }
-  double* ua = Ut + (long long)a * ldu;
-  double* ub = Ut + (long long)b * ldu;
-  for (int i = t; i < l; i += 256) {
-    const double x = ua[i], y = ub[i];
-    ua[i] = cs * x - sn * y;
-    ub[i] = sn * x + cs * y;
+  for (int i = t; i < l; i += FZ_JT) {
+    double* u = Um + (long long)i * ldu;
+    const double x = u[a], y = u[b];
+    u[a] = cs * x - sn * y;
+    u[b] = sn * x + cs * y;
+  }
+}
+
+// Eigenvectors of the l x l Gram matrix T = Bs Bs^T by two-sided Jacobi rotations, one
+// workgroup, T in LDS (l <= FZ_EIG_MAX): with Um = its eigenvectors, the rows of Um^T Bs
+// are orthogonal up to the rounding of the Gram matrix, so that the one-sided rotations on
+// the long rows that follow only polish (one or two sweeps instead of eight or nine).  The
+// same rotation G = [[c, -s], [s, c]] on the pair (a, b) as above: T <- G T G^T, rows then
+// columns, and the columns of Um.  Rounds pair the players as above; all pairs of a round
+// are disjoint and are rotated together.
+constexpr int FZ_EIG_MAX = 128;
+constexpr int FZ_EIG_SWEEPS = 8;
+constexpr int FZ_EIG_LDS_DOUBLES = 19 * 1024;     // 152 KiB: T, and Um beside it when both fit (l <= 97)
+constexpr double FZ_EIG_TOL2 = 1e-20;             // rotate while (T_ab)^2 > tol^2 T_aa T_bb, tol = 1e-10 ...
+constexpr double FZ_EIG_ABS = 1e-13;              // ... and |T_ab| is above the rounding of the largest entry
+
+__global__ void __launch_bounds__(1024) k_gram_eigenvectors(const double* __restrict__ Tg, long long ldt, int l,
+                                                            double* __restrict__ Um, long long ldu) {
+  __shared__ double pool[FZ_EIG_LDS_DOUBLES];
+  __shared__ double cs[FZ_EIG_MAX / 2], sn[FZ_EIG_MAX / 2];
+  __shared__ int pa[FZ_EIG_MAX / 2], pb[FZ_EIG_MAX / 2];
+  __shared__ int rotated;
+  __shared__ double tmax;
+  const int t = threadIdx.x, LD = l + 1;
+  double* T = pool;
+  const bool u_in_lds = 2 * l * LD <= FZ_EIG_LDS_DOUBLES;
+  double* U = u_in_lds ? pool + l * LD : Um;           // (generic pointer: LDS or global)
+  const long long LDU = u_in_lds ? LD : ldu;
+  for (int idx = t; idx < l * l; idx += 1024) {
+    const int i = idx / l, k = idx - i * l;
+    T[i * LD + k] = Tg[(long long)i * ldt + k];
+    U[(long long)i * LDU + k] = i == k ? 1.0 : 0.0;
+  }
+  __syncthreads();
+  if (t == 0) {
+    double mx = 0.0;
+    for (int i = 0; i < l; ++i) mx = fmax(mx, T[i * LD + i]);
+    tmax = mx;
+  }
+  const int n = (l + 1) & ~1, pairs = n / 2;
+  for (int sweep = 0; sweep < FZ_EIG_SWEEPS; ++sweep) {
+    __syncthreads();
+    if (t == 0) rotated = 0;
+    for (int round = 0; round < n - 1; ++round) {
+      __syncthreads();
+      if (t < pairs) {
+        int a, b;
+        if (t == 0) { a = n - 1; b = round; }
+        else { a = (round + t) % (n - 1); b = (round - t + (n - 1)) % (n - 1); }
+        double c = 1.0, s = 0.0;
+        if (a < l && b < l) {
+          const double aa = T[a * LD + a], bb = T[b * LD + b], ab = T[a * LD + b];
+          if (ab * ab > FZ_EIG_TOL2 * aa * bb && fabs(ab) > FZ_EIG_ABS * tmax) {
+            const double zeta = (bb - aa) / (2.0 * ab);
+            const double tt = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+            c = 1.0 / sqrt(1.0 + tt * tt);
+            s = c * tt;
+            rotated = 1;
+          }
+        } else {
+          a = b = -1;
+        }
+        pa[t] = a; pb[t] = b; cs[t] = c; sn[t] = s;
+      }
+      __syncthreads();
+      // rows a, b of every pair
+      for (int idx = t; idx < pairs * l; idx += 1024) {
+        const int k = idx / l, i = idx - k * l, a = pa[k], b = pb[k];
+        if (a < 0 || sn[k] == 0.0) continue;
+        const double x = T[a * LD + i], y = T[b * LD + i];
+        T[a * LD + i] = cs[k] * x - sn[k] * y;
+        T[b * LD + i] = sn[k] * x + cs[k] * y;
+      }
+      __syncthreads();
+      // columns a, b of every pair, of T and of the eigenvector matrix
+      for (int idx = t; idx < pairs * l; idx += 1024) {
+        const int k = idx / l, i = idx - k * l, a = pa[k], b = pb[k];
+        if (a < 0 || sn[k] == 0.0) continue;
+        const double x = T[i * LD + a], y = T[i * LD + b];
+        T[i * LD + a] = cs[k] * x - sn[k] * y;
+        T[i * LD + b] = sn[k] * x + cs[k] * y;
+        double* u = U + (long long)i * LDU;
+        const double ux = u[a], uy = u[b];
+        u[a] = cs[k] * ux - sn[k] * uy;
+        u[b] = sn[k] * ux + cs[k] * uy;
+      }
+    }
+    __syncthreads();
+    if (rotated == 0) break;
+  }
+  if (u_in_lds) {
+    __syncthreads();
+    for (int idx = t; idx < l * l; idx += 1024) {
+      const int i = idx / l, k = idx - i * l;
+      Um[(long long)i * ldu + k] = U[(long long)i * LDU + k];
+    }
   }
 }
 
@@ -460,12 +601,12 @@ __global__ void __launch_bounds__(256) k_sort_sigma(const double* sig2, int l, d
 
 // P[i][jr] = U~[i][perm jr] sqrt(sigma_jr): the l x r matrix that takes Q to A (Alg. 1,
 // lift and balance)
-__global__ void k_build_lift(const double* __restrict__ Ut, long long ldu, const double* sigma_sorted,
+__global__ void k_build_lift(const double* __restrict__ Um, long long ldu, const double* sigma_sorted,
                              const int* perm, int l, int r, double* P, long long ldp) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= l * r) return;
   const int i = idx / r, jr = idx - i * r;
-  P[(long long)i * ldp + jr] = Ut[(long long)perm[jr] * ldu + i] * sqrt(sigma_sorted[jr]);
+  P[(long long)i * ldp + jr] = Um[(long long)i * ldu + perm[jr]] * sqrt(sigma_sorted[jr]);
 }
 
 template <int ACT>
@@ -511,8 +652,8 @@ FactorizePlan plan_factorize(const glowq_unit& u, int r, int p) {
   f.l = r + p;
   f.l16 = (f.l + 15) / 16 * 16;
   f.r16 = (r + 15) / 16 * 16;
-  f.n_groups = (int)((m + 255) / 256);
-  if (f.n_groups < 256) f.n_groups = (int)(m < 256 ? m : 256);
+  f.n_groups = (int)((m + 255) / 256);                 // at most 256 rows per group ...
+  if (f.n_groups < 64) f.n_groups = (int)(m < 64 ? m : 64);   // ... and few groups: their partial sums are added serially
   f.rpw = (int)((m + f.n_groups - 1) / f.n_groups);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
@@ -521,13 +662,16 @@ FactorizePlan plan_factorize(const glowq_unit& u, int r, int p) {
   f.off_z = take((size_t)f.d * f.l16 * 8);
   f.off_bs = take((size_t)f.l * f.d * 8);
   f.off_ut = take((size_t)f.l * f.l16 * 8);
+  f.off_gram = take((size_t)f.l * f.l16 * 8);
   f.off_lift = take((size_t)f.l * f.r16 * 8);
   f.off_a64 = take((size_t)m * f.r16 * 8);
   size_t sl = gemm_slice_doubles((int)m, f.l, f.d, NN_RB);                      // Y = Ms Omega, Y = Ms Z
   size_t s2 = gemm_slice_doubles(f.d, f.l, (int)m, TN_RB);                      // Z = Ms^T Y, Bs^T = Ms^T Q
   size_t s3 = gemm_slice_doubles((int)m, r, f.l, NN_RB);                        // A = Q P
-  if (s2 > sl) sl = s2;
-  if (s3 > sl) sl = s3;
+  size_t s4 = gemm_slice_doubles(f.l, f.l, f.d, TN_RB);                         // Gram of Bs
+  size_t s5 = gemm_slice_doubles(f.d, f.l, f.l, NN_RB);                         // rows = Um^T Bs
+  for (size_t o : {s2, s3, s4, s5})
+    if (o > sl) sl = o;
   f.off_slices = take(sl * 8);
   f.off_root = take((size_t)f.d * 8);
   f.off_inv_root = take((size_t)f.d * 8);
@@ -553,7 +697,8 @@ hipError_t launch_factorize(const glowq_unit& u, const float* const* W_modules, 
   double* Y = (double*)(ws + f.off_y);
   double* Z = (double*)(ws + f.off_z);
   double* Bs = (double*)(ws + f.off_bs);
-  double* Ut = (double*)(ws + f.off_ut);
+  double* Um = (double*)(ws + f.off_ut);
+  double* gram = (double*)(ws + f.off_gram);
   double* lift = (double*)(ws + f.off_lift);
   double* A64 = (double*)(ws + f.off_a64);
   double* slices = (double*)(ws + f.off_slices);
@@ -601,20 +746,31 @@ hipError_t launch_factorize(const glowq_unit& u, const float* const* W_modules, 
       k_cgs<<<dim3((unsigned)f.n_groups), dim3(256), 0, st>>>(Y, f.l16, m, l, f.rpw, f.n_groups, 0, 2, cb);
     }
   }
-  // compressed matrix Bs = Q^T Ms, as (Ms^T Q)^T
-  err = gemm<true>(Ms, d, Y, f.l16, Bs, d, true, d, l, m, slices, st);
+  // compressed matrix Bs = Q^T Ms and its SVD.  When the small Gram matrix fits one
+  // workgroup's LDS its eigenvectors rotate the rows first, and the one-sided rotations on
+  // the long rows only polish.
+  int sweeps = FZ_MAX_SWEEPS;
+  if (l <= FZ_EIG_MAX) {
+    double* BsT = Z;                                                               // [d][l16]
+    err = gemm<true>(Ms, d, Y, f.l16, BsT, f.l16, false, d, l, m, slices, st);     // Ms^T Q
+    if (err == hipSuccess) err = gemm<true>(BsT, f.l16, BsT, f.l16, gram, f.l16, false, l, l, d, slices, st);
+    if (err != hipSuccess) return err;
+    k_gram_eigenvectors<<<dim3(1), dim3(1024), 0, st>>>(gram, f.l16, l, Um, f.l16);
+    err = gemm<false>(BsT, f.l16, Um, f.l16, Bs, d, true, d, l, l, slices, st);    // (BsT Um)^T = Um^T Bs
+    sweeps = FZ_POLISH_SWEEPS;
+  } else {
+    err = gemm<true>(Ms, d, Y, f.l16, Bs, d, true, d, l, m, slices, st);           // (Ms^T Q)^T
+    k_identity<<<dim3((unsigned)((l * l + 255) / 256)), dim3(256), 0, st>>>(Um, f.l16, l);
+  }
   if (err != hipSuccess) return err;
-  // its SVD
-  k_identity<<<dim3((unsigned)((l * l + 255) / 256)), dim3(256), 0, st>>>(Ut, f.l16, l);
   const int n = (l + 1) & ~1;
-  if (n >= 2)
-    for (int sweep = 0; sweep < FZ_MAX_SWEEPS; ++sweep)
-      for (int round = 0; round < n - 1; ++round)
-        k_jacobi_round<<<dim3((unsigned)(n / 2)), dim3(256), 0, st>>>(Bs, d, d, Ut, f.l16, l, n, round, sweep, counters);
+  for (int sweep = 0; sweep < sweeps; ++sweep)
+    for (int round = 0; round < n - 1; ++round)
+      k_jacobi_round<<<dim3((unsigned)(n / 2)), dim3(FZ_JT), 0, st>>>(Bs, d, d, Um, f.l16, l, n, round, sweep, counters);
   k_row_norms<<<dim3((unsigned)l), dim3(256), 0, st>>>(Bs, d, d, sig2);
   k_sort_sigma<<<dim3(1), dim3(256), 0, st>>>(sig2, l, sigma_sorted, perm);
   // truncate, balance, lift
-  k_build_lift<<<dim3((unsigned)((l * r + 255) / 256)), dim3(256), 0, st>>>(Ut, f.l16, sigma_sorted, perm, l, r, lift, f.r16);
+  k_build_lift<<<dim3((unsigned)((l * r + 255) / 256)), dim3(256), 0, st>>>(Um, f.l16, sigma_sorted, perm, l, r, lift, f.r16);
   err = gemm<false>(Y, f.l16, lift, f.r16, A64, f.r16, false, m, r, l, slices, st);
   if (err != hipSuccess) return err;
   row_off = 0;

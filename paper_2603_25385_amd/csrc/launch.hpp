@@ -43,7 +43,7 @@ struct FactorizePlan {
   long long m;        // rows of the stack
   int d, l, l16, r16; // channels; sketch width r + p; both widths rounded up to 16
   int n_groups, rpw;  // row groups of the orthonormalisation and rows per group
-  size_t off_ms, off_y, off_z, off_bs, off_ut, off_lift, off_a64, off_slices, off_root,
+  size_t off_ms, off_y, off_z, off_bs, off_ut, off_gram, off_lift, off_a64, off_slices, off_root,
       off_inv_root, off_c1, off_c2, off_norm, off_norm0, off_sig2, off_sigma, off_perm,
       off_counters;
   size_t bytes;

@@ -161,3 +161,55 @@ def test_unit_importance_argument_checks():
     with pytest.raises(G.GlowqError) as e:
         G.glowq_unit_importance(_unit(B=0), [0x7000], 0x9000, 0xA000, 0)
     assert e.value.status == G.GLOWQ_ERR_NULL
+
+
+def test_quantize_rtn_argument_checks():
+    ok = (0x7000, 64, 256, 128, 0x8000, 0x9000, 0xA000)
+    for i, status in [(0, G.GLOWQ_ERR_NULL), (4, G.GLOWQ_ERR_NULL), (5, G.GLOWQ_ERR_NULL), (6, G.GLOWQ_ERR_NULL)]:
+        a = list(ok)
+        a[i] = 0
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_quantize_rtn(*a)
+        assert e.value.status == status
+    for a, status in [((0x7004,) + ok[1:], G.GLOWQ_ERR_ALIGN),
+                      (ok[:3] + (32,) + ok[4:], G.GLOWQ_ERR_SHAPE),
+                      (ok[:2] + (200,) + ok[3:], G.GLOWQ_ERR_SHAPE),
+                      (ok[:1] + (0,) + ok[2:], G.GLOWQ_ERR_SHAPE),
+                      (ok[:2] + (192, 64) + ok[4:], G.GLOWQ_ERR_UNSUPPORTED),
+                      (ok[:1] + (60,) + ok[2:], G.GLOWQ_ERR_UNSUPPORTED)]:
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_quantize_rtn(*a)
+        assert e.value.status == status, a
+
+
+def test_factorize_argument_checks():
+    u = _unit(n=2, d_out=64, d_in=256)                       # m = 128 rows, d = 256
+    nbytes = G.glowq_factorize_workspace_bytes(u, 16, 8)
+    assert nbytes > 128 * 256 * 8 and nbytes % 256 == 0      # holds at least the float64 stack
+    assert G.glowq_factorize_workspace_bytes(u, 16, 24) > nbytes
+    good = dict(W=[0x7000, 0x7100], sx=0, r=16, p=8, q=2, Om=0xB000, ws=0xC000, nb=nbytes,
+                A=[0xD000, 0xD100], B=0xE000, sig=0xF000)
+
+    def call(**kw):
+        a = dict(good)
+        a.update(kw)
+        G.glowq_factorize_unit(u, a["W"], a["sx"], a["r"], a["p"], a["q"], a["Om"], a["ws"], a["nb"],
+                               a["A"], a["B"], a["sig"], 0)
+
+    for kw, status in [(dict(Om=0), G.GLOWQ_ERR_NULL), (dict(B=0), G.GLOWQ_ERR_NULL),
+                       (dict(W=[0x7000, 0]), G.GLOWQ_ERR_NULL), (dict(A=[0, 0xD100]), G.GLOWQ_ERR_NULL),
+                       (dict(ws=0), G.GLOWQ_ERR_WORKSPACE), (dict(nb=nbytes - 1), G.GLOWQ_ERR_WORKSPACE),
+                       (dict(ws=0xC010), G.GLOWQ_ERR_ALIGN), (dict(Om=0xB004), G.GLOWQ_ERR_ALIGN),
+                       (dict(sx=0xB104), G.GLOWQ_ERR_ALIGN), (dict(W=[0x7000, 0x7108]), G.GLOWQ_ERR_ALIGN),
+                       (dict(r=0), G.GLOWQ_ERR_SHAPE), (dict(p=-1), G.GLOWQ_ERR_SHAPE),
+                       (dict(q=-1), G.GLOWQ_ERR_SHAPE),
+                       (dict(r=136, p=0), G.GLOWQ_ERR_SHAPE),          # more ranks than the stack has rows
+                       (dict(r=128, p=200), G.GLOWQ_ERR_SHAPE),        # sketch wider than d_in
+                       (dict(r=12), G.GLOWQ_ERR_UNSUPPORTED), (dict(q=9), G.GLOWQ_ERR_UNSUPPORTED)]:
+        with pytest.raises(G.GlowqError) as e:
+            call(**kw)
+        assert e.value.status == status, kw
+    wide = _unit(n=4, d_out=512, ldy=512, d_in=1024)
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_factorize_workspace_bytes(wide, 128, 136)   # r + p above the sketch limit
+    assert e.value.status == G.GLOWQ_ERR_UNSUPPORTED
