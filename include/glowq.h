@@ -287,6 +287,36 @@ glowq_status glowq_factorize_unit(const glowq_unit* u, const float* const* W_mod
                                   void* const* A_out, void* B_out, double* sigma_out,
                                   void* stream);
 
+/* ---- microscaling variant: MXFP4 weights, MXFP8 activations (W4A8) ------------
+ * The same forward (Sec. 3.3, Eqs. 8-9) on the floating-point-like datatypes of the paper's
+ * datatype appendix and the W4A8 rows of its main results, for up to 16 tokens:
+ *   Y_i = Xq dequant(W_mx,i)^T + R A_i^T,   R = X B^T,
+ * Xq the activations quantised to MXFP8 (E4M3) inside the call, W_mx,i MXFP4 (E2M1) weights,
+ * the correction from the 16-bit X, B and A_i exactly as in the W4A16 calls.  Formats of the
+ * OCP Microscaling (MX) v1.0 specification: blocks of 32 consecutive input channels share an
+ * E8M0 scale 2^(code - 127); conversion: shared exponent floor(log2(max |v|)) - emax (2 for
+ * E2M1, 8 for E4M3) clamped to [-127, 127], elements rounded to nearest even and clamped to
+ * the largest finite value; a block of zeros gets code 127.  The main product runs on the
+ * block-scaled matrix instruction, fp32 accumulation.
+ * glowq_mx_prepare_weights: codes DEVICE uint32 [d_out][d_in/8], element 8j+e of a row in
+ *   bits 4e..4e+3 of word j (E2M1 code, sign in bit 3); scales DEVICE uint8 [d_out][d_in/32];
+ *   w_prepared DEVICE, glowq_mx_prepared_bytes(d_out, d_in) bytes.  d_in a multiple of 128,
+ *   d_out a multiple of 8 (else GLOWQ_ERR_UNSUPPORTED).
+ * glowq_mx_quantize_activations: the activation quantiser by itself; X DEVICE act dtype
+ *   [T][d_in]; codes DEVICE uint8 [T][d_in] (E4M3), scales DEVICE uint8 [T][d_in/32].
+ * glowq_mx_group_forward: `u` as for glowq_group_forward with modules[i].w_prepared from
+ *   glowq_mx_prepare_weights (group_size is ignored); T <= 16 (more: GLOWQ_ERR_UNSUPPORTED);
+ *   workspace DEVICE, 256-byte aligned, glowq_mx_workspace_bytes(u) bytes, any contents.
+ *   Three or five small launches on `stream` (quantise X; R when restored; the forward). */
+glowq_status glowq_mx_prepared_bytes(int32_t d_out, int32_t d_in, size_t* bytes);
+glowq_status glowq_mx_prepare_weights(const uint32_t* codes, const uint8_t* scales, int32_t d_out,
+                                      int32_t d_in, void* w_prepared, void* stream);
+glowq_status glowq_mx_quantize_activations(const void* X, int32_t T, int32_t d_in, int32_t act_dtype,
+                                           uint8_t* codes, uint8_t* scales, void* stream);
+glowq_status glowq_mx_workspace_bytes(const glowq_unit* u, size_t* bytes);
+glowq_status glowq_mx_group_forward(const glowq_unit* u, int32_t restore, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
 /* ---- inspection hooks (bit-exactness checks of the storage format) ---------
  * Both read the prepared layout of one module (the buffer the forward kernels
  * stream) with small kernels of their own.

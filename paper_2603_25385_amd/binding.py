@@ -83,6 +83,11 @@ def _load():
         "glowq_factorize_workspace_bytes": (ctypes.c_int, [up, i32, i32, ctypes.POINTER(sz)]),
         "glowq_factorize_unit": (ctypes.c_int, [up, ctypes.POINTER(vp), vp, i32, i32, i32, vp, vp, sz,
                                                 ctypes.POINTER(vp), vp, vp, vp]),
+        "glowq_mx_prepared_bytes": (ctypes.c_int, [i32, i32, ctypes.POINTER(sz)]),
+        "glowq_mx_prepare_weights": (ctypes.c_int, [vp, vp, i32, i32, vp, vp]),
+        "glowq_mx_quantize_activations": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp]),
+        "glowq_mx_workspace_bytes": (ctypes.c_int, [up, ctypes.POINTER(sz)]),
+        "glowq_mx_group_forward": (ctypes.c_int, [up, i32, vp, sz, vp]),
         "glowq_debug_unpack": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
         "glowq_debug_dequant": (ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]),
         # include/glowq_probe.h
@@ -290,6 +295,36 @@ def glowq_factorize_unit(unit: glowq_unit, W_modules, sigma_x_diag: int, r: int,
                                      Omega or None, workspace or None, workspace_bytes, a,
                                      B_out or None, sigma_out or None, stream or None),
            "glowq_factorize_unit")
+
+
+def glowq_mx_prepared_bytes(d_out: int, d_in: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.glowq_mx_prepared_bytes(d_out, d_in, ctypes.byref(n)), "glowq_mx_prepared_bytes")
+    return n.value
+
+
+def glowq_mx_prepare_weights(codes: int, scales: int, d_out: int, d_in: int, w_prepared: int,
+                             stream: int = 0) -> None:
+    _check(_lib.glowq_mx_prepare_weights(codes or None, scales or None, d_out, d_in, w_prepared or None,
+                                         stream or None), "glowq_mx_prepare_weights")
+
+
+def glowq_mx_quantize_activations(X: int, T: int, d_in: int, act_dtype: int, codes: int, scales: int,
+                                  stream: int = 0) -> None:
+    _check(_lib.glowq_mx_quantize_activations(X or None, T, d_in, act_dtype, codes or None, scales or None,
+                                              stream or None), "glowq_mx_quantize_activations")
+
+
+def glowq_mx_workspace_bytes(unit: glowq_unit) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.glowq_mx_workspace_bytes(ctypes.byref(unit), ctypes.byref(n)), "glowq_mx_workspace_bytes")
+    return n.value
+
+
+def glowq_mx_group_forward(unit: glowq_unit, restore: int, workspace: int, workspace_bytes: int,
+                           stream: int = 0) -> None:
+    _check(_lib.glowq_mx_group_forward(ctypes.byref(unit), restore, workspace or None, workspace_bytes,
+                                       stream or None), "glowq_mx_group_forward")
 
 
 def glowq_debug_unpack(w_prepared: int, d_out: int, d_in: int, group_size: int, q_out: int,

@@ -473,6 +473,70 @@ glowq_status glowq_factorize_unit(const glowq_unit* u, const float* const* W_mod
                                      A_out, B_out, sigma_out, (hipStream_t)stream));
 }
 
+// ---- microscaling variant ----------------------------------------------------------------
+static glowq_status check_mx_weights_shape(int d_out, int d_in) {
+  if (d_in < 32 || d_in > (1 << 16) || d_in % 32) return GLOWQ_ERR_SHAPE;     // whole MX blocks
+  if (d_out < 1 || d_out > (1 << 20)) return GLOWQ_ERR_SHAPE;
+  if (d_in % 128 || d_out % 8) return GLOWQ_ERR_UNSUPPORTED;
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_mx_prepared_bytes(int32_t d_out, int32_t d_in, size_t* bytes) {
+  if (!bytes) return GLOWQ_ERR_NULL;
+  glowq_status s = check_mx_weights_shape(d_out, d_in);
+  if (s != GLOWQ_OK) return s;
+  *bytes = mx_prepared_bytes(d_out, d_in);
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_mx_prepare_weights(const uint32_t* codes, const uint8_t* scales, int32_t d_out,
+                                      int32_t d_in, void* w_prepared, void* stream) {
+  if (!codes || !scales || !w_prepared) return GLOWQ_ERR_NULL;
+  glowq_status s = check_mx_weights_shape(d_out, d_in);
+  if (s != GLOWQ_OK) return s;
+  if (misaligned(codes) || misaligned(w_prepared)) return GLOWQ_ERR_ALIGN;
+  return hip_status(launch_mx_prepare(codes, scales, d_out, d_in, w_prepared, (hipStream_t)stream));
+}
+
+glowq_status glowq_mx_quantize_activations(const void* X, int32_t T, int32_t d_in, int32_t act_dtype,
+                                           uint8_t* codes, uint8_t* scales, void* stream) {
+  if (!X || !codes || !scales) return GLOWQ_ERR_NULL;
+  if (T < 1 || T > (1 << 20) || d_in < 32 || d_in > (1 << 16) || d_in % 32) return GLOWQ_ERR_SHAPE;
+  if (act_dtype != GLOWQ_F16 && act_dtype != GLOWQ_BF16) return GLOWQ_ERR_DTYPE;
+  if (misaligned(X) || misaligned(codes)) return GLOWQ_ERR_ALIGN;
+  return hip_status(launch_mx_quantize_x(X, T, d_in, act_dtype, codes, scales, (hipStream_t)stream));
+}
+
+// the unit checks of the ordinary forward without its group size (MX blocks are 32 channels)
+static glowq_status validate_mx(const glowq_unit* u, bool ptrs, bool corrected) {
+  if (!u) return GLOWQ_ERR_NULL;
+  glowq_unit v = *u;
+  v.group_size = 128;
+  glowq_status s = validate(&v, ptrs, corrected);
+  if (s != GLOWQ_OK) return s;
+  if (u->T > MX_MAX_TOKENS) return GLOWQ_ERR_UNSUPPORTED;
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_mx_workspace_bytes(const glowq_unit* u, size_t* bytes) {
+  if (!u || !bytes) return GLOWQ_ERR_NULL;
+  glowq_status s = validate_mx(u, false, false);
+  if (s != GLOWQ_OK) return s;
+  *bytes = plan_mx_workspace(*u, nullptr).bytes;
+  return GLOWQ_OK;
+}
+
+glowq_status glowq_mx_group_forward(const glowq_unit* u, int32_t restore, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  const bool corrected = u && u->r > 0 && restore;
+  glowq_status s = validate_mx(u, true, corrected);
+  if (s != GLOWQ_OK) return s;
+  if (!workspace) return GLOWQ_ERR_WORKSPACE;
+  if ((uintptr_t)workspace & 255u) return GLOWQ_ERR_ALIGN;
+  if (workspace_bytes < plan_mx_workspace(*u, nullptr).bytes) return GLOWQ_ERR_WORKSPACE;
+  return hip_status(launch_mx_forward(*u, restore != 0, (char*)workspace, (hipStream_t)stream));
+}
+
 glowq_status glowq_debug_unpack(const void* w_prepared, int32_t d_out, int32_t d_in,
                                 int32_t group_size, uint8_t* q_out, void* stream) {
   if (!w_prepared || !q_out) return GLOWQ_ERR_NULL;

@@ -16,7 +16,7 @@ import sys
 CSRC = os.path.dirname(os.path.abspath(__file__))
 LIB_DIR = os.path.join(os.path.dirname(CSRC), "lib")
 LIB = os.path.join(LIB_DIR, "libglowq.so")
-SOURCES = ["api.hip", "prepare.hip", "proj.hip", "decode.hip", "prefill.hip", "probe.hip", "factorize.hip"]
+SOURCES = ["api.hip", "prepare.hip", "proj.hip", "decode.hip", "prefill.hip", "probe.hip", "factorize.hip", "mx.hip"]
 # packed-fp32 instructions are switched off for device code on purpose
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -52,6 +52,21 @@ FactorizePlan plan_factorize(const glowq_unit& u, int r, int p);
 hipError_t launch_factorize(const glowq_unit& u, const float* const* W_modules, const double* sigma_x,
                             int r, int p, int q, const double* Omega, char* ws, void* const* A_out,
                             void* B_out, double* sigma_out, hipStream_t st);
+// Microscaling variant (MXFP4 weights, MXFP8 activations), up to 16 tokens.
+struct MxWorkspace {
+  UnitWorkspace unit;       // the unit's ordinary slice (projection partial sums, R in 16 bit)
+  size_t off_xcodes;        // E4M3 codes of the activations, [16][d_in]
+  size_t off_xscales;       // their E8M0 block scales, [16][d_in / 32]
+  size_t bytes;
+};
+constexpr int MX_MAX_TOKENS = 16;
+size_t mx_prepared_bytes(int d_out, int d_in);
+MxWorkspace plan_mx_workspace(const glowq_unit& u, char* base);
+hipError_t launch_mx_prepare(const uint32_t* codes, const uint8_t* scales, int d_out, int d_in, void* prepared,
+                             hipStream_t st);
+hipError_t launch_mx_quantize_x(const void* X, int T, int d_in, int act, uint8_t* codes, uint8_t* scales,
+                                hipStream_t st);
+hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace, hipStream_t st);
 // slices' start offsets in units of 256 bytes (every slice is 256-byte aligned)
 constexpr int STATUS_BATCH = 256;
 struct StatusBatch {

@@ -1,0 +1,269 @@
+// Microscaling variant of the group forward for up to 16 tokens: MXFP4 weights and MXFP8
+// activations in the main product, on the block-scaled matrix instruction of gfx950
+// (v_mfma_scale_f32_16x16x128_f8f6f4), the 16-bit low-rank correction unchanged (paper
+// Sec. 3.3, Eqs. 8-9, on the datatypes of the datatype appendix and the W4A8 rows of the
+// main results; formats of the OCP MX v1.0 specification: blocks of 32 channels, E8M0
+// scale, E2M1 / E4M3 elements).
+//
+// Operand layouts of the instruction (activations as A in fp8, weights as B in fp4),
+// verified on the hardware:
+//   A, fp8: lane l = token (l & 15), group g = l >> 4; register w, byte b holds channel
+//           (w < 4 ? 0 : 64) + 16 g + 4 (w & 3) + b of the 128-channel tile
+//   B, fp4: lane l = row (l & 15), group g; register w < 4, nibble n holds channel 32 g + 8 w + n
+//   scales: the scale of (token or row i, 32-channel block kb) comes from lane i + 16 kb,
+//           the byte of its scale register that the instruction's byte selector names
+//   D:      lane l, register v holds (token 4 (l >> 4) + v, row l & 15)
+// So a weight lane's four registers are 32 consecutive channels, exactly one MX block with
+// its scale in the same lane, and a weight tile record is the canonical packed words of 16
+// rows x 128 channels, lane after lane: no bit is touched between HBM and the matrix core.
+//
+// Weight storage (glowq_mx_prepare_weights): codes region [row block][tile][lane][4 words],
+// then scales region [row block][tile][lane] bytes.  Rows past d_out: code 0, scale 127.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace glowq {
+
+typedef int v8i_t __attribute__((ext_vector_type(8)));
+
+// ---------------------------------------------------------------------------------------
+// preparation of the weights: one thread per word of the codes region / byte of the scales
+// ---------------------------------------------------------------------------------------
+__global__ void k_mx_prepare(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                             int d_out, int d_in, uint32_t* __restrict__ out_codes,
+                             uint8_t* __restrict__ out_scales, long long n_words, long long n_scales) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int ktiles = d_in / 128;
+  if (idx < n_words) {
+    const int w = (int)(idx & 3), lane = (int)((idx >> 2) & 63);
+    const long long tile = idx >> 8;
+    const int kt = (int)(tile % ktiles), rb = (int)(tile / ktiles);
+    const int row = rb * 16 + (lane & 15);
+    out_codes[idx] = row < d_out ? codes[(long long)row * (d_in / 8) + 16 * kt + 4 * (lane >> 4) + w] : 0u;
+  }
+  if (idx < n_scales) {
+    const int lane = (int)(idx & 63);
+    const long long tile = idx >> 6;
+    const int kt = (int)(tile % ktiles), rb = (int)(tile / ktiles);
+    const int row = rb * 16 + (lane & 15);
+    out_scales[idx] = row < d_out ? scales[(long long)row * (d_in / 32) + 4 * kt + (lane >> 4)] : (uint8_t)127;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// MXFP8 (E4M3) quantisation of the activations: one thread per (token, block of 32)
+// ---------------------------------------------------------------------------------------
+// code of |v| < 512 rounded to E4M3, nearest even, clamped to 448
+__device__ inline uint32_t e4m3_round(double a) {
+  if (a < 0x1p-6) return (uint32_t)__builtin_rint(a * 0x1p9);      // subnormal grid (8 is the smallest normal)
+  const uint64_t mag = __builtin_bit_cast(uint64_t, a);
+  const uint64_t r = mag + ((1ull << 48) - 1) + ((mag >> 49) & 1);   // 52 - 3 = 49 bits dropped
+  const uint32_t code = (uint32_t)(((r >> 52) - 1023 + 7) << 3) | (uint32_t)((r >> 49) & 7);
+  return code > 0x7Eu ? 0x7Eu : code;
+}
+
+template <int ACT>
+__global__ void __launch_bounds__(256) k_mx_quantize_x(const uint16_t* __restrict__ X, int T, int d_in,
+                                                       uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int blocks = d_in / 32;
+  if (idx >= T * blocks) return;
+  const int t = idx / blocks, b = idx - t * blocks;
+  const u32x4_t* src = (const u32x4_t*)(X + (long long)t * d_in + 32 * b);
+  double v[32];
+  double amax = 0.0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const u32x4_t w = src[q];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t word = w[e >> 1];
+      const double x = act16_value<ACT>((e & 1) ? (word >> 16) : (word & 0xffffu));
+      v[8 * q + e] = x;
+      amax = fmax(amax, fabs(x));
+    }
+  }
+  int shared = 0;
+  if (amax > 0.0) {
+    shared = (int)((__builtin_bit_cast(uint64_t, amax) >> 52) & 0x7ff) - 1023 - 8;   // floor(log2 amax) - emax
+    shared = max(-127, min(127, shared));
+  }
+  const double inv = __builtin_bit_cast(double, (uint64_t)(1023 - shared) << 52);      // 2^-shared
+  uint32_t out[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const double x = v[4 * q + e] * inv;
+      uint32_t c = e4m3_round(fabs(x));
+      if (x < 0.0 && c != 0) c |= 0x80u;
+      word |= c << (8 * e);
+    }
+    out[q] = word;
+  }
+  u32x4_t* dst = (u32x4_t*)(codes + (long long)t * d_in + 32 * b);
+  dst[0] = u32x4_t{out[0], out[1], out[2], out[3]};
+  dst[1] = u32x4_t{out[4], out[5], out[6], out[7]};
+  scales[(long long)t * blocks + b] = (uint8_t)(shared + 127);
+}
+
+// ---------------------------------------------------------------------------------------
+// the forward.  One workgroup (4 waves) per 16-row block of one module; wave w takes the
+// 128-channel tiles w, w + 4, ... and the 32-rank steps w, w + 4, ... of the correction; the
+// four partial tiles meet in LDS and wave 0 stores.
+// ---------------------------------------------------------------------------------------
+struct MxModule {
+  const uint32_t* codes;     // prepared codes region
+  const uint8_t* scales;     // prepared scales region
+  const uint16_t* A;         // act dtype [d_out][r]
+  void* Y;
+  int d_out, ldy;
+  int first_block;           // index of the module's first row block in the grid
+};
+
+struct MxArgs {
+  MxModule mod[GLOWQ_MAX_MODULES];
+  int n_modules;
+  const uint8_t* xcodes;     // [T][d_in] E4M3
+  const uint8_t* xscales;    // [T][d_in / 32] E8M0
+  const uint16_t* R16;       // act dtype [T][r], or NULL when not restored
+  int T, d_in, r;
+  int out_f32;
+};
+
+template <int ACT>
+__global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
+  __shared__ float part[4][64][4];
+  int mi = 0;
+#pragma unroll
+  for (int i = 1; i < GLOWQ_MAX_MODULES; ++i)
+    if (i < a.n_modules && (int)blockIdx.x >= a.mod[i].first_block) mi = i;
+  const MxModule& m = a.mod[mi];
+  const int rb = (int)blockIdx.x - m.first_block;
+  const int w = threadIdx.x >> 6, l = threadIdx.x & 63, i = l & 15, g = l >> 4;
+  const int ktiles = a.d_in / 128;
+  const bool tok = i < a.T;
+  float4_t acc = {0.f, 0.f, 0.f, 0.f};
+  const u32x4_t* wc = (const u32x4_t*)m.codes + ((long long)rb * ktiles) * 64 + l;
+  const uint8_t* ws = m.scales + ((long long)rb * ktiles) * 64 + l;
+  const uint8_t* xc = a.xcodes + (long long)(tok ? i : 0) * a.d_in + 16 * g;
+  const uint8_t* xs = a.xscales + (long long)(tok ? i : 0) * (a.d_in / 32) + g;
+#pragma unroll 4
+  for (int kt = w; kt < ktiles; kt += 4) {
+    const u32x4_t bw = wc[(long long)kt * 64];
+    const int sb = ws[(long long)kt * 64];
+    u32x4_t a0 = {0, 0, 0, 0}, a1 = {0, 0, 0, 0};
+    int sa = 127;
+    if (tok) {
+      a0 = *(const u32x4_t*)(xc + 128 * kt);
+      a1 = *(const u32x4_t*)(xc + 128 * kt + 64);
+      sa = xs[4 * kt];
+    }
+    const v8i_t A = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
+    const v8i_t B = {(int)bw[0], (int)bw[1], (int)bw[2], (int)bw[3], 0, 0, 0, 0};
+    acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B, acc, 0, 4, 0, sa, 0, sb);
+  }
+  // correction: + R A_i^T, 32 ranks per instruction (token rows as A, weight rows as B; lane
+  // (i, g) holds ranks 32 s + 8 g .. + 8)
+  if (a.R16) {
+    const int row = rb * 16 + i;
+    for (int s = w; 32 * s < a.r; s += 4) {
+      const int j0 = 32 * s + 8 * g;
+      u32x4_t ra = {0, 0, 0, 0}, rbv = {0, 0, 0, 0};
+      if (j0 < a.r) {
+        if (tok) ra = *(const u32x4_t*)(a.R16 + (long long)i * a.r + j0);
+        if (row < m.d_out) rbv = *(const u32x4_t*)(m.A + (long long)row * a.r + j0);
+      }
+      acc = mfma16<ACT>(ra, rbv, acc);
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) part[w][l][v] = acc[v];
+  __syncthreads();
+  if (w != 0) return;
+  const int row = rb * 16 + i;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int t = 4 * g + v;
+    const float y = ((part[0][l][v] + part[1][l][v]) + part[2][l][v]) + part[3][l][v];
+    if (t < a.T && row < m.d_out) {
+      if (a.out_f32) ((float*)m.Y)[(long long)t * m.ldy + row] = y;
+      else ((uint16_t*)m.Y)[(long long)t * m.ldy + row] = to_act16<ACT>(y);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+size_t mx_prepared_bytes(int d_out, int d_in) {
+  return (size_t)((d_out + 15) / 16) * (size_t)(d_in / 128) * (1024 + 64);
+}
+
+hipError_t launch_mx_prepare(const uint32_t* codes, const uint8_t* scales, int d_out, int d_in, void* prepared,
+                             hipStream_t st) {
+  const long long tiles = (long long)((d_out + 15) / 16) * (d_in / 128);
+  const long long n_words = tiles * 256, n_scales = tiles * 64;
+  k_mx_prepare<<<dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st>>>(
+      codes, scales, d_out, d_in, (uint32_t*)prepared, (uint8_t*)prepared + n_words * 4, n_words, n_scales);
+  return hipGetLastError();
+}
+
+hipError_t launch_mx_quantize_x(const void* X, int T, int d_in, int act, uint8_t* codes, uint8_t* scales,
+                                hipStream_t st) {
+  const int n = T * (d_in / 32);
+  dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (act == GLOWQ_F16) k_mx_quantize_x<ACT_F16><<<grid, block, 0, st>>>((const uint16_t*)X, T, d_in, codes, scales);
+  else k_mx_quantize_x<ACT_BF16><<<grid, block, 0, st>>>((const uint16_t*)X, T, d_in, codes, scales);
+  return hipGetLastError();
+}
+
+MxWorkspace plan_mx_workspace(const glowq_unit& u, char* base) {
+  MxWorkspace w;
+  w.unit = plan_unit_workspace(u, base);
+  w.off_xcodes = w.unit.bytes;
+  w.off_xscales = (w.off_xcodes + (size_t)16 * u.d_in + 255) & ~(size_t)255;
+  w.bytes = (w.off_xscales + (size_t)16 * (u.d_in / 32) + 255) & ~(size_t)255;
+  return w;
+}
+
+hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace, hipStream_t st) {
+  const MxWorkspace w = plan_mx_workspace(u, workspace);
+  uint8_t* xcodes = (uint8_t*)(workspace + w.off_xcodes);
+  uint8_t* xscales = (uint8_t*)(workspace + w.off_xscales);
+  hipError_t err = launch_mx_quantize_x(u.X, u.T, u.d_in, u.act_dtype, xcodes, xscales, st);
+  if (err != hipSuccess) return err;
+  const bool corrected = restore && u.r > 0;
+  if (corrected) {
+    err = launch_proj(u, w.unit, nullptr, true, st);       // R = X B^T in the activation type
+    if (err != hipSuccess) return err;
+  }
+  MxArgs a;
+  a.n_modules = u.n_modules;
+  int blocks = 0;
+  for (int i = 0; i < u.n_modules; ++i) {
+    const glowq_module& m = u.modules[i];
+    const long long tiles = (long long)((m.d_out + 15) / 16) * (u.d_in / 128);
+    a.mod[i].codes = (const uint32_t*)m.w_prepared;
+    a.mod[i].scales = (const uint8_t*)m.w_prepared + tiles * 1024;
+    a.mod[i].A = (const uint16_t*)m.A;
+    a.mod[i].Y = m.Y;
+    a.mod[i].d_out = m.d_out;
+    a.mod[i].ldy = m.ldy;
+    a.mod[i].first_block = blocks;
+    blocks += (m.d_out + 15) / 16;
+  }
+  a.xcodes = xcodes;
+  a.xscales = xscales;
+  a.R16 = corrected ? (const uint16_t*)(w.unit.base + w.unit.off_r16) : nullptr;
+  a.T = u.T;
+  a.d_in = u.d_in;
+  a.r = u.r;
+  a.out_f32 = u.out_dtype == GLOWQ_F32;
+  if (u.act_dtype == GLOWQ_F16) k_mx_decode<ACT_F16><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
+  else k_mx_decode<ACT_BF16><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace glowq
