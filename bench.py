@@ -60,6 +60,9 @@ WORKLOADS = {
     # offline factorisation (Alg. 1) of a q/k/v group with d = 3072, r = 64, p = 16, q = 2:
     # the setting of the paper's timing table of the randomised SVD
     "factorize_d3072": (0, 0, "factorize"),
+    # microscaling variant (MXFP4 weights, MXFP8 activations) on the shapes of workload 2
+    "cfg2_T1_mx": (2, 1, "mx"),
+    "cfg2_T16_mx": (2, 16, "mx"),
 }
 METRIC = "grouped W4+low-rank forward: decode HBM GB/s & us/group; prefill TFLOP/s"
 
@@ -487,6 +490,8 @@ def main() -> int:
             return importance_scores(torch, args)
         if bound == "factorize":
             return factorize_unit(torch, args)
+        if bound == "mx":
+            return mx_workload(torch, args, args.workload)
         out = run_workload(args.workload, args, torch, not args.no_cpu_baseline)
         out["peaks"] = {"hbm_GBps": HBM_PEAK_GBS, "mfma_f16_bf16_TFLOPs": MFMA_PEAK_TFLOPS}
         print(json.dumps(out))
@@ -579,6 +584,113 @@ def importance_scores(torch, args):
     print(json.dumps(out))
     if not args.no_checks and err > 1e-9:
         raise SystemExit(f"bench.py: importance scores do not match the oracle: {out['checks']}")
+    return 0
+
+
+def mx_workload(torch, args, name):
+    """glowq_mx_group_forward on the q/k/v unit of workload 2: MXFP4 weights (E2M1 codes, an
+    E8M0 scale per 32 channels), activations quantised to MXFP8 inside the call, the 16-bit
+    correction as in the W4A16 path.  Operands are random codes and scales of the recipe's
+    magnitudes, rotated over enough copies to defeat the caches; the first copy's first
+    module is checked against the oracle."""
+    import numpy as np
+
+    import paper_2603_25385_amd as G
+    from glowq_inputs import CONFIGS, config_units
+    from oracle import glowq_oracle as O
+    from oracle import mx_oracle as MX
+
+    cfg_id, T, _ = WORKLOADS[name]
+    cfg = CONFIGS[cfg_id]
+    shape = config_units(cfg_id)[0]
+    r, act = cfg["r"], cfg["act"]
+    d = shape.d_in
+    steps = args.steps if args.steps is not None else 200
+    warmup = args.warmup if args.warmup is not None else 20
+    restored = args.restore != "none"
+    by = shape.rows * d // 2 + shape.rows * (d // 32) + T * d * 2 + T * shape.rows * 2
+    fl = 2 * T * d * shape.rows
+    if restored:
+        by += shape.rows * r * 2 + r * d * 2
+        fl += 2 * T * r * d + 2 * T * r * shape.rows
+    ro = by - T * shape.rows * 2
+    n_rot = args.rot if args.rot is not None else max(1, min(24, int(np.ceil(600e6 / ro))))
+    act_code = {"f16": G.GLOWQ_F16, "bf16": G.GLOWQ_BF16}[act]
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[act]
+    st = torch.cuda.current_stream().cuda_stream
+    gen = torch.Generator(device="cuda")
+    keep, units, host0, y0 = [], [], None, None
+    for rot in range(n_rot):
+        gen.manual_seed(cfg["seed"] + 77 * rot)
+        X = (torch.randn(T, d, generator=gen, device="cuda") * 1.0).to(tdt)
+        B = (torch.randn(r, d, generator=gen, device="cuda") * 0.01).to(tdt)
+        mods, ys = [], []
+        for o in shape.d_outs:
+            codes = torch.randint(-2 ** 31, 2 ** 31 - 1, (o, d // 8), generator=gen, device="cuda", dtype=torch.int64).to(torch.int32)
+            scales = torch.randint(117, 123, (o, d // 32), generator=gen, device="cuda", dtype=torch.int64).to(torch.uint8)
+            A = (torch.randn(o, r, generator=gen, device="cuda") * 0.01).to(tdt)
+            prep = torch.empty(G.glowq_mx_prepared_bytes(o, d), dtype=torch.uint8, device="cuda")
+            G.glowq_mx_prepare_weights(codes.data_ptr(), scales.data_ptr(), o, d, prep.data_ptr(), st)
+            Y = torch.empty((T, o), dtype=tdt, device="cuda")
+            keep += [prep, A, Y]
+            ys.append(Y)
+            mods.append(G.make_module(prep.data_ptr(), A.data_ptr(), Y.data_ptr(), o, o))
+            if rot == 0 and host0 is None:
+                b16 = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+                words = codes.cpu().numpy().view(np.uint32)
+                host0 = dict(X=b16(X), B=b16(B), act=act, r=r, d_in=d, T=T,
+                             modules=[dict(codes=O.unpack_int4(words), scales=scales.cpu().numpy(),
+                                           A=b16(A), d_out=o)])
+                y0 = Y
+            torch.cuda.synchronize()
+        keep += [X, B]
+        units.append(G.make_unit(X.data_ptr(), B.data_ptr(), mods, T, d, r, 0, act_code, act_code))
+    ws_bytes = G.glowq_mx_workspace_bytes(units[0])
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        G.glowq_mx_group_forward(units[i % n_rot], 1 if restored else 0, ws.data_ptr(), ws_bytes,
+                                 torch.cuda.current_stream().cuda_stream)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ms, wall = time_steps(torch, step, steps, args.mode, REPLAYS)
+    ms_hot, _ = time_steps(torch, lambda i: step(0), steps, args.mode, 2)
+    med = float(np.median(ms))
+    y0.fill_(float("nan"))
+    step(0)
+    torch.cuda.synchronize()
+    ref = MX.mx_group_forward(host0, restored)[0]
+    err = rel_err(y0.to(torch.float64).cpu().numpy(), ref)
+    tol = TOL + ULP[act]
+    gbs = by / (med * 1e-3) / 1e9
+    out = {"metric": METRIC + " (microscaling variant: MXFP4 weights, MXFP8 activations)", "value": gbs,
+           "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": med,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "mxfp4 x mxfp8 (fp32 accumulate)",
+           "data": "synthetic",
+           "config": {"workload": f"{cfg['name']} T={T} r={r} MXFP4/MXFP8 ({name})", "units": 1,
+                      "restored_units": int(restored), "rotating_copies": n_rot, "launch": args.mode},
+           "us_per_step": med * 1e3,
+           "timing": {"replays": REPLAYS, "us_per_step_median": med * 1e3, "us_per_step_min": min(ms) * 1e3,
+                      "us_per_step_max": max(ms) * 1e3, "wall_us_per_step_median": float(np.median(wall)) * 1e3,
+                      "hot_us_per_step": min(ms_hot) * 1e3},
+           "algorithmic_bytes": by, "algorithmic_flops": fl,
+           "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": gbs / HBM_PEAK_GBS, "traffic": None},
+           "checks": {"parity": {"module": 0, "max_rel_err": err, "tolerance": tol, "ok": bool(err <= tol)}}}
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        MX.mx_group_forward(host0, restored)
+        dt = time.perf_counter() - t0
+        cb = by * host0["modules"][0]["d_out"] / shape.rows
+        out["cpu_baseline"] = {"value": cb / dt / 1e9, "unit": "GB/s", "cores": os.cpu_count(), "kind": "oracle",
+                               "cpu_model": cpu_model(),
+                               "sample": "module 0 of the unit (%d of %d rows), one pass, %.2f s" % (
+                                   host0["modules"][0]["d_out"], shape.rows, dt)}
+    print(json.dumps(out))
+    if not args.no_checks and err > tol:
+        raise SystemExit(f"bench.py: microscaling forward does not match the oracle: {out['checks']}")
     return 0
 
 

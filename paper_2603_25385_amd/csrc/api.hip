@@ -522,7 +522,7 @@ glowq_status glowq_mx_workspace_bytes(const glowq_unit* u, size_t* bytes) {
   if (!u || !bytes) return GLOWQ_ERR_NULL;
   glowq_status s = validate_mx(u, false, false);
   if (s != GLOWQ_OK) return s;
-  *bytes = plan_mx_workspace(*u, nullptr).bytes;
+  *bytes = plan_mx_workspace(*u).bytes;
   return GLOWQ_OK;
 }
 
@@ -533,7 +533,7 @@ glowq_status glowq_mx_group_forward(const glowq_unit* u, int32_t restore, void* 
   if (s != GLOWQ_OK) return s;
   if (!workspace) return GLOWQ_ERR_WORKSPACE;
   if ((uintptr_t)workspace & 255u) return GLOWQ_ERR_ALIGN;
-  if (workspace_bytes < plan_mx_workspace(*u, nullptr).bytes) return GLOWQ_ERR_WORKSPACE;
+  if (workspace_bytes < plan_mx_workspace(*u).bytes) return GLOWQ_ERR_WORKSPACE;
   return hip_status(launch_mx_forward(*u, restore != 0, (char*)workspace, (hipStream_t)stream));
 }
 

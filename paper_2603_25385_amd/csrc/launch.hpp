@@ -54,14 +54,15 @@ hipError_t launch_factorize(const glowq_unit& u, const float* const* W_modules, 
                             void* B_out, double* sigma_out, hipStream_t st);
 // Microscaling variant (MXFP4 weights, MXFP8 activations), up to 16 tokens.
 struct MxWorkspace {
-  UnitWorkspace unit;       // the unit's ordinary slice (projection partial sums, R in 16 bit)
+  size_t off_rpart;         // fp32 partial sums of the projection, [ks][16][r]
   size_t off_xcodes;        // E4M3 codes of the activations, [16][d_in]
   size_t off_xscales;       // their E8M0 block scales, [16][d_in / 32]
   size_t bytes;
+  int ks, kslice;           // K slices of the projection and channels per slice
 };
 constexpr int MX_MAX_TOKENS = 16;
 size_t mx_prepared_bytes(int d_out, int d_in);
-MxWorkspace plan_mx_workspace(const glowq_unit& u, char* base);
+MxWorkspace plan_mx_workspace(const glowq_unit& u);
 hipError_t launch_mx_prepare(const uint32_t* codes, const uint8_t* scales, int d_out, int d_in, void* prepared,
                              hipStream_t st);
 hipError_t launch_mx_quantize_x(const void* X, int T, int d_in, int act, uint8_t* codes, uint8_t* scales,

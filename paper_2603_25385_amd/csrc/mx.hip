@@ -51,7 +51,7 @@ __global__ void k_mx_prepare(const uint32_t* __restrict__ codes, const uint8_t* 
 }
 
 // ---------------------------------------------------------------------------------------
-// MXFP8 (E4M3) quantisation of the activations: one thread per (token, block of 32)
+// MXFP8 (E4M3) quantisation of the activations
 // ---------------------------------------------------------------------------------------
 // code of |v| < 512 rounded to E4M3, nearest even, clamped to 448
 __device__ inline uint32_t e4m3_round(double a) {
@@ -62,50 +62,104 @@ __device__ inline uint32_t e4m3_round(double a) {
   return code > 0x7Eu ? 0x7Eu : code;
 }
 
+// Eight neighbouring lanes per (token, block of 32): four values each, the block maximum by
+// lane shuffles.  idx counts (token, block, eighth); every lane of a wave must call this
+// (lanes past the end take part in the shuffles and store nothing).
 template <int ACT>
-__global__ void __launch_bounds__(256) k_mx_quantize_x(const uint16_t* __restrict__ X, int T, int d_in,
-                                                       uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ inline void mx_quantize_block(const uint16_t* __restrict__ X, int T, int d_in,
+                                         uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, int idx) {
   const int blocks = d_in / 32;
-  if (idx >= T * blocks) return;
-  const int t = idx / blocks, b = idx - t * blocks;
-  const u32x4_t* src = (const u32x4_t*)(X + (long long)t * d_in + 32 * b);
-  double v[32];
-  double amax = 0.0;
+  const bool live = idx < T * blocks * 8;
+  const int blk = live ? idx >> 3 : 0, sub = idx & 7;
+  const int t = blk / blocks, b = blk - t * blocks;
+  const uint2 w = *(const uint2*)(X + (long long)t * d_in + 32 * b + 4 * sub);
+  double v[4];
+  v[0] = act16_value<ACT>(w.x & 0xffffu);
+  v[1] = act16_value<ACT>(w.x >> 16);
+  v[2] = act16_value<ACT>(w.y & 0xffffu);
+  v[3] = act16_value<ACT>(w.y >> 16);
+  double amax = fmax(fmax(fabs(v[0]), fabs(v[1])), fmax(fabs(v[2]), fabs(v[3])));
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const u32x4_t w = src[q];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint32_t word = w[e >> 1];
-      const double x = act16_value<ACT>((e & 1) ? (word >> 16) : (word & 0xffffu));
-      v[8 * q + e] = x;
-      amax = fmax(amax, fabs(x));
-    }
-  }
+  for (int o = 1; o < 8; o <<= 1) amax = fmax(amax, __shfl_xor(amax, o, 64));
   int shared = 0;
   if (amax > 0.0) {
     shared = (int)((__builtin_bit_cast(uint64_t, amax) >> 52) & 0x7ff) - 1023 - 8;   // floor(log2 amax) - emax
     shared = max(-127, min(127, shared));
   }
   const double inv = __builtin_bit_cast(double, (uint64_t)(1023 - shared) << 52);      // 2^-shared
-  uint32_t out[8];
+  uint32_t word = 0;
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    uint32_t word = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const double x = v[4 * q + e] * inv;
-      uint32_t c = e4m3_round(fabs(x));
-      if (x < 0.0 && c != 0) c |= 0x80u;
-      word |= c << (8 * e);
-    }
-    out[q] = word;
+  for (int e = 0; e < 4; ++e) {
+    const double x = v[e] * inv;
+    uint32_t c = e4m3_round(fabs(x));
+    if (x < 0.0 && c != 0) c |= 0x80u;
+    word |= c << (8 * e);
   }
-  u32x4_t* dst = (u32x4_t*)(codes + (long long)t * d_in + 32 * b);
-  dst[0] = u32x4_t{out[0], out[1], out[2], out[3]};
-  dst[1] = u32x4_t{out[4], out[5], out[6], out[7]};
-  scales[(long long)t * blocks + b] = (uint8_t)(shared + 127);
+  if (!live) return;
+  *(uint32_t*)(codes + (long long)t * d_in + 32 * b + 4 * sub) = word;
+  if (sub == 0) scales[(long long)t * blocks + b] = (uint8_t)(shared + 127);
+}
+
+template <int ACT>
+__global__ void __launch_bounds__(256) k_mx_quantize_x(const uint16_t* __restrict__ X, int T, int d_in,
+                                                       uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+  mx_quantize_block<ACT>(X, T, d_in, codes, scales, (int)(blockIdx.x * blockDim.x + threadIdx.x));
+}
+
+// First launch of the forward (workgroups of 16 waves): the leading `ks` workgroups each take
+// a slice of `kslice` channels (a multiple of 256; at most 16 slices) of the shared projection R = X B^T and leave fp32 partial sums
+// Rpart[slice][16][r]; the others quantise the activations.  Nothing waits inside.  In a
+// projection workgroup wave w owns the 16-rank block w % nbp and the part w / nbp of the
+// slice's channels (nbp = rank blocks rounded up to a power of two), so that every load of a
+// wave is in flight at once; the parts meet in LDS.
+struct MxFrontArgs {
+  const uint16_t* X;
+  const uint16_t* B;         // act dtype [r][d_in], or NULL when not restored
+  float* Rpart;
+  uint8_t* xcodes;
+  uint8_t* xscales;
+  int T, d_in, r, ks, kslice;
+};
+constexpr int MX_FRONT_THREADS = 1024;
+
+template <int ACT>
+__global__ void __launch_bounds__(MX_FRONT_THREADS) k_mx_front(MxFrontArgs a) {
+  __shared__ float part[16][64][4];
+  const int n_proj = a.B ? a.ks : 0;
+  if ((int)blockIdx.x >= n_proj) {
+    mx_quantize_block<ACT>(a.X, a.T, a.d_in, a.xcodes, a.xscales,
+                           (int)((blockIdx.x - n_proj) * MX_FRONT_THREADS + threadIdx.x));
+    return;
+  }
+  const int kz = blockIdx.x, w = threadIdx.x >> 6, l = threadIdx.x & 63, i = l & 15, g = l >> 4;
+  const int nbs = (a.r + 15) >> 4;
+  const int nbp = nbs <= 1 ? 1 : nbs <= 2 ? 2 : nbs <= 4 ? 4 : 8;
+  const int kparts = min(16 / nbp, 8), per = a.kslice / kparts;       // (per: a multiple of 32)
+  const int nb = w % nbp, kp = w / nbp;
+  const int kbeg = kz * a.kslice + kp * per, kend = kp < kparts ? min(a.d_in, kbeg + per) : kbeg;
+  const int rank = 16 * nb + i;
+  const bool tok = i < a.T, live = rank < a.r;
+  float4_t acc = {0.f, 0.f, 0.f, 0.f};
+  const uint16_t* xp = a.X + (long long)(tok ? i : 0) * a.d_in + 8 * g;
+  const uint16_t* bp = a.B + (long long)(live ? rank : 0) * a.d_in + 8 * g;
+#pragma unroll 16
+  for (int k0 = kbeg; k0 < kend; k0 += 32) {
+    u32x4_t xa = {0, 0, 0, 0}, bb = {0, 0, 0, 0};
+    if (tok) xa = *(const u32x4_t*)(xp + k0);
+    if (live) bb = *(const u32x4_t*)(bp + k0);
+    acc = mfma16<ACT>(xa, bb, acc);
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) part[w][l][v] = acc[v];
+  __syncthreads();
+  if (kp != 0) return;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    float sum = 0.f;
+    for (int q = 0; q < kparts; ++q) sum += part[q * nbp + nb][l][v];
+    const int t = 4 * g + v;
+    if (t < a.T && live) a.Rpart[((long long)kz * 16 + t) * a.r + rank] = sum;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -127,7 +181,8 @@ struct MxArgs {
   int n_modules;
   const uint8_t* xcodes;     // [T][d_in] E4M3
   const uint8_t* xscales;    // [T][d_in / 32] E8M0
-  const uint16_t* R16;       // act dtype [T][r], or NULL when not restored
+  const float* Rpart;        // fp32 [ks][16][r] partial sums of R, or NULL when not restored
+  int ks;
   int T, d_in, r;
   int out_f32;
 };
@@ -149,7 +204,7 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
   const uint8_t* ws = m.scales + ((long long)rb * ktiles) * 64 + l;
   const uint8_t* xc = a.xcodes + (long long)(tok ? i : 0) * a.d_in + 16 * g;
   const uint8_t* xs = a.xscales + (long long)(tok ? i : 0) * (a.d_in / 32) + g;
-#pragma unroll 4
+#pragma unroll 8
   for (int kt = w; kt < ktiles; kt += 4) {
     const u32x4_t bw = wc[(long long)kt * 64];
     const int sb = ws[(long long)kt * 64];
@@ -164,19 +219,30 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
     const v8i_t B = {(int)bw[0], (int)bw[1], (int)bw[2], (int)bw[3], 0, 0, 0, 0};
     acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B, acc, 0, 4, 0, sa, 0, sb);
   }
-  // correction: + R A_i^T, 32 ranks per instruction (token rows as A, weight rows as B; lane
-  // (i, g) holds ranks 32 s + 8 g .. + 8)
-  if (a.R16) {
-    const int row = rb * 16 + i;
-    for (int s = w; 32 * s < a.r; s += 4) {
-      const int j0 = 32 * s + 8 * g;
-      u32x4_t ra = {0, 0, 0, 0}, rbv = {0, 0, 0, 0};
-      if (j0 < a.r) {
-        if (tok) ra = *(const u32x4_t*)(a.R16 + (long long)i * a.r + j0);
-        if (row < m.d_out) rbv = *(const u32x4_t*)(m.A + (long long)row * a.r + j0);
+  // the wave's correction step (ranks 32 w + 8 g .. + 8; r <= 128, so a wave has at most one):
+  // R is the sum of the projection's slices, in slice order, rounded to the activation type
+  // (token rows as A, weight rows as B)
+  if (a.Rpart != nullptr && 32 * w < a.r) {
+    u32x4_t ra = {0, 0, 0, 0}, rbv = {0, 0, 0, 0};
+    const int j0 = 32 * w + 8 * g;
+    if (j0 < a.r) {
+      const int row = rb * 16 + i;
+      if (row < m.d_out) rbv = *(const u32x4_t*)(m.A + (long long)row * a.r + j0);
+      if (tok) {
+        float rs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+        for (int kz = 0; kz < a.ks; ++kz) {
+          const float4_t* p = (const float4_t*)(a.Rpart + ((long long)kz * 16 + i) * a.r + j0);
+          const float4_t p0 = p[0], p1 = p[1];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { rs[e] += p0[e]; rs[4 + e] += p1[e]; }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          ra[e] = (uint32_t)to_act16<ACT>(rs[2 * e]) | ((uint32_t)to_act16<ACT>(rs[2 * e + 1]) << 16);
       }
-      acc = mfma16<ACT>(ra, rbv, acc);
     }
+    acc = mfma16<ACT>(ra, rbv, acc);
   }
 #pragma unroll
   for (int v = 0; v < 4; ++v) part[w][l][v] = acc[v];
@@ -212,33 +278,45 @@ hipError_t launch_mx_prepare(const uint32_t* codes, const uint8_t* scales, int d
 
 hipError_t launch_mx_quantize_x(const void* X, int T, int d_in, int act, uint8_t* codes, uint8_t* scales,
                                 hipStream_t st) {
-  const int n = T * (d_in / 32);
+  const int n = T * (d_in / 32) * 8;
   dim3 grid((unsigned)((n + 255) / 256)), block(256);
   if (act == GLOWQ_F16) k_mx_quantize_x<ACT_F16><<<grid, block, 0, st>>>((const uint16_t*)X, T, d_in, codes, scales);
   else k_mx_quantize_x<ACT_BF16><<<grid, block, 0, st>>>((const uint16_t*)X, T, d_in, codes, scales);
   return hipGetLastError();
 }
 
-MxWorkspace plan_mx_workspace(const glowq_unit& u, char* base) {
+static size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+MxWorkspace plan_mx_workspace(const glowq_unit& u) {
   MxWorkspace w;
-  w.unit = plan_unit_workspace(u, base);
-  w.off_xcodes = w.unit.bytes;
-  w.off_xscales = (w.off_xcodes + (size_t)16 * u.d_in + 255) & ~(size_t)255;
-  w.bytes = (w.off_xscales + (size_t)16 * (u.d_in / 32) + 255) & ~(size_t)255;
+  // K slices of the projection: at most 16, a multiple of 256 channels each
+  w.kslice = ((u.d_in + 15) / 16 + 255) / 256 * 256;
+  w.ks = (u.d_in + w.kslice - 1) / w.kslice;
+  w.off_rpart = 0;
+  w.off_xcodes = up256((size_t)w.ks * 16 * (u.r > 0 ? u.r : 0) * 4);
+  w.off_xscales = w.off_xcodes + up256((size_t)MX_MAX_TOKENS * u.d_in);
+  w.bytes = w.off_xscales + up256((size_t)MX_MAX_TOKENS * (u.d_in / 32));
   return w;
 }
 
 hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace, hipStream_t st) {
-  const MxWorkspace w = plan_mx_workspace(u, workspace);
+  const MxWorkspace w = plan_mx_workspace(u);
   uint8_t* xcodes = (uint8_t*)(workspace + w.off_xcodes);
   uint8_t* xscales = (uint8_t*)(workspace + w.off_xscales);
-  hipError_t err = launch_mx_quantize_x(u.X, u.T, u.d_in, u.act_dtype, xcodes, xscales, st);
-  if (err != hipSuccess) return err;
+  float* rpart = (float*)(workspace + w.off_rpart);
   const bool corrected = restore && u.r > 0;
-  if (corrected) {
-    err = launch_proj(u, w.unit, nullptr, true, st);       // R = X B^T in the activation type
-    if (err != hipSuccess) return err;
-  }
+  const bool f16 = u.act_dtype == GLOWQ_F16;
+  MxFrontArgs fa;
+  fa.X = (const uint16_t*)u.X;
+  fa.B = corrected ? (const uint16_t*)u.B : nullptr;
+  fa.Rpart = rpart;
+  fa.xcodes = xcodes;
+  fa.xscales = xscales;
+  fa.T = u.T; fa.d_in = u.d_in; fa.r = u.r; fa.ks = w.ks; fa.kslice = w.kslice;
+  const int qblocks = (u.T * (u.d_in / 32) * 8 + MX_FRONT_THREADS - 1) / MX_FRONT_THREADS;
+  dim3 fgrid((unsigned)(qblocks + (corrected ? w.ks : 0)));
+  if (f16) k_mx_front<ACT_F16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
+  else k_mx_front<ACT_BF16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
   MxArgs a;
   a.n_modules = u.n_modules;
   int blocks = 0;
@@ -256,7 +334,8 @@ hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace,
   }
   a.xcodes = xcodes;
   a.xscales = xscales;
-  a.R16 = corrected ? (const uint16_t*)(w.unit.base + w.unit.off_r16) : nullptr;
+  a.Rpart = corrected ? rpart : nullptr;
+  a.ks = w.ks;
   a.T = u.T;
   a.d_in = u.d_in;
   a.r = u.r;

@@ -213,3 +213,39 @@ def test_factorize_argument_checks():
     with pytest.raises(G.GlowqError) as e:
         G.glowq_factorize_workspace_bytes(wide, 128, 136)   # r + p above the sketch limit
     assert e.value.status == G.GLOWQ_ERR_UNSUPPORTED
+
+
+def test_mx_argument_checks():
+    assert G.glowq_mx_prepared_bytes(64, 256) == 4 * 2 * (1024 + 64)        # 4 row blocks x 2 tiles
+    assert G.glowq_mx_prepared_bytes(40, 256) == 3 * 2 * (1024 + 64)        # a ragged last row block
+    for a, status in [((64, 200), G.GLOWQ_ERR_SHAPE), ((0, 256), G.GLOWQ_ERR_SHAPE),
+                      ((64, 160), G.GLOWQ_ERR_UNSUPPORTED), ((60, 256), G.GLOWQ_ERR_UNSUPPORTED)]:
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_mx_prepared_bytes(*a)
+        assert e.value.status == status, a
+    for a, status in [((0, 0x8000, 64, 256, 0x9000), G.GLOWQ_ERR_NULL), ((0x7000, 0, 64, 256, 0x9000), G.GLOWQ_ERR_NULL),
+                      ((0x7000, 0x8000, 64, 256, 0), G.GLOWQ_ERR_NULL), ((0x7004, 0x8000, 64, 256, 0x9000), G.GLOWQ_ERR_ALIGN),
+                      ((0x7000, 0x8001, 64, 256, 0x9000), None)]:
+        if status is None:
+            continue                                     # (scale bytes need no alignment; the call would run)
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_mx_prepare_weights(*a)
+        assert e.value.status == status, a
+    for a, status in [((0, 4, 256, G.GLOWQ_F16, 0x8000, 0x9000), G.GLOWQ_ERR_NULL),
+                      ((0x7000, 0, 256, G.GLOWQ_F16, 0x8000, 0x9000), G.GLOWQ_ERR_SHAPE),
+                      ((0x7000, 4, 250, G.GLOWQ_F16, 0x8000, 0x9000), G.GLOWQ_ERR_SHAPE),
+                      ((0x7000, 4, 256, G.GLOWQ_F32, 0x8000, 0x9000), G.GLOWQ_ERR_DTYPE),
+                      ((0x7000, 4, 256, G.GLOWQ_F16, 0x8004, 0x9000), G.GLOWQ_ERR_ALIGN)]:
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_mx_quantize_activations(*a)
+        assert e.value.status == status, a
+    u = _unit(group_size=0, T=16)                        # the group size plays no part here
+    nb = G.glowq_mx_workspace_bytes(u)
+    assert nb % 256 == 0 and nb >= 16 * 256 + 16 * 8
+    for kw, args, status in [(dict(T=17), (0xC000, 1 << 20), G.GLOWQ_ERR_UNSUPPORTED),
+                             (dict(), (0, nb), G.GLOWQ_ERR_WORKSPACE), (dict(), (0xC000, nb - 1), G.GLOWQ_ERR_WORKSPACE),
+                             (dict(), (0xC010, nb), G.GLOWQ_ERR_ALIGN), (dict(B=0), (0xC000, nb), G.GLOWQ_ERR_NULL),
+                             (dict(r=12), (0xC000, nb), G.GLOWQ_ERR_UNSUPPORTED)]:
+        with pytest.raises(G.GlowqError) as e:
+            G.glowq_mx_group_forward(_unit(group_size=0, **{"T": 16, **kw}), 1, *args)
+        assert e.value.status == status, (kw, args)
