@@ -163,9 +163,14 @@ __global__ void __launch_bounds__(MX_FRONT_THREADS) k_mx_front(MxFrontArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// the forward.  One workgroup (4 waves) per 16-row block of one module; wave w takes the
-// 128-channel tiles w, w + 4, ... and the 32-rank steps w, w + 4, ... of the correction; the
-// four partial tiles meet in LDS and wave 0 stores.
+// the forward.  One workgroup (4 waves) per RB consecutive 16-row blocks of one module (one
+// for up to four tokens; three beyond, so that an activation tile in registers serves three
+// weight tiles); wave w takes the 128-channel tiles w, w + 4, ... and the correction step of
+// ranks 32 w ..; the four partial tiles of a row block meet in LDS and wave q stores block q.
+// Measured no faster: sixteen waves per workgroup; a walk over the tiles that starts at
+// another place in every workgroup.  Measured much slower (24 us instead of 15 at one token):
+// letting the projection workgroup that finishes last add the slices into R behind a
+// device-scope fence, so that the correction step reads R instead of sixteen partial sums.
 // ---------------------------------------------------------------------------------------
 struct MxModule {
   const uint32_t* codes;     // prepared codes region
@@ -187,27 +192,40 @@ struct MxArgs {
   int out_f32;
 };
 
-template <int ACT>
+template <int ACT, int RB>
 __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
-  __shared__ float part[4][64][4];
+  __shared__ float part[4][RB][64][4];
   int mi = 0;
 #pragma unroll
   for (int i = 1; i < GLOWQ_MAX_MODULES; ++i)
     if (i < a.n_modules && (int)blockIdx.x >= a.mod[i].first_block) mi = i;
   const MxModule& m = a.mod[mi];
-  const int rb = (int)blockIdx.x - m.first_block;
+  const int rb0 = ((int)blockIdx.x - m.first_block) * RB;          // first of this workgroup's row blocks
+  const int n_rb = (m.d_out + 15) / 16;
   const int w = threadIdx.x >> 6, l = threadIdx.x & 63, i = l & 15, g = l >> 4;
   const int ktiles = a.d_in / 128;
   const bool tok = i < a.T;
-  float4_t acc = {0.f, 0.f, 0.f, 0.f};
-  const u32x4_t* wc = (const u32x4_t*)m.codes + ((long long)rb * ktiles) * 64 + l;
-  const uint8_t* ws = m.scales + ((long long)rb * ktiles) * 64 + l;
+  float4_t acc[RB];
+  const u32x4_t* wc[RB];
+  const uint8_t* ws[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) {
+    acc[q] = float4_t{0.f, 0.f, 0.f, 0.f};
+    const int rb = min(rb0 + q, n_rb - 1);                         // (a row block past the end repeats the last; not stored)
+    wc[q] = (const u32x4_t*)m.codes + ((long long)rb * ktiles) * 64 + l;
+    ws[q] = m.scales + ((long long)rb * ktiles) * 64 + l;
+  }
   const uint8_t* xc = a.xcodes + (long long)(tok ? i : 0) * a.d_in + 16 * g;
   const uint8_t* xs = a.xscales + (long long)(tok ? i : 0) * (a.d_in / 32) + g;
 #pragma unroll 8
   for (int kt = w; kt < ktiles; kt += 4) {
-    const u32x4_t bw = wc[(long long)kt * 64];
-    const int sb = ws[(long long)kt * 64];
+    u32x4_t bw[RB];
+    int sb[RB];
+#pragma unroll
+    for (int q = 0; q < RB; ++q) {
+      bw[q] = wc[q][(long long)kt * 64];
+      sb[q] = ws[q][(long long)kt * 64];
+    }
     u32x4_t a0 = {0, 0, 0, 0}, a1 = {0, 0, 0, 0};
     int sa = 127;
     if (tok) {
@@ -216,43 +234,51 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
       sa = xs[4 * kt];
     }
     const v8i_t A = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
-    const v8i_t B = {(int)bw[0], (int)bw[1], (int)bw[2], (int)bw[3], 0, 0, 0, 0};
-    acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B, acc, 0, 4, 0, sa, 0, sb);
+#pragma unroll
+    for (int q = 0; q < RB; ++q) {
+      const v8i_t B = {(int)bw[q][0], (int)bw[q][1], (int)bw[q][2], (int)bw[q][3], 0, 0, 0, 0};
+      acc[q] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B, acc[q], 0, 4, 0, sa, 0, sb[q]);
+    }
   }
   // the wave's correction step (ranks 32 w + 8 g .. + 8; r <= 128, so a wave has at most one):
   // R is the sum of the projection's slices, in slice order, rounded to the activation type
   // (token rows as A, weight rows as B)
   if (a.Rpart != nullptr && 32 * w < a.r) {
-    u32x4_t ra = {0, 0, 0, 0}, rbv = {0, 0, 0, 0};
+    u32x4_t ra = {0, 0, 0, 0};
     const int j0 = 32 * w + 8 * g;
-    if (j0 < a.r) {
-      const int row = rb * 16 + i;
-      if (row < m.d_out) rbv = *(const u32x4_t*)(m.A + (long long)row * a.r + j0);
-      if (tok) {
-        float rs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (j0 < a.r && tok) {
+      float rs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
-        for (int kz = 0; kz < a.ks; ++kz) {
-          const float4_t* p = (const float4_t*)(a.Rpart + ((long long)kz * 16 + i) * a.r + j0);
-          const float4_t p0 = p[0], p1 = p[1];
+      for (int kz = 0; kz < a.ks; ++kz) {
+        const float4_t* p = (const float4_t*)(a.Rpart + ((long long)kz * 16 + i) * a.r + j0);
+        const float4_t p0 = p[0], p1 = p[1];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { rs[e] += p0[e]; rs[4 + e] += p1[e]; }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          ra[e] = (uint32_t)to_act16<ACT>(rs[2 * e]) | ((uint32_t)to_act16<ACT>(rs[2 * e + 1]) << 16);
+        for (int e = 0; e < 4; ++e) { rs[e] += p0[e]; rs[4 + e] += p1[e]; }
       }
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        ra[e] = (uint32_t)to_act16<ACT>(rs[2 * e]) | ((uint32_t)to_act16<ACT>(rs[2 * e + 1]) << 16);
     }
-    acc = mfma16<ACT>(ra, rbv, acc);
+#pragma unroll
+    for (int q = 0; q < RB; ++q) {
+      u32x4_t rbv = {0, 0, 0, 0};
+      const int row = (rb0 + q) * 16 + i;
+      if (j0 < a.r && row < m.d_out) rbv = *(const u32x4_t*)(m.A + (long long)row * a.r + j0);
+      acc[q] = mfma16<ACT>(ra, rbv, acc[q]);
+    }
   }
 #pragma unroll
-  for (int v = 0; v < 4; ++v) part[w][l][v] = acc[v];
+  for (int q = 0; q < RB; ++q)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) part[w][q][l][v] = acc[q][v];
   __syncthreads();
-  if (w != 0) return;
-  const int row = rb * 16 + i;
+  // wave q stores row block q
+  if (w >= RB) return;
+  const int row = (rb0 + w) * 16 + i;
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     const int t = 4 * g + v;
-    const float y = ((part[0][l][v] + part[1][l][v]) + part[2][l][v]) + part[3][l][v];
+    const float y = ((part[0][w][l][v] + part[1][w][l][v]) + part[2][w][l][v]) + part[3][w][l][v];
     if (t < a.T && row < m.d_out) {
       if (a.out_f32) ((float*)m.Y)[(long long)t * m.ldy + row] = y;
       else ((uint16_t*)m.Y)[(long long)t * m.ldy + row] = to_act16<ACT>(y);
@@ -319,6 +345,7 @@ hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace,
   else k_mx_front<ACT_BF16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
   MxArgs a;
   a.n_modules = u.n_modules;
+  const int RB = u.T <= 4 ? 1 : 3;
   int blocks = 0;
   for (int i = 0; i < u.n_modules; ++i) {
     const glowq_module& m = u.modules[i];
@@ -330,7 +357,7 @@ hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace,
     a.mod[i].d_out = m.d_out;
     a.mod[i].ldy = m.ldy;
     a.mod[i].first_block = blocks;
-    blocks += (m.d_out + 15) / 16;
+    blocks += ((m.d_out + 15) / 16 + RB - 1) / RB;
   }
   a.xcodes = xcodes;
   a.xscales = xscales;
@@ -340,8 +367,11 @@ hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace,
   a.d_in = u.d_in;
   a.r = u.r;
   a.out_f32 = u.out_dtype == GLOWQ_F32;
-  if (u.act_dtype == GLOWQ_F16) k_mx_decode<ACT_F16><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
-  else k_mx_decode<ACT_BF16><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
+  dim3 grid((unsigned)blocks), block(256);
+  if (f16 && RB == 1) k_mx_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a);
+  else if (f16) k_mx_decode<ACT_F16, 3><<<grid, block, 0, st>>>(a);
+  else if (RB == 1) k_mx_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a);
+  else k_mx_decode<ACT_BF16, 3><<<grid, block, 0, st>>>(a);
   return hipGetLastError();
 }
 

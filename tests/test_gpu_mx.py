@@ -145,6 +145,19 @@ def test_full_size_group():
             assert rel_err(g, y) <= TOL
 
 
+def test_calls_in_a_row_through_one_workspace():
+    # nothing of a call survives in the workspace: 200 calls through one workspace, the
+    # output of the last equal to the first one's bits
+    shape = UnitShape("g", 512, (136, 72))
+    u = make_unit(shape, 16, 40, "f16", seed=15)
+    du = MxDeviceUnit(u)
+    first = du.forward(True)
+    for it in range(200):
+        G.glowq_mx_group_forward(du.desc, 1, du.ws.data_ptr(), du.ws_bytes, stream())
+    got = du.forward(True)
+    assert all(np.array_equal(a, b) for a, b in zip(first, got))
+
+
 def test_more_than_16_tokens_is_refused():
     shape = UnitShape("s", 256, (64,))
     u = make_unit(shape, 17, 8, "f16")
