@@ -106,12 +106,12 @@ __global__ void __launch_bounds__(256) k_mx_quantize_x(const uint16_t* __restric
   mx_quantize_block<ACT>(X, T, d_in, codes, scales, (int)(blockIdx.x * blockDim.x + threadIdx.x));
 }
 
-// First launch of the forward (workgroups of 16 waves): the leading `ks` workgroups each take
-// a slice of `kslice` channels (a multiple of 256; at most 16 slices) of the shared projection R = X B^T and leave fp32 partial sums
-// Rpart[slice][16][r]; the others quantise the activations.  Nothing waits inside.  In a
-// projection workgroup wave w owns the 16-rank block w % nbp and the part w / nbp of the
-// slice's channels (nbp = rank blocks rounded up to a power of two), so that every load of a
-// wave is in flight at once; the parts meet in LDS.
+// First launch of the forward (workgroups of 16 waves).  The leading workgroups compute the
+// shared projection R = X B^T: workgroup (slice kz, rank block nb) takes `kslice` channels
+// (a multiple of 512; at most 4 slices) of 16 ranks, its sixteen waves a sixteenth of the
+// slice each (every load of a wave in flight at once), the parts meet in LDS and leave fp32
+// partial sums Rpart[slice][16][r].  The other workgroups quantise the activations.  Nothing
+// waits inside.
 struct MxFrontArgs {
   const uint16_t* X;
   const uint16_t* B;         // act dtype [r][d_in], or NULL when not restored
@@ -125,24 +125,23 @@ constexpr int MX_FRONT_THREADS = 1024;
 template <int ACT>
 __global__ void __launch_bounds__(MX_FRONT_THREADS) k_mx_front(MxFrontArgs a) {
   __shared__ float part[16][64][4];
-  const int n_proj = a.B ? a.ks : 0;
+  const int nbs = (a.r + 15) >> 4;
+  const int n_proj = a.B ? a.ks * nbs : 0;
   if ((int)blockIdx.x >= n_proj) {
     mx_quantize_block<ACT>(a.X, a.T, a.d_in, a.xcodes, a.xscales,
                            (int)((blockIdx.x - n_proj) * MX_FRONT_THREADS + threadIdx.x));
     return;
   }
-  const int kz = blockIdx.x, w = threadIdx.x >> 6, l = threadIdx.x & 63, i = l & 15, g = l >> 4;
-  const int nbs = (a.r + 15) >> 4;
-  const int nbp = nbs <= 1 ? 1 : nbs <= 2 ? 2 : nbs <= 4 ? 4 : 8;
-  const int kparts = min(16 / nbp, 8), per = a.kslice / kparts;       // (per: a multiple of 32)
-  const int nb = w % nbp, kp = w / nbp;
-  const int kbeg = kz * a.kslice + kp * per, kend = kp < kparts ? min(a.d_in, kbeg + per) : kbeg;
+  const int kz = (int)blockIdx.x % a.ks, nb = (int)blockIdx.x / a.ks;
+  const int w = threadIdx.x >> 6, l = threadIdx.x & 63, i = l & 15, g = l >> 4;
+  const int per = a.kslice / 16;                                       // (a multiple of 32)
+  const int kbeg = min(a.d_in, kz * a.kslice + w * per), kend = min(a.d_in, kbeg + per);
   const int rank = 16 * nb + i;
   const bool tok = i < a.T, live = rank < a.r;
   float4_t acc = {0.f, 0.f, 0.f, 0.f};
   const uint16_t* xp = a.X + (long long)(tok ? i : 0) * a.d_in + 8 * g;
   const uint16_t* bp = a.B + (long long)(live ? rank : 0) * a.d_in + 8 * g;
-#pragma unroll 16
+#pragma unroll 8
   for (int k0 = kbeg; k0 < kend; k0 += 32) {
     u32x4_t xa = {0, 0, 0, 0}, bb = {0, 0, 0, 0};
     if (tok) xa = *(const u32x4_t*)(xp + k0);
@@ -152,11 +151,12 @@ __global__ void __launch_bounds__(MX_FRONT_THREADS) k_mx_front(MxFrontArgs a) {
 #pragma unroll
   for (int v = 0; v < 4; ++v) part[w][l][v] = acc[v];
   __syncthreads();
-  if (kp != 0) return;
+  if (w != 0) return;
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     float sum = 0.f;
-    for (int q = 0; q < kparts; ++q) sum += part[q * nbp + nb][l][v];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) sum += part[q][l][v];
     const int t = 4 * g + v;
     if (t < a.T && live) a.Rpart[((long long)kz * 16 + t) * a.r + rank] = sum;
   }
@@ -168,7 +168,8 @@ __global__ void __launch_bounds__(MX_FRONT_THREADS) k_mx_front(MxFrontArgs a) {
 // weight tiles); wave w takes the 128-channel tiles w, w + 4, ... and the correction step of
 // ranks 32 w ..; the four partial tiles of a row block meet in LDS and wave q stores block q.
 // Measured no faster: sixteen waves per workgroup; a walk over the tiles that starts at
-// another place in every workgroup.  Measured much slower (24 us instead of 15 at one token):
+// another place in every workgroup.  Measured slower: sixteen slices of the projection instead
+// of four (15.0 instead of 13.4 us at one token).  Measured much slower (24 us):
 // letting the projection workgroup that finishes last add the slices into R behind a
 // device-scope fence, so that the correction step reads R instead of sixteen partial sums.
 // ---------------------------------------------------------------------------------------
@@ -315,8 +316,8 @@ static size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 MxWorkspace plan_mx_workspace(const glowq_unit& u) {
   MxWorkspace w;
-  // K slices of the projection: at most 16, a multiple of 256 channels each
-  w.kslice = ((u.d_in + 15) / 16 + 255) / 256 * 256;
+  // K slices of the projection: at most 4, a multiple of 512 channels each
+  w.kslice = ((u.d_in + 3) / 4 + 511) / 512 * 512;
   w.ks = (u.d_in + w.kslice - 1) / w.kslice;
   w.off_rpart = 0;
   w.off_xcodes = up256((size_t)w.ks * 16 * (u.r > 0 ? u.r : 0) * 4);
@@ -340,7 +341,7 @@ hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace,
   fa.xscales = xscales;
   fa.T = u.T; fa.d_in = u.d_in; fa.r = u.r; fa.ks = w.ks; fa.kslice = w.kslice;
   const int qblocks = (u.T * (u.d_in / 32) * 8 + MX_FRONT_THREADS - 1) / MX_FRONT_THREADS;
-  dim3 fgrid((unsigned)(qblocks + (corrected ? w.ks : 0)));
+  dim3 fgrid((unsigned)(qblocks + (corrected ? w.ks * ((u.r + 15) / 16) : 0)));
   if (f16) k_mx_front<ACT_F16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
   else k_mx_front<ACT_BF16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
   MxArgs a;
