@@ -289,7 +289,7 @@ glowq_status glowq_factorize_unit(const glowq_unit* u, const float* const* W_mod
 
 /* ---- microscaling variant: MXFP4 weights, MXFP8 activations (W4A8) ------------
  * The same forward (Sec. 3.3, Eqs. 8-9) on the floating-point-like datatypes of the paper's
- * datatype appendix and the W4A8 rows of its main results, for up to 16 tokens:
+ * datatype appendix and the W4A8 rows of its main results:
  *   Y_i = Xq dequant(W_mx,i)^T + R A_i^T,   R = X B^T,
  * Xq the activations quantised to MXFP8 (E4M3) inside the call, W_mx,i MXFP4 (E2M1) weights,
  * the correction from the 16-bit X, B and A_i exactly as in the W4A16 calls.  Formats of the
@@ -305,9 +305,11 @@ glowq_status glowq_factorize_unit(const glowq_unit* u, const float* const* W_mod
  * glowq_mx_quantize_activations: the activation quantiser by itself; X DEVICE act dtype
  *   [T][d_in]; codes DEVICE uint8 [T][d_in] (E4M3), scales DEVICE uint8 [T][d_in/32].
  * glowq_mx_group_forward: `u` as for glowq_group_forward with modules[i].w_prepared from
- *   glowq_mx_prepare_weights (group_size is ignored); T <= 16 (more: GLOWQ_ERR_UNSUPPORTED);
- *   workspace DEVICE, 256-byte aligned, glowq_mx_workspace_bytes(u) bytes, any contents.
- *   Three or five small launches on `stream` (quantise X; R when restored; the forward). */
+ *   glowq_mx_prepare_weights (group_size is ignored); workspace DEVICE, 256-byte aligned,
+ *   glowq_mx_workspace_bytes(u) bytes (it depends on T), any contents.  Up to 16 tokens: two
+ *   launches on `stream` (activation quantiser and projection; the weight stream).  More
+ *   tokens: the activation quantiser, the stand-alone projection when restored, and a tiled
+ *   product (128 tokens x 128 rows per workgroup). */
 glowq_status glowq_mx_prepared_bytes(int32_t d_out, int32_t d_in, size_t* bytes);
 glowq_status glowq_mx_prepare_weights(const uint32_t* codes, const uint8_t* scales, int32_t d_out,
                                       int32_t d_in, void* w_prepared, void* stream);

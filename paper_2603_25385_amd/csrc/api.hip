@@ -513,9 +513,7 @@ static glowq_status validate_mx(const glowq_unit* u, bool ptrs, bool corrected) 
   glowq_unit v = *u;
   v.group_size = 128;
   glowq_status s = validate(&v, ptrs, corrected);
-  if (s != GLOWQ_OK) return s;
-  if (u->T > MX_MAX_TOKENS) return GLOWQ_ERR_UNSUPPORTED;
-  return GLOWQ_OK;
+  return s;
 }
 
 glowq_status glowq_mx_workspace_bytes(const glowq_unit* u, size_t* bytes) {

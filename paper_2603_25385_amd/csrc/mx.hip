@@ -1,4 +1,4 @@
-// Microscaling variant of the group forward for up to 16 tokens: MXFP4 weights and MXFP8
+// Microscaling variant of the group forward: MXFP4 weights and MXFP8
 // activations in the main product, on the block-scaled matrix instruction of gfx950
 // (v_mfma_scale_f32_16x16x128_f8f6f4), the 16-bit low-rank correction unchanged (paper
 // Sec. 3.3, Eqs. 8-9, on the datatypes of the datatype appendix and the W4A8 rows of the
@@ -288,6 +288,161 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// more than 16 tokens: a tiled product on the same instruction.  Workgroup tile 128 tokens x
+// 128 rows, four waves as 2 x 2 with 64 x 64 each (16 accumulator tiles), K in steps of one
+// 128-channel tile through two LDS buffers: while the waves multiply step k out of one
+// buffer, the loads of step k + 1 are in flight into registers and go to the other buffer
+// behind them; one barrier per step.  The weight tile sits in LDS exactly as in memory (a
+// wave reads the 1 KiB of a row block lane after lane, no bank conflict by construction);
+// the activation tile is [token][128 bytes] with a row pitch of 144 bytes, which spreads the
+// sixteen tokens of a fragment read over all banks.  The correction (R from the stand-alone
+// projection, in the activation type) is r / 32 more 16-bit instructions per accumulator
+// tile in the epilogue.
+// ---------------------------------------------------------------------------------------
+constexpr int MXG_TOK = 128, MXG_ROWS = 128, MXG_PITCH = 144;
+
+struct MxGemmArgs {
+  MxModule mod[GLOWQ_MAX_MODULES];      // first_block: index of the module's first workgroup
+  int n_modules;
+  const uint8_t* xcodes;
+  const uint8_t* xscales;
+  const uint16_t* R16;                  // act dtype [T][r], or NULL when not restored
+  int T, d_in, r, out_f32;
+  int tok_tiles;                        // ceil(T / 128); token tiles of a row tile are neighbours in the grid
+};
+
+template <int ACT>
+__global__ void __launch_bounds__(256) k_mx_gemm(MxGemmArgs a) {
+  __shared__ __attribute__((aligned(16))) uint8_t As[2][MXG_TOK * MXG_PITCH];
+  __shared__ u32x4_t Bs[2][8 * 64];
+  __shared__ uint32_t Asc[2][MXG_TOK];          // four scale bytes per token
+  __shared__ uint32_t Bsc[2][8 * 16];           // 64 scale bytes per row block
+  int mi = 0;
+#pragma unroll
+  for (int i = 1; i < GLOWQ_MAX_MODULES; ++i)
+    if (i < a.n_modules && (int)blockIdx.x >= a.mod[i].first_block) mi = i;
+  const MxModule& m = a.mod[mi];
+  const int local = (int)blockIdx.x - m.first_block;
+  const int tt = local % a.tok_tiles, nt = local / a.tok_tiles;
+  const int tok0 = tt * MXG_TOK, rb0 = nt * 8;
+  const int n_rb = (m.d_out + 15) / 16, ktiles = a.d_in / 128;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, i = l & 15, g = l >> 4;
+  const int wm = w >> 1, wn = w & 1;
+  // what this thread stages per step: four 16-byte pieces of the activation tile, two of the
+  // weight tile, one word of scales
+  const uint8_t* asrc[4];
+  int adst[4];
+  bool alive[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int c = tid + 256 * q, tok = c >> 3, part = c & 7;
+    alive[q] = tok0 + tok < a.T;
+    asrc[q] = a.xcodes + (long long)(alive[q] ? tok0 + tok : 0) * a.d_in + 16 * part;
+    adst[q] = tok * MXG_PITCH + 16 * part;
+  }
+  const u32x4_t* bsrc[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int c = tid + 256 * q, rbi = c >> 6, ln = c & 63;
+    bsrc[q] = (const u32x4_t*)m.codes + ((long long)min(rb0 + rbi, n_rb - 1) * ktiles) * 64 + ln;
+  }
+  const bool sc_is_a = tid < 128;
+  const uint32_t* scsrc;
+  bool sc_live = true;
+  if (sc_is_a) {
+    sc_live = tok0 + tid < a.T;
+    scsrc = (const uint32_t*)(a.xscales + (long long)(sc_live ? tok0 + tid : 0) * (a.d_in / 32));
+  } else {
+    const int q = tid - 128, rbi = q >> 4;
+    scsrc = (const uint32_t*)(m.scales + ((long long)min(rb0 + rbi, n_rb - 1) * ktiles) * 64) + (q & 15);
+  }
+  u32x4_t areg[4], breg[2];
+  uint32_t screg;
+  auto fetch = [&](int kt) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) areg[q] = alive[q] ? *(const u32x4_t*)(asrc[q] + 128 * kt) : u32x4_t{0, 0, 0, 0};
+#pragma unroll
+    for (int q = 0; q < 2; ++q) breg[q] = bsrc[q][(long long)kt * 64];
+    screg = sc_is_a ? (sc_live ? scsrc[kt] : 0x7f7f7f7fu) : scsrc[(long long)kt * 16];
+  };
+  auto stage = [&](int buf) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *(u32x4_t*)(&As[buf][adst[q]]) = areg[q];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) Bs[buf][tid + 256 * q] = breg[q];
+    if (sc_is_a) Asc[buf][tid] = screg;
+    else Bsc[buf][tid - 128] = screg;
+  };
+  float4_t acc[4][4];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) acc[tb][nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+  fetch(0);
+  stage(0);
+  __syncthreads();
+  for (int kt = 0; kt < ktiles; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < ktiles) fetch(kt + 1);
+    v8i_t B[4];
+    int sb[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const int rbi = 4 * wn + nb;
+      const u32x4_t bw = Bs[buf][rbi * 64 + l];
+      B[nb] = v8i_t{(int)bw[0], (int)bw[1], (int)bw[2], (int)bw[3], 0, 0, 0, 0};
+      sb[nb] = ((const uint8_t*)Bsc[buf])[rbi * 64 + l];
+    }
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+      const int tok = 64 * wm + 16 * tb + i;
+      const u32x4_t lo = *(const u32x4_t*)(&As[buf][tok * MXG_PITCH + 16 * g]);
+      const u32x4_t hi = *(const u32x4_t*)(&As[buf][tok * MXG_PITCH + 64 + 16 * g]);
+      const int sa = ((const uint8_t*)Asc[buf])[tok * 4 + g];
+      const v8i_t A = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb)
+        acc[tb][nb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B[nb], acc[tb][nb], 0, 4, 0, sa, 0, sb[nb]);
+    }
+    if (kt + 1 < ktiles) stage(buf ^ 1);
+    __syncthreads();
+  }
+  // correction: + R A_i^T (token rows as A, weight rows as B; lane (i, g): ranks 32 s + 8 g .. + 8)
+  if (a.R16) {
+    for (int s = 0; 32 * s < a.r; ++s) {
+      const int j0 = 32 * s + 8 * g;
+      u32x4_t rb[4];
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb) {
+        const int row = (rb0 + 4 * wn + nb) * 16 + i;
+        rb[nb] = (j0 < a.r && row < m.d_out) ? *(const u32x4_t*)(m.A + (long long)row * a.r + j0) : u32x4_t{0, 0, 0, 0};
+      }
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) {
+        const int tok = tok0 + 64 * wm + 16 * tb + i;
+        const u32x4_t ra = (j0 < a.r && tok < a.T) ? *(const u32x4_t*)(a.R16 + (long long)tok * a.r + j0) : u32x4_t{0, 0, 0, 0};
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) acc[tb][nb] = mfma16<ACT>(ra, rb[nb], acc[tb][nb]);
+      }
+    }
+  }
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const int row = (rb0 + 4 * wn + nb) * 16 + i;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int tok = tok0 + 64 * wm + 16 * tb + 4 * g + v;
+        if (tok < a.T && row < m.d_out) {
+          if (a.out_f32) ((float*)m.Y)[(long long)tok * m.ldy + row] = acc[tb][nb][v];
+          else ((uint16_t*)m.Y)[(long long)tok * m.ldy + row] = to_act16<ACT>(acc[tb][nb][v]);
+        }
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
 size_t mx_prepared_bytes(int d_out, int d_in) {
@@ -316,6 +471,16 @@ static size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 MxWorkspace plan_mx_workspace(const glowq_unit& u) {
   MxWorkspace w;
+  if (u.T > MX_MAX_TOKENS) {
+    // the tiled path: the unit's ordinary slice (partial sums and R of the stand-alone
+    // projection), then the quantised activations
+    w.ks = w.kslice = 0;
+    w.off_rpart = 0;
+    w.off_xcodes = up256(plan_unit_workspace(u, nullptr).bytes);
+    w.off_xscales = w.off_xcodes + up256((size_t)u.T * u.d_in);
+    w.bytes = w.off_xscales + up256((size_t)u.T * (u.d_in / 32));
+    return w;
+  }
   // K slices of the projection: at most 4, a multiple of 512 channels each
   w.kslice = ((u.d_in + 3) / 4 + 511) / 512 * 512;
   w.ks = (u.d_in + w.kslice - 1) / w.kslice;
@@ -326,7 +491,46 @@ MxWorkspace plan_mx_workspace(const glowq_unit& u) {
   return w;
 }
 
+static hipError_t launch_mx_gemm(const glowq_unit& u, bool restore, char* workspace, hipStream_t st) {
+  const MxWorkspace w = plan_mx_workspace(u);
+  uint8_t* xcodes = (uint8_t*)(workspace + w.off_xcodes);
+  uint8_t* xscales = (uint8_t*)(workspace + w.off_xscales);
+  hipError_t err = launch_mx_quantize_x(u.X, u.T, u.d_in, u.act_dtype, xcodes, xscales, st);
+  if (err != hipSuccess) return err;
+  const bool corrected = restore && u.r > 0;
+  const UnitWorkspace uw = plan_unit_workspace(u, workspace);
+  if (corrected) {
+    err = launch_proj(u, uw, nullptr, true, st);          // R = X B^T in the activation type
+    if (err != hipSuccess) return err;
+  }
+  MxGemmArgs a;
+  a.n_modules = u.n_modules;
+  a.tok_tiles = (u.T + MXG_TOK - 1) / MXG_TOK;
+  int blocks = 0;
+  for (int i = 0; i < u.n_modules; ++i) {
+    const glowq_module& m = u.modules[i];
+    const long long tiles = (long long)((m.d_out + 15) / 16) * (u.d_in / 128);
+    a.mod[i].codes = (const uint32_t*)m.w_prepared;
+    a.mod[i].scales = (const uint8_t*)m.w_prepared + tiles * 1024;
+    a.mod[i].A = (const uint16_t*)m.A;
+    a.mod[i].Y = m.Y;
+    a.mod[i].d_out = m.d_out;
+    a.mod[i].ldy = m.ldy;
+    a.mod[i].first_block = blocks;
+    blocks += ((m.d_out + MXG_ROWS - 1) / MXG_ROWS) * a.tok_tiles;
+  }
+  a.xcodes = xcodes;
+  a.xscales = xscales;
+  a.R16 = corrected ? (const uint16_t*)(uw.base + uw.off_r16) : nullptr;
+  a.T = u.T; a.d_in = u.d_in; a.r = u.r;
+  a.out_f32 = u.out_dtype == GLOWQ_F32;
+  if (u.act_dtype == GLOWQ_F16) k_mx_gemm<ACT_F16><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
+  else k_mx_gemm<ACT_BF16><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
+  return hipGetLastError();
+}
+
 hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace, hipStream_t st) {
+  if (u.T > MX_MAX_TOKENS) return launch_mx_gemm(u, restore, workspace, st);
   const MxWorkspace w = plan_mx_workspace(u);
   uint8_t* xcodes = (uint8_t*)(workspace + w.off_xcodes);
   uint8_t* xscales = (uint8_t*)(workspace + w.off_xscales);

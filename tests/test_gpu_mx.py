@@ -158,9 +158,49 @@ def test_calls_in_a_row_through_one_workspace():
     assert all(np.array_equal(a, b) for a, b in zip(first, got))
 
 
-def test_more_than_16_tokens_is_refused():
-    shape = UnitShape("s", 256, (64,))
-    u = make_unit(shape, 17, 8, "f16")
-    with pytest.raises(G.GlowqError) as e:
-        MxDeviceUnit(u)
-    assert e.value.status == G.GLOWQ_ERR_UNSUPPORTED
+@pytest.mark.parametrize("act", ["f16", "bf16"])
+@pytest.mark.parametrize("T", [17, 48, 130, 300])
+def test_tiled_path(act, T):
+    # more than 16 tokens: the tiled product (token tiles of 128 with a ragged last one, row
+    # tiles of 128 with ragged modules, three K tiles), restored and not
+    shape = UnitShape("g", 384, (40, 264, 136))
+    u = make_unit(shape, T, 24, act, seed=16)
+    du = MxDeviceUnit(u)
+    for restore in (True, False):
+        got = du.forward(restore)
+        ref = MX.mx_group_forward(u, restore)
+        for g, y in zip(got, ref):
+            assert rel_err(g, y) <= TOL
+
+
+@pytest.mark.parametrize("r", [0, 8, 128])
+def test_tiled_path_ranks_and_16_bit_output(r):
+    shape = UnitShape("s", 1024, (200,))
+    u = make_unit(shape, 70, r, "bf16", seed=17)
+    du = MxDeviceUnit(u, out="act")
+    got = du.forward(True)[0]
+    ref = MX.mx_group_forward(u, True)[0]
+    assert rel_err(got, ref) <= TOL + ULP["bf16"]
+
+
+def test_tiled_path_exact_on_small_integers():
+    rng = np.random.default_rng(18)
+    d, T = 256, 150
+    Wg = rng.choice([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], size=(144, d)) * rng.choice([-1, 1], size=(144, d))
+    Xg = rng.integers(-8, 9, size=(T, d)).astype(np.float64)
+    Xg[:, ::32] = 8.0
+    Wg[:, ::32] = 6.0
+    u = MX.build_unit_mx([Wg], O.f64_to_bits(Xg, "f16"), 0, "f16")
+    got = MxDeviceUnit(u).forward(False)[0]
+    assert np.array_equal(got, Xg @ Wg.T)
+
+
+def test_full_size_prefill():
+    # 512 tokens on the q/k/v group of the 3B shapes (d = 3072, rows 3072 + 1024 + 1024), r = 64
+    shape = UnitShape("qkv", 3072, (3072, 1024, 1024))
+    u = make_unit(shape, 512, 64, "bf16", seed=19)
+    du = MxDeviceUnit(u)
+    got = du.forward(True)
+    ref = MX.mx_group_forward(u, True)
+    for g, y in zip(got, ref):
+        assert rel_err(g, y) <= TOL
