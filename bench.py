@@ -55,6 +55,9 @@ WORKLOADS = {
     "stream24": (0, 0, "stream"),
     "mfma_f16": (0, 0, "mfma_probe"),
     "mfma_bf16": (0, 0, "mfma_probe"),
+    "mfma_fp8fp4": (0, 0, "mfma_probe"),
+    "mfma_fp4fp4": (0, 0, "mfma_probe"),
+    "mfma_fp8fp4_32": (0, 0, "mfma_probe"),
     # offline side of GlowQ-S: the importance scores of the Llama-2-7B-shaped QKV unit
     "cfg2_scores": (2, 0, "scores"),
     # offline factorisation (Alg. 1) of a q/k/v group with d = 3072, r = 64, p = 16, q = 2:
@@ -486,7 +489,8 @@ def main() -> int:
         if bound == "stream":
             return stream_ceiling(torch, args)
         if bound == "mfma_probe":
-            return mfma_ceiling(torch, args, args.workload.endswith("bf16"))
+            kind = {"mfma_f16": 0, "mfma_bf16": 1, "mfma_fp8fp4": 2, "mfma_fp4fp4": 3, "mfma_fp8fp4_32": 4}[args.workload]
+            return mfma_ceiling(torch, args, kind)
         if bound == "scores":
             return importance_scores(torch, args)
         if bound == "factorize":
@@ -921,11 +925,14 @@ def mfma_ceiling(torch, args, bf16):
         rows.append({"waves_per_simd": wps, "TFLOPs": flops[0] / (med * 1e-3) / 1e12,
                      "ms_per_step_median": med, "ms_per_step_min": min(ms)})
     tf = max(r["TFLOPs"] for r in rows)
-    print(json.dumps({"metric": f"register-resident 16x16x32 {'bf16' if bf16 else 'f16'} matrix loop "
-                                "(measured ceiling)",
+    name = ["16x16x32 f16", "16x16x32 bf16", "block-scaled 16x16x128 fp8 x fp4", "block-scaled 16x16x128 fp4 x fp4",
+            "block-scaled 32x32x64 fp8 x fp4"][bf16]
+    peak = [MFMA_PEAK_TFLOPS, MFMA_PEAK_TFLOPS, FP8_PEAK_TFLOPS, 2 * FP8_PEAK_TFLOPS, FP8_PEAK_TFLOPS][bf16]
+    per_clock = [1024, 1024, 2048, 4096, 2048][bf16]        # flops per SIMD and clock at the published peak
+    print(json.dumps({"metric": f"register-resident {name} matrix loop (measured ceiling)",
                       "value": tf, "unit": "TFLOP/s", "steps": steps, "by_occupancy": rows,
-                      "frac_of_mfma_peak": tf / MFMA_PEAK_TFLOPS,
-                      "implied_clock_GHz": tf * 1e12 / (256 * 4 * 1024) / 1e9}))
+                      "frac_of_mfma_peak": tf / peak, "published_peak_TFLOPs": peak,
+                      "implied_clock_GHz": tf * 1e12 / (256 * 4 * per_clock) / 1e9}))
     return 0
 
 

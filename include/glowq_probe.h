@@ -21,8 +21,10 @@ int32_t glowq_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, v
 
 /* One launch of 256 x waves_per_simd workgroups of 4 waves (waves_per_simd in 1..8: that
  * many waves on every SIMD of the chip) in which every wave issues iters x 8 independent
- * 16x16x32 matrix-core instructions (binary16, or bfloat16 if bf16 != 0) on operands that
- * stay in registers.  *flops (HOST) receives the floating-point operations of the
+ * 16x16x32 matrix-core instructions (binary16, or bfloat16 if bf16 == 1) on operands that
+ * stay in registers; bf16 == 2: the block-scaled 16x16x128 instruction on fp8 x fp4 operands,
+ * bf16 == 3: on fp4 x fp4 operands; bf16 == 4: the 32x32x64 shape of it on fp8 x fp4 operands
+ * (four chains).  *flops (HOST) receives the floating-point operations of the
  * launch.  sink: DEVICE, one float, never written in practice. */
 int32_t glowq_probe_mfma(int32_t iters, int32_t bf16, int32_t waves_per_simd, float* sink,
                          double* flops, void* stream);

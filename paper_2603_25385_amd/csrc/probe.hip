@@ -64,6 +64,60 @@ __global__ void __launch_bounds__(MFMA_WAVES * 64) k_probe_mfma(int iters, float
   if (s == -1.0f) sink[0] = s;
 }
 
+// the same with the block-scaled 16x16x128 instruction: fp8 x fp4 operands (FP4_BOTH false)
+// or fp4 x fp4 (true), unit scales
+typedef int pv8i __attribute__((ext_vector_type(8)));
+template <bool FP4_BOTH>
+__global__ void __launch_bounds__(MFMA_WAVES * 64) k_probe_mfma_scaled(int iters, float* sink) {
+  const pv8i a8 = {0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838};   // E4M3 ones
+  const pu32x4 a4 = {0x22222222u, 0x22222222u, 0x22222222u, 0x22222222u};                                            // E2M1 ones
+  const pu32x4 b = {0x22222222u, 0x22222222u ^ (threadIdx.x & 1u), 0x22222222u, 0x22222222u};
+  const int sc = 127;
+  pfloat4 acc[MFMA_CHAINS];
+#pragma unroll
+  for (int c = 0; c < MFMA_CHAINS; ++c) acc[c] = pfloat4{0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int c = 0; c < MFMA_CHAINS; ++c) {
+      if constexpr (FP4_BOTH)
+        asm volatile("v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %3, %3 op_sel_hi:[0,0,0] cbsz:4 blgp:4"
+                     : "+v"(acc[c]) : "v"(a4), "v"(b), "v"(sc));
+      else
+        asm volatile("v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %3, %3 op_sel_hi:[0,0,0] blgp:4"
+                     : "+v"(acc[c]) : "v"(a8), "v"(b), "v"(sc));
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < MFMA_CHAINS; ++c) s += acc[c][0] + acc[c][1] + acc[c][2] + acc[c][3];
+  if (s == -1.0f) sink[0] = s;
+}
+
+// and with the 32x32x64 shape of the same instruction (fp8 x fp4), four chains of 16 registers
+typedef float pfloat16 __attribute__((ext_vector_type(16)));
+__global__ void __launch_bounds__(MFMA_WAVES * 64) k_probe_mfma_scaled32(int iters, float* sink) {
+  const pv8i a8 = {0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838, 0x38383838};
+  const pu32x4 b = {0x22222222u, 0x22222222u ^ (threadIdx.x & 1u), 0x22222222u, 0x22222222u};
+  const int sc = 127;
+  pfloat16 acc[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %3 op_sel_hi:[0,0,0] blgp:4"
+                   : "+v"(acc[c]) : "v"(a8), "v"(b), "v"(sc));
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[c][e];
+  if (s == -1.0f) sink[0] = s;
+}
+
 }  // namespace glowq
 
 using namespace glowq;
@@ -84,9 +138,18 @@ int32_t glowq_probe_mfma(int32_t iters, int32_t bf16, int32_t waves_per_simd, fl
   if (!sink || !flops) return -1;
   if (iters < 1 || iters > (1 << 24) || waves_per_simd < 1 || waves_per_simd > 8) return -2;
   const int wgs = MFMA_CUS * waves_per_simd;
-  if (bf16) k_probe_mfma<true><<<dim3(wgs), dim3(MFMA_WAVES * 64), 0, (hipStream_t)stream>>>(iters, sink);
-  else k_probe_mfma<false><<<dim3(wgs), dim3(MFMA_WAVES * 64), 0, (hipStream_t)stream>>>(iters, sink);
-  *flops = (double)wgs * MFMA_WAVES * (double)iters * MFMA_CHAINS * (2.0 * 16 * 16 * 32);
+  dim3 grid(wgs), block(MFMA_WAVES * 64);
+  int depth = 32;
+  if (bf16 == 2) { k_probe_mfma_scaled<false><<<grid, block, 0, (hipStream_t)stream>>>(iters, sink); depth = 128; }
+  else if (bf16 == 3) { k_probe_mfma_scaled<true><<<grid, block, 0, (hipStream_t)stream>>>(iters, sink); depth = 128; }
+  else if (bf16 == 4) {      // (four chains of 32x32x64: the same operations per loop pass as eight of 16x16x128)
+    k_probe_mfma_scaled32<<<grid, block, 0, (hipStream_t)stream>>>(iters, sink);
+    *flops = (double)wgs * MFMA_WAVES * (double)iters * 4 * (2.0 * 32 * 32 * 64);
+    return hipGetLastError() == hipSuccess ? 0 : -7;
+  }
+  else if (bf16) k_probe_mfma<true><<<grid, block, 0, (hipStream_t)stream>>>(iters, sink);
+  else k_probe_mfma<false><<<grid, block, 0, (hipStream_t)stream>>>(iters, sink);
+  *flops = (double)wgs * MFMA_WAVES * (double)iters * MFMA_CHAINS * (2.0 * 16 * 16 * depth);
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
