@@ -160,6 +160,53 @@ static void abi_checks(void) {
     CHECK(glowq_layerwise_forward(&lw, 1, Bs, (void*)0x9000, all, NULL) == GLOWQ_ERR_NULL);
     CHECK(glowq_layerwise_forward(&lw, 1, NULL, (void*)0x9000, all, NULL) == GLOWQ_ERR_NULL);
   }
+  {
+    /* the offline side and the microscaling variant: workspace planning over every size
+       class, and rejection before anything is enqueued */
+    static const int Kf[] = {128, 512, 3072, 8192};
+    for (unsigned b = 0; b < sizeof Kf / sizeof *Kf; ++b)
+      for (int r = 8; r <= GLOWQ_MAX_RANK; r += 24)
+        for (int p = 0; p <= 24; p += 8)
+          for (int nm = 1; nm <= GLOWQ_MAX_MODULES; nm += 7) {
+            glowq_unit v = make_unit(ms, 1, Kf[b], 0, 128);
+            v.n_modules = nm;
+            long long rows = 0;
+            for (int i = 0; i < nm; ++i) rows += ms[i].d_out;
+            glowq_status want = (r > rows || r + p > Kf[b]) ? GLOWQ_ERR_SHAPE : GLOWQ_OK;
+            CHECK(glowq_factorize_workspace_bytes(&v, r, p, &bytes) == want);
+            if (want == GLOWQ_OK) CHECK(bytes % 256 == 0 && bytes >= (size_t)rows * Kf[b] * 8);
+          }
+    const float* Wp[1] = {(const float*)0x7000};
+    void* Ap[1] = {(void*)0xD000};
+    glowq_unit f = make_unit(&m, 1, 256, 0, 128);
+    CHECK(glowq_factorize_workspace_bytes(&f, 16, 8, &bytes) == GLOWQ_OK);
+    CHECK(glowq_factorize_unit(&f, Wp, NULL, 16, 8, 2, (const double*)0xB000, (void*)0xC000, bytes - 1, Ap,
+                               (void*)0xE000, NULL, NULL) == GLOWQ_ERR_WORKSPACE);
+    CHECK(glowq_factorize_unit(&f, Wp, NULL, 16, 8, 9, (const double*)0xB000, (void*)0xC000, bytes, Ap,
+                               (void*)0xE000, NULL, NULL) == GLOWQ_ERR_UNSUPPORTED);
+    CHECK(glowq_factorize_unit(&f, Wp, NULL, 16, 8, 2, NULL, (void*)0xC000, bytes, Ap, (void*)0xE000, NULL,
+                               NULL) == GLOWQ_ERR_NULL);
+    CHECK(glowq_quantize_rtn(NULL, 64, 256, 128, (uint32_t*)0x8000, (uint16_t*)0x9000, (uint16_t*)0xA000, NULL) ==
+          GLOWQ_ERR_NULL);
+    CHECK(glowq_quantize_rtn((const float*)0x7000, 64, 200, 128, (uint32_t*)0x8000, (uint16_t*)0x9000,
+                             (uint16_t*)0xA000, NULL) == GLOWQ_ERR_SHAPE);
+    for (unsigned a = 0; a < sizeof Ts / sizeof *Ts; ++a)
+      for (unsigned b = 0; b < sizeof Ks / sizeof *Ks; ++b)
+        for (int r = 0; r <= GLOWQ_MAX_RANK; r += 64) {
+          glowq_unit v = make_unit(ms, Ts[a], Ks[b], r, 0);
+          v.n_modules = GLOWQ_MAX_MODULES;
+          CHECK(glowq_mx_workspace_bytes(&v, &bytes) == GLOWQ_OK && bytes % 256 == 0);
+          CHECK(bytes >= (size_t)(Ts[a] > 16 ? Ts[a] : 16) * Ks[b]);
+        }
+    glowq_unit x = make_unit(&m, 4, 256, 16, 0);
+    CHECK(glowq_mx_workspace_bytes(&x, &bytes) == GLOWQ_OK);
+    CHECK(glowq_mx_group_forward(&x, 1, (void*)0xC000, bytes - 1, NULL) == GLOWQ_ERR_WORKSPACE);
+    CHECK(glowq_mx_group_forward(&x, 1, (void*)0xC010, bytes, NULL) == GLOWQ_ERR_ALIGN);
+    CHECK(glowq_mx_prepared_bytes(40, 256, &bytes) == GLOWQ_OK && bytes == 3 * 2 * 1088);
+    CHECK(glowq_mx_prepare_weights(NULL, NULL, 64, 256, NULL, NULL) == GLOWQ_ERR_NULL);
+    CHECK(glowq_mx_quantize_activations((void*)0x7000, 4, 250, GLOWQ_F16, (uint8_t*)0x8000, (uint8_t*)0x9000,
+                                        NULL) == GLOWQ_ERR_SHAPE);
+  }
   CHECK(glowq_prepared_bytes(40, 128, 128, &bytes) == GLOWQ_OK && bytes == 3 * 272 * 4);
   CHECK(glowq_prepared_bytes(40, 100, 128, &bytes) == GLOWQ_ERR_SHAPE);
   CHECK(glowq_prepare_weights(NULL, NULL, NULL, 64, 256, 64, NULL, NULL) == GLOWQ_ERR_NULL);

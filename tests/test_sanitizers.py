@@ -35,7 +35,8 @@ def test_abi_host_layer_under_asan_ubsan(tmp_path):
     host_san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
                 "-Xarch_host", "-fno-sanitize-recover=all"]
     objs, procs = [], []
-    for src in ["api.hip", "prepare.hip", "proj.hip", "decode.hip", "prefill.hip", "probe.hip"]:
+    for src in ["api.hip", "prepare.hip", "proj.hip", "decode.hip", "prefill.hip", "probe.hip",
+                "factorize.hip", "mx.hip"]:
         obj = str(tmp_path / (src + ".o"))
         extra = ["-mllvm", "-amdgpu-mfma-vgpr-form"] if src == "decode.hip" else []
         procs.append(subprocess.Popen(
