@@ -679,6 +679,10 @@ def mx_workload(torch, args, name):
         roof = {"bound": "mfma", "achieved": tfs, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": tfs / FP8_PEAK_TFLOPS, "traffic": None,
                 "note": "fp8 x fp4 on the block-scaled instruction runs at the fp8 rate"}
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{name}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            roof["traffic"] = json.load(f).get("hbm_bytes_per_step")
     out = {"metric": METRIC + " (microscaling variant: MXFP4 weights, MXFP8 activations)",
            "value": gbs if decode else tfs,
            "unit": "GB/s" if decode else "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": med,
