@@ -50,9 +50,10 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   // enough slices to fill the chip
   // (a handful of tokens: one wave per (rank, part) and parts of about 2048 channels, so
   // that a wave has all its loads in flight at once, at most four parts; up to 32 tokens:
-  // eight slices, one workgroup each; the consumers add the parts themselves)
+  // four slices, two workgroups each (one per half of the ranks); the consumers add the
+  // parts themselves)
   const bool direct = u.T <= 4;
-  int ksplit = direct ? (u.d_in + 2047) / 2048 : is_decode(u.T) ? 8 : (256 + tblocks - 1) / tblocks;
+  int ksplit = direct ? (u.d_in + 2047) / 2048 : is_decode(u.T) ? 4 : (256 + tblocks - 1) / tblocks;
   if (direct && ksplit > 4) ksplit = 4;
   if (ksplit > 32) ksplit = 32;
   if (ksplit < 1) ksplit = 1;

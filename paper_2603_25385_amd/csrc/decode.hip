@@ -47,7 +47,8 @@ __global__ void __launch_bounds__(NW * 64) k_decode(DecodeArgs a, ProjArgs p, in
   __shared__ uint32_t r_flag;
   __shared__ __attribute__((aligned(1024))) uint32_t lds_af[NW * DEC_RG * 256];
   if ((int)blockIdx.x < n_prod) {
-    proj_workgroup<ACT>(p, (int)blockIdx.x / p.ksplit, (int)blockIdx.x % p.ksplit, lds);
+    const int per_tb = p.ksplit * p.groups, rem = (int)blockIdx.x % per_tb;
+    proj_workgroup<ACT>(p, (int)blockIdx.x / per_tb, rem % p.ksplit, rem / p.ksplit, lds);
     return;
   }
   decode_workgroup<ACT, TBK, NW>(a, p, (int)blockIdx.x - n_prod, n_blocks, lds, r_lds, &r_flag, lds_af);
@@ -209,7 +210,10 @@ hipError_t launch_decode_multi(const glowq_unit* const* units, const UnitWorkspa
     a.ctl = (Control*)ws[i].base;
     if (restore[i]) {
       p = make_proj_args(u, ws[i], nullptr, true);
-      n_prod = ((u.T + 15) / 16) * ws[i].ksplit;
+      // (few K slices, so that the consumers gather few partial sums per rank, and two
+      // workgroups per slice, so that a projection workgroup reads no more of B than before)
+      p.groups = u.r > 16 ? 2 : 1;
+      n_prod = ((u.T + 15) / 16) * ws[i].ksplit * p.groups;
     }
     dim3 grid((unsigned)(n_prod + (blocks + DEC_RG - 1) / DEC_RG));
     // (eight waves per workgroup, i.e. twice the tiles in flight per compute unit, were

@@ -508,15 +508,14 @@ __device__ inline void correction_take(CorrFrag& c, const uint32_t* lds_row, int
 __device__ inline void vm_load_dev(u32x4_t& v, const void* p) {
   asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
 }
-template <int ACT, int TBK, int NW>
-__device__ inline bool fetch_r_coop(const DecodeArgs& a, const ProjArgs& p, uint16_t* r_lds, uint32_t* flag) {
+template <int ACT, int TBK, int NW, int MAXP>
+__device__ inline bool fetch_r_coop_parts(const DecodeArgs& a, const ProjArgs& p, uint16_t* r_lds, uint32_t* flag) {
   const int tid = threadIdx.x;
   const int hp = a.r >> 1;                     // rank pairs (16-byte units) per token and part
   const int n_el = a.T * hp;                   // (token, rank pair) elements, <= 32 * 64
   const uint32_t tag = (uint32_t)(launch_tag() & 0xffffffffull);
   const u32x4_t* units = (const u32x4_t*)p.Rpart;
   constexpr int EPR = 2;                       // elements per thread and round
-  constexpr int MAXP = 8;                      // parts (ksplit <= 8 for these token counts)
   if (tid == 0) *flag = 0u;
   __syncthreads();
   for (int spin = 0; spin < (1 << 12); ++spin) {
@@ -566,6 +565,13 @@ __device__ inline bool fetch_r_coop(const DecodeArgs& a, const ProjArgs& p, uint
   }
   if (tid == 0) atomicOr(&a.ctl->status, 1u);
   return false;
+}
+
+template <int ACT, int TBK, int NW>
+__device__ inline bool fetch_r_coop(const DecodeArgs& a, const ProjArgs& p, uint16_t* r_lds, uint32_t* flag) {
+  // (MAXP: the parts a thread loads per element; at most four for these token counts)
+  if (p.ksplit <= 4) return fetch_r_coop_parts<ACT, TBK, NW, 4>(a, p, r_lds, flag);
+  return fetch_r_coop_parts<ACT, TBK, NW, 8>(a, p, r_lds, flag);
 }
 
 // Folds the NW waves' fp32 tiles of one row block through LDS and stores the result.

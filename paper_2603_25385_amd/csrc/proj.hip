@@ -124,6 +124,7 @@ ProjArgs make_proj_args(const glowq_unit& u, const UnitWorkspace& ws, float* R32
   a.R32 = R32;
   a.R16 = want_r16 ? (uint16_t*)(ws.base + ws.off_r16) : nullptr;
   a.ctl = (Control*)ws.base;
+  a.groups = 1;
   return a;
 }
 

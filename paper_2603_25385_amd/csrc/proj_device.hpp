@@ -17,17 +17,22 @@ struct ProjArgs {
   float* R32;          // optional fp32 [T][r]
   uint16_t* R16;       // optional act dtype [T][r]
   Control* ctl;        // control words of the unit's workspace slice
+  int groups;          // in-launch projection of 5 to 32 tokens: workgroups that share a K
+                       // slice, each with its own run of 16-rank blocks (1 or 2)
 };
 
-// One workgroup = (16-token block tb, K slice kz); any whole number of waves.
+// One workgroup = (16-token block tb, K slice kz, group ng of the slice's 16-rank blocks);
+// any whole number of waves.
 // lds: blockDim.x / 64 * 256 floats.
 // No reduction here: every partial sum is published as one 8-byte device-scope store
 // {fp32 bits, low word of the launch tag}, slot (t, kz, j) = slots[(t ksplit + kz) r + j],
 // and the consumers add the slices (no fence, no counter, nothing to wait for).
 template <int ACT>
-__device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* lds) {
+__device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, int ng, float* lds) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
   const int nbs = (a.r + 15) >> 4;
+  const int nb_per = (nbs + a.groups - 1) / a.groups;
+  const int nb0 = ng * nb_per, nb1 = min(nbs, nb0 + nb_per);      // this workgroup's rank blocks
   const int i = lane & 15, kq = lane >> 4;
   // tokens past T and ranks past r are computed from clamped (valid, finite) rows and
   // never stored: row i of D depends on row i of the first operand only, column n on
@@ -56,7 +61,7 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
       if (!in) xf[s] = u32x4_t{0u, 0u, 0u, 0u};
 #pragma unroll
       for (int nb = 0; nb < 8; ++nb) {
-        if (nb < nbs) {
+        if (nb >= nb0 && nb < nb1) {
           const int rank = min(nb * 16 + i, a.r - 1);
           bf[s][nb] = *(const u32x4_t*)(a.B + (size_t)rank * a.K + kc + 8 * kq);
         }
@@ -66,14 +71,14 @@ __device__ inline void proj_workgroup(const ProjArgs& a, int tb, int kz, float* 
     for (int s = 0; s < PB; ++s)
 #pragma unroll
       for (int nb = 0; nb < 8; ++nb)
-        if (nb < nbs) acc[nb] = mfma16<ACT>(xf[s], bf[s][nb], acc[nb]);   // D[token][rank]
+        if (nb >= nb0 && nb < nb1) acc[nb] = mfma16<ACT>(xf[s], bf[s][nb], acc[nb]);   // D[token][rank]
   }
 
   GLOWQ_STAMP(1);
   // fold the waves' tiles and store this slice's partial sum
 #pragma unroll
   for (int nb = 0; nb < 8; ++nb) {
-    if (nb < nbs) {
+    if (nb >= nb0 && nb < nb1) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) lds[(wave * 4 + v) * 64 + lane] = acc[nb][v];
       __syncthreads();
