@@ -505,7 +505,7 @@ glowq_status glowq_mx_quantize_activations(const void* X, int32_t T, int32_t d_i
   if (T < 1 || T > (1 << 20) || d_in < 32 || d_in > (1 << 16) || d_in % 32) return GLOWQ_ERR_SHAPE;
   if (act_dtype != GLOWQ_F16 && act_dtype != GLOWQ_BF16) return GLOWQ_ERR_DTYPE;
   if (misaligned(X) || misaligned(codes)) return GLOWQ_ERR_ALIGN;
-  return hip_status(launch_mx_quantize_x(X, T, d_in, act_dtype, codes, scales, (hipStream_t)stream));
+  return hip_status(launch_mx_quantize_x(X, T, d_in, act_dtype, codes, scales, false, (hipStream_t)stream));
 }
 
 // the unit checks of the ordinary forward without its group size (MX blocks are 32 channels)

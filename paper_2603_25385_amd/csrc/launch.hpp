@@ -55,8 +55,8 @@ hipError_t launch_factorize(const glowq_unit& u, const float* const* W_modules, 
 // Microscaling variant (MXFP4 weights, MXFP8 activations), up to 16 tokens.
 struct MxWorkspace {
   size_t off_rpart;         // fp32 partial sums of the projection, [ks][16][r]
-  size_t off_xcodes;        // E4M3 codes of the activations, [16][d_in]
-  size_t off_xscales;       // their E8M0 block scales, [16][d_in / 32]
+  size_t off_xcodes;        // E4M3 codes of the activations in fragment order, whole 16-token blocks
+  size_t off_xscales;       // their E8M0 block scales, likewise
   size_t bytes;
   int ks, kslice;           // K slices of the projection and channels per slice
 };
@@ -66,7 +66,7 @@ MxWorkspace plan_mx_workspace(const glowq_unit& u);
 hipError_t launch_mx_prepare(const uint32_t* codes, const uint8_t* scales, int d_out, int d_in, void* prepared,
                              hipStream_t st);
 hipError_t launch_mx_quantize_x(const void* X, int T, int d_in, int act, uint8_t* codes, uint8_t* scales,
-                                hipStream_t st);
+                                bool fragment_order, hipStream_t st);
 hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace, hipStream_t st);
 // slices' start offsets in units of 256 bytes (every slice is 256-byte aligned)
 constexpr int STATUS_BATCH = 256;

@@ -65,13 +65,20 @@ __device__ inline uint32_t e4m3_round(double a) {
 // Eight neighbouring lanes per (token, block of 32): four values each, the block maximum by
 // lane shuffles.  idx counts (token, block, eighth); every lane of a wave must call this
 // (lanes past the end take part in the shuffles and store nothing).
-template <int ACT>
+// FRAG false: the canonical layouts, codes [T][d_in] and scales [T][d_in / 32].  FRAG true:
+// fragment order, as the forward kernels read it -- per (16-token block, 128-channel tile)
+// two 1 KiB chunks of codes [half][lane][16 bytes], lane = token + 16 g holding the channels
+// 64 half + 16 g .. + 16 of its token (the fp8 operand of the matrix instruction as it
+// stands, so that a wave's fetch is one contiguous KiB), and 64 scale bytes [lane], lane =
+// token + 16 block.  Slots of tokens past T are not written.
+template <int ACT, bool FRAG>
 __device__ inline void mx_quantize_block(const uint16_t* __restrict__ X, int T, int d_in,
-                                         uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, int idx) {
+                                         uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, long long idx) {
   const int blocks = d_in / 32;
-  const bool live = idx < T * blocks * 8;
-  const int blk = live ? idx >> 3 : 0, sub = idx & 7;
-  const int t = blk / blocks, b = blk - t * blocks;
+  const bool live = idx < (long long)T * blocks * 8;
+  const long long blk = live ? idx >> 3 : 0;
+  const int sub = (int)(idx & 7);
+  const int t = (int)(blk / blocks), b = (int)(blk - (long long)t * blocks);
   const uint2 w = *(const uint2*)(X + (long long)t * d_in + 32 * b + 4 * sub);
   double v[4];
   v[0] = act16_value<ACT>(w.x & 0xffffu);
@@ -96,14 +103,22 @@ __device__ inline void mx_quantize_block(const uint16_t* __restrict__ X, int T, 
     word |= c << (8 * e);
   }
   if (!live) return;
-  *(uint32_t*)(codes + (long long)t * d_in + 32 * b + 4 * sub) = word;
-  if (sub == 0) scales[(long long)t * blocks + b] = (uint8_t)(shared + 127);
+  if (FRAG) {
+    const int ktiles = d_in / 128, kt = b >> 2, kb = b & 3;
+    const long long tile = (long long)(t >> 4) * ktiles + kt;
+    const int c = 32 * (kb & 1) + 4 * sub;                       // channel within the half
+    *(uint32_t*)(codes + (tile * 2 + (kb >> 1)) * 1024 + ((t & 15) + 16 * (c >> 4)) * 16 + (c & 15)) = word;
+    if (sub == 0) scales[tile * 64 + (t & 15) + 16 * kb] = (uint8_t)(shared + 127);
+  } else {
+    *(uint32_t*)(codes + (long long)t * d_in + 32 * b + 4 * sub) = word;
+    if (sub == 0) scales[(long long)t * blocks + b] = (uint8_t)(shared + 127);
+  }
 }
 
-template <int ACT>
+template <int ACT, bool FRAG>
 __global__ void __launch_bounds__(256) k_mx_quantize_x(const uint16_t* __restrict__ X, int T, int d_in,
                                                        uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
-  mx_quantize_block<ACT>(X, T, d_in, codes, scales, (int)(blockIdx.x * blockDim.x + threadIdx.x));
+  mx_quantize_block<ACT, FRAG>(X, T, d_in, codes, scales, (long long)blockIdx.x * blockDim.x + threadIdx.x);
 }
 
 // First launch of the forward (workgroups of 16 waves).  The leading workgroups compute the
@@ -128,8 +143,8 @@ __global__ void __launch_bounds__(MX_FRONT_THREADS) k_mx_front(MxFrontArgs a) {
   const int nbs = (a.r + 15) >> 4;
   const int n_proj = a.B ? a.ks * nbs : 0;
   if ((int)blockIdx.x >= n_proj) {
-    mx_quantize_block<ACT>(a.X, a.T, a.d_in, a.xcodes, a.xscales,
-                           (int)((blockIdx.x - n_proj) * MX_FRONT_THREADS + threadIdx.x));
+    mx_quantize_block<ACT, true>(a.X, a.T, a.d_in, a.xcodes, a.xscales,
+                                 (long long)(blockIdx.x - n_proj) * MX_FRONT_THREADS + threadIdx.x);
     return;
   }
   const int kz = (int)blockIdx.x % a.ks, nb = (int)blockIdx.x / a.ks;
@@ -185,8 +200,8 @@ struct MxModule {
 struct MxArgs {
   MxModule mod[GLOWQ_MAX_MODULES];
   int n_modules;
-  const uint8_t* xcodes;     // [T][d_in] E4M3
-  const uint8_t* xscales;    // [T][d_in / 32] E8M0
+  const uint8_t* xcodes;     // E4M3, fragment order (see mx_quantize_block)
+  const uint8_t* xscales;    // E8M0, fragment order
   const float* Rpart;        // fp32 [ks][16][r] partial sums of R, or NULL when not restored
   int ks;
   int T, d_in, r;
@@ -216,8 +231,8 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
     wc[q] = (const u32x4_t*)m.codes + ((long long)rb * ktiles) * 64 + l;
     ws[q] = m.scales + ((long long)rb * ktiles) * 64 + l;
   }
-  const uint8_t* xc = a.xcodes + (long long)(tok ? i : 0) * a.d_in + 16 * g;
-  const uint8_t* xs = a.xscales + (long long)(tok ? i : 0) * (a.d_in / 32) + g;
+  const uint8_t* xc = a.xcodes + l * 16;            // fragment order: a tile is two chunks of 1 KiB
+  const uint8_t* xs = a.xscales + l;
 #pragma unroll 8
   for (int kt = w; kt < ktiles; kt += 4) {
     u32x4_t bw[RB];
@@ -230,9 +245,9 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
     u32x4_t a0 = {0, 0, 0, 0}, a1 = {0, 0, 0, 0};
     int sa = 127;
     if (tok) {
-      a0 = *(const u32x4_t*)(xc + 128 * kt);
-      a1 = *(const u32x4_t*)(xc + 128 * kt + 64);
-      sa = xs[4 * kt];
+      a0 = *(const u32x4_t*)(xc + 2048 * kt);
+      a1 = *(const u32x4_t*)(xc + 2048 * kt + 1024);
+      sa = xs[64 * kt];
     }
     const v8i_t A = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
 #pragma unroll
@@ -299,9 +314,9 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
 // for the 32x32x64 shape alike - the rate of the 16-bit instructions, not twice it.)  Both tiles sit in LDS in fragment order, so that a wave's
 // fragment read is 1 KiB lane after lane (no bank conflict by construction): the weight tile
 // is the prepared layout as it is in memory; the activation tile is [token block][half]
-// [lane][16 bytes], each lane of a load fetching the 16 bytes that the same lane of the
-// matrix instruction will hold.  Tokens past T repeat the last token (their outputs are not
-// stored).  The correction (R from the stand-alone projection, in the activation type) is
+// [lane][16 bytes], which is how the quantiser leaves it in the workspace, so every load is
+// one contiguous KiB.  Slots of tokens past T hold whatever the workspace held (a row of the
+// first operand touches its own output row only, and those are not stored).  The correction (R from the stand-alone projection, in the activation type) is
 // r / 32 more 16-bit instructions per accumulator tile in the epilogue.
 // ---------------------------------------------------------------------------------------
 constexpr int MXG_TOK = 128, MXG_ROWS = 128;
@@ -334,12 +349,12 @@ __global__ void __launch_bounds__(256) k_mx_gemm(MxGemmArgs a) {
   const int wm = w >> 1, wn = w & 1;
   // this wave's share of a step's loads: activation chunks 4w .. 4w + 3 (chunk = token block,
   // half), weight row blocks 2w, 2w + 1, and one of the four 256-byte pieces of the scales
+  const int n_tb = (a.T + 15) / 16;                 // token blocks that exist (a tile's blocks past them repeat the last)
   const uint8_t* asrc[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const int chunk = 4 * w + q, tb = chunk >> 1, h = chunk & 1;
-    const int tok = min(tok0 + 16 * tb + i, a.T - 1);
-    asrc[q] = a.xcodes + (long long)tok * a.d_in + 64 * h + 16 * g;
+    const int chunk = 4 * w + q, tb = min(tok0 / 16 + (chunk >> 1), n_tb - 1), h = chunk & 1;
+    asrc[q] = a.xcodes + (((long long)tb * ktiles) * 2 + h) * 1024 + l * 16;
   }
   const u32x4_t* bsrc[2];
 #pragma unroll
@@ -348,9 +363,9 @@ __global__ void __launch_bounds__(256) k_mx_gemm(MxGemmArgs a) {
   const uint32_t* scsrc;
   long long sc_step;                    // dwords per K tile
   if (w < 2) {
-    const int tok = min(tok0 + 64 * w + l, a.T - 1);
-    scsrc = (const uint32_t*)(a.xscales + (long long)tok * (a.d_in / 32));
-    sc_step = 1;
+    const int tb = min(tok0 / 16 + 4 * w + (l >> 4), n_tb - 1);
+    scsrc = (const uint32_t*)(a.xscales + ((long long)tb * ktiles) * 64) + (l & 15);
+    sc_step = 16;
   } else {
     const int rbi = 4 * (w - 2) + (l >> 4);
     scsrc = (const uint32_t*)(m.scales + ((long long)min(rb0 + rbi, n_rb - 1) * ktiles) * 64) + (l & 15);
@@ -360,7 +375,7 @@ __global__ void __launch_bounds__(256) k_mx_gemm(MxGemmArgs a) {
   auto issue = [&](int kt, int buf) {
     const uint32_t base = lds0 + buf * MXG_BUF;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) lds_dma16(asrc[q] + 128 * kt, base + MXG_A + (4 * w + q) * 1024);
+    for (int q = 0; q < 4; ++q) lds_dma16(asrc[q] + 2048 * kt, base + MXG_A + (4 * w + q) * 1024);
 #pragma unroll
     for (int q = 0; q < 2; ++q) lds_dma16(bsrc[q] + (long long)kt * 64, base + MXG_B + (2 * w + q) * 1024);
     lds_dma4(scsrc + kt * sc_step, base + (w < 2 ? MXG_ASC + 256 * w : MXG_BSC + 256 * (w - 2)));
@@ -391,7 +406,7 @@ __global__ void __launch_bounds__(256) k_mx_gemm(MxGemmArgs a) {
       const int tbg = 4 * wm + tb;
       const u32x4_t lo = *(const u32x4_t*)(L + MXG_A + (2 * tbg) * 1024 + l * 16);
       const u32x4_t hi = *(const u32x4_t*)(L + MXG_A + (2 * tbg + 1) * 1024 + l * 16);
-      const int sa = L[MXG_ASC + (16 * tbg + i) * 4 + g];
+      const int sa = L[MXG_ASC + tbg * 64 + l];
       const v8i_t A = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
 #pragma unroll
       for (int nb = 0; nb < 4; ++nb)
@@ -452,11 +467,17 @@ hipError_t launch_mx_prepare(const uint32_t* codes, const uint8_t* scales, int d
 }
 
 hipError_t launch_mx_quantize_x(const void* X, int T, int d_in, int act, uint8_t* codes, uint8_t* scales,
-                                hipStream_t st) {
-  const int n = T * (d_in / 32) * 8;
+                                bool fragment_order, hipStream_t st) {
+  const long long n = (long long)T * (d_in / 32) * 8;
   dim3 grid((unsigned)((n + 255) / 256)), block(256);
-  if (act == GLOWQ_F16) k_mx_quantize_x<ACT_F16><<<grid, block, 0, st>>>((const uint16_t*)X, T, d_in, codes, scales);
-  else k_mx_quantize_x<ACT_BF16><<<grid, block, 0, st>>>((const uint16_t*)X, T, d_in, codes, scales);
+  const uint16_t* x = (const uint16_t*)X;
+  if (act == GLOWQ_F16) {
+    if (fragment_order) k_mx_quantize_x<ACT_F16, true><<<grid, block, 0, st>>>(x, T, d_in, codes, scales);
+    else k_mx_quantize_x<ACT_F16, false><<<grid, block, 0, st>>>(x, T, d_in, codes, scales);
+  } else {
+    if (fragment_order) k_mx_quantize_x<ACT_BF16, true><<<grid, block, 0, st>>>(x, T, d_in, codes, scales);
+    else k_mx_quantize_x<ACT_BF16, false><<<grid, block, 0, st>>>(x, T, d_in, codes, scales);
+  }
   return hipGetLastError();
 }
 
@@ -470,8 +491,9 @@ MxWorkspace plan_mx_workspace(const glowq_unit& u) {
     w.ks = w.kslice = 0;
     w.off_rpart = 0;
     w.off_xcodes = up256(plan_unit_workspace(u, nullptr).bytes);
-    w.off_xscales = w.off_xcodes + up256((size_t)u.T * u.d_in);
-    w.bytes = w.off_xscales + up256((size_t)u.T * (u.d_in / 32));
+    const size_t t16 = (size_t)(u.T + 15) / 16 * 16;           // whole 16-token blocks
+    w.off_xscales = w.off_xcodes + up256(t16 * u.d_in);
+    w.bytes = w.off_xscales + up256(t16 * (u.d_in / 32));
     return w;
   }
   // K slices of the projection: at most 4, a multiple of 512 channels each
@@ -488,7 +510,7 @@ static hipError_t launch_mx_gemm(const glowq_unit& u, bool restore, char* worksp
   const MxWorkspace w = plan_mx_workspace(u);
   uint8_t* xcodes = (uint8_t*)(workspace + w.off_xcodes);
   uint8_t* xscales = (uint8_t*)(workspace + w.off_xscales);
-  hipError_t err = launch_mx_quantize_x(u.X, u.T, u.d_in, u.act_dtype, xcodes, xscales, st);
+  hipError_t err = launch_mx_quantize_x(u.X, u.T, u.d_in, u.act_dtype, xcodes, xscales, true, st);
   if (err != hipSuccess) return err;
   const bool corrected = restore && u.r > 0;
   const UnitWorkspace uw = plan_unit_workspace(u, workspace);
