@@ -71,7 +71,9 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   w.pf_part_stages = (stages + parts - 1) / parts;
   w.pf_parts = (stages + w.pf_part_stages - 1) / w.pf_part_stages;
   w.off_rpart = w.ctl_bytes;
-  const int slabs = is_decode(u.T) ? w.kstride : (w.kstride > w.pf_parts ? w.kstride : w.pf_parts);
+  // (T > 32: room for eight slices, which is what the stand-alone projection uses)
+  int slabs = is_decode(u.T) ? w.kstride : (w.kstride > w.pf_parts ? w.kstride : w.pf_parts);
+  if (!is_decode(u.T) && slabs < 8) slabs = 8;
   size_t rpart = (u.r > 0) ? (size_t)slabs * u.T * u.r * (is_decode(u.T) ? 8 : 4) : 0;
   w.off_r16 = align_up(w.off_rpart + rpart, 256);
   size_t r16 = (u.r > 0) ? (size_t)u.T * u.r * 2 : 0;

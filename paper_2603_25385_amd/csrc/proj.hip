@@ -134,8 +134,9 @@ hipError_t launch_proj(const glowq_unit& u, const UnitWorkspace& ws, float* R32,
   // layout of the partial sums for this path: [slice][T][r]; slices as planned, but never
   // more than the partial-sum area (sized for the decode layout) can hold
   const size_t cap = (ws.off_r16 - ws.off_rpart) / ((size_t)u.T * u.r * sizeof(float));
-  int ksplit = ws.ksplit;
-  if ((size_t)ksplit > cap) ksplit = (int)cap;
+  // (as many slices as the area holds, up to eight: the stand-alone projection has no other
+  // work on the chip to hide its latency behind)
+  int ksplit = cap < 8 ? (int)cap : 8;
   if (ksplit < 1) return hipErrorInvalidValue;
   const int steps = u.d_in / 32, per = (steps + ksplit - 1) / ksplit;
   a.kslice = per * 32;
