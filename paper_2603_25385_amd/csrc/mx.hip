@@ -19,8 +19,10 @@
 //
 // Weight storage (glowq_mx_prepare_weights): codes region [row block][tile][lane][4 words],
 // then scales region [row block][tile][lane] bytes.  Rows past d_out: code 0, scale 127.
+#include <algorithm>
 #include "common.hpp"
 #include "launch.hpp"
+#include "proj_device.hpp"
 
 namespace glowq {
 
@@ -53,18 +55,61 @@ __global__ void k_mx_prepare(const uint32_t* __restrict__ codes, const uint8_t* 
 // ---------------------------------------------------------------------------------------
 // MXFP8 (E4M3) quantisation of the activations
 // ---------------------------------------------------------------------------------------
-// code of |v| < 512 rounded to E4M3, nearest even, clamped to 448
-__device__ inline uint32_t e4m3_round(double a) {
-  if (a < 0x1p-6) return (uint32_t)__builtin_rint(a * 0x1p9);      // subnormal grid (8 is the smallest normal)
-  const uint64_t mag = __builtin_bit_cast(uint64_t, a);
-  const uint64_t r = mag + ((1ull << 48) - 1) + ((mag >> 49) & 1);   // 52 - 3 = 49 bits dropped
-  const uint32_t code = (uint32_t)(((r >> 52) - 1023 + 7) << 3) | (uint32_t)((r >> 49) & 7);
-  return code > 0x7Eu ? 0x7Eu : code;
+// 16-bit pattern of the activation type as fp32 (exact)
+template <int ACT>
+__device__ inline float act16_f32(uint32_t h) {
+  if constexpr (ACT == ACT_F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+  else return __builtin_bit_cast(float, h << 16);
 }
 
-// Eight neighbouring lanes per (token, block of 32): four values each, the block maximum by
-// lane shuffles.  idx counts (token, block, eighth); every lane of a wave must call this
-// (lanes past the end take part in the shuffles and store nothing).
+// Sixteen consecutive channels of one token (lo, hi: their 16-bit patterns), half of an MX
+// block; the other half is with the neighbouring lane (lane ^ 1), so both lanes of a pair
+// must call this together.  Returns the sixteen E4M3 codes and the block's E8M0 scale code.
+// Everything is exact but the one rounding to E4M3: the block maximum through the integer
+// patterns of the magnitudes (they order as the values do), the values as fp32, the division
+// by the power of two as a product, the clamp to +-448 (a scaled magnitude lies below 512),
+// and the rounding itself by the conversion instruction (nearest even, subnormal codes kept,
+// a zero keeps its sign bit, which the product ignores: the stored code of a zero is +0).
+template <int ACT>
+__device__ inline void mx_quantize16(const u32x4_t lo, const u32x4_t hi, u32x4_t& codes, int& scale_code) {
+  typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+  u16x2_t mm = {0, 0};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const u16x2_t a = __builtin_bit_cast(u16x2_t, lo[e] & 0x7fff7fffu), c = __builtin_bit_cast(u16x2_t, hi[e] & 0x7fff7fffu);
+    mm = __builtin_elementwise_max(mm, __builtin_elementwise_max(a, c));
+  }
+  uint32_t m16 = max((uint32_t)mm[0], (uint32_t)mm[1]);
+  m16 = max(m16, (uint32_t)__shfl_xor((int)m16, 1, 64));
+  int shared = 0;
+  if (m16 != 0u) {
+    const uint32_t mmax = __builtin_bit_cast(uint32_t, act16_f32<ACT>(m16));
+    const int ef = (int)(mmax >> 23);
+    // floor(log2 max) - emax; a maximum below 2^-126 (bfloat16 only) has no exponent field
+    const int fl = ef != 0 ? ef - 127 : (31 - __builtin_clz(mmax)) - 149;
+    shared = max(-127, min(127, fl - 8));
+  }
+  const float inv = __builtin_bit_cast(float, (uint32_t)(127 - shared) << 23);        // 2^-shared
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t w0 = q < 2 ? lo[2 * q] : hi[2 * q - 4], w1 = q < 2 ? lo[2 * q + 1] : hi[2 * q - 3];
+    const float x0 = __builtin_amdgcn_fmed3f(act16_f32<ACT>(w0 & 0xffffu) * inv, -448.f, 448.f);
+    const float x1 = __builtin_amdgcn_fmed3f(act16_f32<ACT>(w0 >> 16) * inv, -448.f, 448.f);
+    const float x2 = __builtin_amdgcn_fmed3f(act16_f32<ACT>(w1 & 0xffffu) * inv, -448.f, 448.f);
+    const float x3 = __builtin_amdgcn_fmed3f(act16_f32<ACT>(w1 >> 16) * inv, -448.f, 448.f);
+    int word = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+    word = __builtin_amdgcn_cvt_pk_fp8_f32(x2, x3, word, true);
+    // -0 -> +0: a byte of 0x80 loses its sign
+    const uint32_t u = (uint32_t)word;
+    const uint32_t nz = (u & 0x7f7f7f7fu) + 0x7f7f7f7fu;          // bit 7 of a byte set iff its low seven bits are not zero
+    codes[q] = u & (nz | 0x7f7f7f7fu);
+  }
+  scale_code = shared + 127;
+}
+
+// Two neighbouring lanes per (token, block of 32).  idx counts (token, 16-channel piece);
+// every lane of a wave must call this (lanes past the end take part in the shuffle and
+// store nothing).
 // FRAG false: the canonical layouts, codes [T][d_in] and scales [T][d_in / 32].  FRAG true:
 // fragment order, as the forward kernels read it -- per (16-token block, 128-channel tile)
 // two 1 KiB chunks of codes [half][lane][16 bytes], lane = token + 16 g holding the channels
@@ -74,44 +119,25 @@ __device__ inline uint32_t e4m3_round(double a) {
 template <int ACT, bool FRAG>
 __device__ inline void mx_quantize_block(const uint16_t* __restrict__ X, int T, int d_in,
                                          uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, long long idx) {
-  const int blocks = d_in / 32;
-  const bool live = idx < (long long)T * blocks * 8;
-  const long long blk = live ? idx >> 3 : 0;
-  const int sub = (int)(idx & 7);
-  const int t = (int)(blk / blocks), b = (int)(blk - (long long)t * blocks);
-  const uint2 w = *(const uint2*)(X + (long long)t * d_in + 32 * b + 4 * sub);
-  double v[4];
-  v[0] = act16_value<ACT>(w.x & 0xffffu);
-  v[1] = act16_value<ACT>(w.x >> 16);
-  v[2] = act16_value<ACT>(w.y & 0xffffu);
-  v[3] = act16_value<ACT>(w.y >> 16);
-  double amax = fmax(fmax(fabs(v[0]), fabs(v[1])), fmax(fabs(v[2]), fabs(v[3])));
-#pragma unroll
-  for (int o = 1; o < 8; o <<= 1) amax = fmax(amax, __shfl_xor(amax, o, 64));
-  int shared = 0;
-  if (amax > 0.0) {
-    shared = (int)((__builtin_bit_cast(uint64_t, amax) >> 52) & 0x7ff) - 1023 - 8;   // floor(log2 amax) - emax
-    shared = max(-127, min(127, shared));
-  }
-  const double inv = __builtin_bit_cast(double, (uint64_t)(1023 - shared) << 52);      // 2^-shared
-  uint32_t word = 0;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const double x = v[e] * inv;
-    uint32_t c = e4m3_round(fabs(x));
-    if (x < 0.0 && c != 0) c |= 0x80u;
-    word |= c << (8 * e);
-  }
+  const int pieces = d_in / 16;
+  const bool live = idx < (long long)T * pieces;
+  const long long it = live ? idx : 0;
+  const int t = (int)(it / pieces), h = (int)(it - (long long)t * pieces);
+  const u32x4_t* src = (const u32x4_t*)(X + (long long)t * d_in + 16 * h);
+  u32x4_t c;
+  int sc;
+  mx_quantize16<ACT>(src[0], src[1], c, sc);
   if (!live) return;
+  const int b = h >> 1;
   if (FRAG) {
     const int ktiles = d_in / 128, kt = b >> 2, kb = b & 3;
     const long long tile = (long long)(t >> 4) * ktiles + kt;
-    const int c = 32 * (kb & 1) + 4 * sub;                       // channel within the half
-    *(uint32_t*)(codes + (tile * 2 + (kb >> 1)) * 1024 + ((t & 15) + 16 * (c >> 4)) * 16 + (c & 15)) = word;
-    if (sub == 0) scales[tile * 64 + (t & 15) + 16 * kb] = (uint8_t)(shared + 127);
+    const int g = 2 * (kb & 1) + (h & 1);                        // 16-channel piece within the half
+    *(u32x4_t*)(codes + (tile * 2 + (kb >> 1)) * 1024 + ((t & 15) + 16 * g) * 16) = c;
+    if (!(h & 1)) scales[tile * 64 + (t & 15) + 16 * kb] = (uint8_t)sc;
   } else {
-    *(uint32_t*)(codes + (long long)t * d_in + 32 * b + 4 * sub) = word;
-    if (sub == 0) scales[(long long)t * blocks + b] = (uint8_t)(shared + 127);
+    *(u32x4_t*)(codes + (long long)t * d_in + 16 * h) = c;
+    if (!(h & 1)) scales[(long long)t * (d_in / 32) + b] = (uint8_t)sc;
   }
 }
 
@@ -200,6 +226,7 @@ struct MxModule {
 struct MxArgs {
   MxModule mod[GLOWQ_MAX_MODULES];
   int n_modules;
+  const uint16_t* X;         // act dtype [T][d_in] (the one-launch kernel quantises it itself)
   const uint8_t* xcodes;     // E4M3, fragment order (see mx_quantize_block)
   const uint8_t* xscales;    // E8M0, fragment order
   const float* Rpart;        // fp32 [ks][16][r] partial sums of R, or NULL when not restored
@@ -298,6 +325,218 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
     if (t < a.T && row < m.d_out) {
       if (a.out_f32) ((float*)m.Y)[(long long)t * m.ldy + row] = y;
       else ((uint16_t*)m.Y)[(long long)t * m.ldy + row] = to_act16<ACT>(y);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// up to four tokens, one launch.  The leading workgroups are the projection (one wave per
+// rank and K part, proj_wave_direct: every partial sum is published as one 8-byte slot
+// {fp32 bits, low word of the launch tag} that validates itself); the others take one 16-row
+// block each and do everything else themselves: every workgroup quantises the whole X into
+// LDS (T d_in values, two to eight hundred instructions per thread, under the latency of its
+// own weight loads, which are issued first but behind the loads of X: loads return in order),
+// its four waves take the 128-channel tiles round robin, eight tiles per register buffer and
+// two buffers in flight, and each wave asks for the slots of its own correction step in the
+// middle of its first round (global -> LDS, device scope) and checks them after its stream.
+// A slot that does not carry this launch's tag is asked for again; the
+// projection workgroups lead the grid and wait for nothing, the wait is bounded all the same,
+// and a wave that gives up stores NaN in its rows rather than leave the correction out
+// unnoticed.
+// LDS: part [4][64][4] floats, then the E4M3 codes [tile][half][g][4 tokens][16 bytes], then
+// the scale codes [tile][block][4 tokens], then per wave and K part 1 KiB of slots.
+// ---------------------------------------------------------------------------------------
+constexpr int MXS_MAX_TOKENS = 4;
+constexpr int MXS_ITEMS = 4;          // 16-channel pieces of X per thread, at most
+constexpr int MXS_ROUND = 8;          // tiles per wave and register buffer
+constexpr int MXS_MAX_PARTS = 2;      // K parts of the in-launch projection
+
+// lds_dma16 at device scope (not served from a cache that may hold an older copy)
+__device__ inline void lds_dma16_coherent(const void* gptr, uint32_t lds_base) {
+  const uint32_t m = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off sc1"
+               : : "v"(gptr), "s"(m) : "memory", "m0");
+}
+
+template <int ACT>
+__global__ void __launch_bounds__(256, 4) k_mx_decode_small(MxArgs a, ProjArgs p, int n_prod) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t mxs_lds[];
+  const int w = threadIdx.x >> 6, l = threadIdx.x & 63, i = l & 15, g = l >> 4;
+  if ((int)blockIdx.x < n_prod) {
+    proj_wave_direct<ACT>(p, (int)blockIdx.x * 4 + w, l);
+    return;
+  }
+  const int ktiles = a.d_in / 128;
+  float* part = (float*)mxs_lds;
+  u32x4_t* xq = (u32x4_t*)(mxs_lds + 4096);
+  uint8_t* xsc = mxs_lds + 4096 + (size_t)ktiles * 512;
+  const int blk = (int)blockIdx.x - n_prod;
+  int mi = 0;
+#pragma unroll
+  for (int q = 1; q < GLOWQ_MAX_MODULES; ++q)
+    if (q < a.n_modules && blk >= a.mod[q].first_block) mi = q;
+  const MxModule& m = a.mod[mi];
+  const int rb = blk - m.first_block;
+  const bool tok = i < a.T;
+
+  // X first: this thread's 16-channel pieces (token t, tile kt, half, g), piece index
+  // tid + 256 n; the two halves of a block sit in neighbouring lanes
+  const int n_items = a.T * ktiles * 8;
+  u32x4_t xl[MXS_ITEMS], xh[MXS_ITEMS];
+#pragma unroll
+  for (int n = 0; n < MXS_ITEMS; ++n) {
+    const int idx = min((int)threadIdx.x + 256 * n, n_items - 1);          // past the end: loaded again, not stored
+    const int t = idx / (8 * ktiles), rem = idx - t * 8 * ktiles;
+    const u32x4_t* src = (const u32x4_t*)(a.X + (size_t)t * a.d_in + 16 * rem);   // 128 kt + 64 half + 16 g = 16 rem
+    if (256 * n < n_items) { xl[n] = src[0]; xh[n] = src[1]; }
+  }
+  // then the weights: the wave's tiles w, w + 4, ...
+  const u32x4_t* wc = (const u32x4_t*)m.codes + ((size_t)rb * ktiles) * 64 + l;
+  const uint8_t* ws = m.scales + ((size_t)rb * ktiles) * 64 + l;
+  const int nj = (ktiles - w + 3) >> 2;
+  u32x4_t bwA[MXS_ROUND], bwB[MXS_ROUND];
+  int sbA[MXS_ROUND], sbB[MXS_ROUND];
+  auto load = [&](u32x4_t (&bw)[MXS_ROUND], int (&sb)[MXS_ROUND], int j0) {
+#pragma unroll
+    for (int q = 0; q < MXS_ROUND; ++q) {
+      const int kt = min(w + 4 * (j0 + q), ktiles - 1);                     // past the end: loaded again, not used
+      bw[q] = wc[(size_t)kt * 64];
+      sb[q] = ws[(size_t)kt * 64];
+    }
+  };
+  load(bwA, sbA, 0);
+  // the wave's correction step: ranks 32 w + 8 g .. + 8 of A_i
+  const int j0r = 32 * w + 8 * g;
+  const bool corr = p.B != nullptr && 32 * w < a.r;
+  u32x4_t rbv = {0, 0, 0, 0};
+  if (corr) {
+    const int row = rb * 16 + i;
+    if (j0r < a.r && row < m.d_out) rbv = *(const u32x4_t*)(m.A + (size_t)row * a.r + j0r);
+  }
+  // quantise (every lane of a wave goes through the same rounds)
+#pragma unroll
+  for (int n = 0; n < MXS_ITEMS; ++n) {
+    if (256 * n < n_items) {
+      const int idx = (int)threadIdx.x + 256 * n;
+      u32x4_t c;
+      int sc;
+      mx_quantize16<ACT>(xl[n], xh[n], c, sc);
+      if (idx < n_items) {
+        const int t = idx / (8 * ktiles), rem = idx - t * 8 * ktiles;
+        const int kt = rem >> 3, half = (rem >> 2) & 1, gg = rem & 3;
+        xq[((kt * 2 + half) * 4 + gg) * 4 + t] = c;
+        if (!(gg & 1)) xsc[kt * 16 + (2 * half + (gg >> 1)) * 4 + t] = (uint8_t)sc;
+      }
+    }
+  }
+  __syncthreads();
+
+  // The slots of the wave's correction step travel global -> LDS, one load per K part: lane
+  // (unit e = l & 3, token (l >> 2) & 3, rank group l >> 4) fetches 16 bytes = two slots, so
+  // that the 64 bytes of a (rank group, token) lie together, [group][token][unit].  Asked
+  // for in the middle of the wave's first round of tiles: behind the weights in the queue
+  // (loads return in order), and late enough for the projection to have published.
+  uint8_t* rfw = mxs_lds + 4096 + (size_t)ktiles * 528 + (size_t)w * (MXS_MAX_PARTS * 1024);
+  const uint32_t rfw_lds = lds_address(rfw);
+  const u32x4_t* rsrc;
+  {
+    const int e = l & 3, tk = min((l >> 2) & 3, a.T - 1), j0 = min(32 * w + 8 * (l >> 4), max(a.r - 8, 0));
+    rsrc = (const u32x4_t*)((const unsigned long long*)p.Rpart + (size_t)tk * p.ksplit * a.r + j0) + e;
+  }
+  auto r_issue = [&]() {
+#pragma unroll
+    for (int part = 0; part < MXS_MAX_PARTS; ++part)
+      if (part < p.ksplit) lds_dma16_coherent(rsrc + (size_t)part * (a.r >> 1), rfw_lds + part * 1024);
+  };
+
+  float4_t acc = {0.f, 0.f, 0.f, 0.f};
+  auto run = [&](const u32x4_t (&bw)[MXS_ROUND], const int (&sb)[MXS_ROUND], int j0) {
+#pragma unroll
+    for (int q = 0; q < MXS_ROUND; ++q) {
+      if (q == MXS_ROUND / 2 && j0 == 0 && corr) r_issue();
+      const int kt = w + 4 * (j0 + q);
+      if (kt < ktiles) {
+        u32x4_t a0 = {0, 0, 0, 0}, a1 = {0, 0, 0, 0};
+        int sa = 127;
+        if (tok) {
+          a0 = xq[((kt * 2 + 0) * 4 + g) * 4 + i];
+          a1 = xq[((kt * 2 + 1) * 4 + g) * 4 + i];
+          sa = xsc[kt * 16 + g * 4 + i];
+        }
+        const v8i_t A = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
+        const v8i_t B = {(int)bw[q][0], (int)bw[q][1], (int)bw[q][2], (int)bw[q][3], 0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B, acc, 0, 4, 0, sa, 0, sb[q]);
+      }
+    }
+  };
+  for (int j0 = 0; j0 < nj; j0 += 2 * MXS_ROUND) {
+    const bool second = j0 + MXS_ROUND < nj;
+    if (second) load(bwB, sbB, j0 + MXS_ROUND);
+    run(bwA, sbA, j0);
+    if (second) {
+      if (j0 + 2 * MXS_ROUND < nj) load(bwA, sbA, j0 + 2 * MXS_ROUND);
+      run(bwB, sbB, j0 + MXS_ROUND);
+    }
+  }
+
+  if (corr) {
+    if (nj <= 0) r_issue();                           // (a wave without a tile has not asked yet)
+    const bool on = tok && j0r < a.r;
+    const uint32_t tag = (uint32_t)(launch_tag() & 0xffffffffull);
+    const u32x4_t* mine = (const u32x4_t*)(rfw + (size_t)(g * 4 + (tok ? i : 0)) * 64);
+    float s[8];
+    bool done = false;
+    for (int spin = 0; spin < (1 << 16); ++spin) {
+      vm_wait<0>();                                   // the slots asked for last have landed in LDS
+      bool ok = true;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s[e] = 0.f;
+#pragma unroll
+      for (int part = 0; part < MXS_MAX_PARTS; ++part) {
+        if (part < p.ksplit) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const u32x4_t u = mine[part * 64 + e];
+            const uint32_t v0 = u[0], t0 = u[1], v1 = u[2], t1 = u[3];
+            ok = ok && t0 == tag && t1 == tag;
+            s[2 * e] += __builtin_bit_cast(float, v0);
+            s[2 * e + 1] += __builtin_bit_cast(float, v1);
+          }
+        }
+      }
+      if (!on) ok = true;
+      if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) {
+        done = true;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(2);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // (the reads above are done with the rows)
+      r_issue();
+    }
+    u32x4_t ra = {0, 0, 0, 0};
+    if (on) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        ra[e] = (uint32_t)to_act16<ACT>(s[2 * e]) | ((uint32_t)to_act16<ACT>(s[2 * e + 1]) << 16);
+    }
+    acc = mfma16<ACT>(ra, rbv, acc);
+    if (!done) {
+      const float nan = __builtin_bit_cast(float, 0x7fc00000u);
+      acc = float4_t{nan, nan, nan, nan};
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) part[(w * 64 + l) * 4 + v] = acc[v];
+  __syncthreads();
+  if (w != 0) return;
+  const int row = rb * 16 + i;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int t = 4 * g + v;
+    const float y = ((part[l * 4 + v] + part[(64 + l) * 4 + v]) + part[(128 + l) * 4 + v]) + part[(192 + l) * 4 + v];
+    if (t < a.T && row < m.d_out) {
+      if (a.out_f32) ((float*)m.Y)[(size_t)t * m.ldy + row] = y;
+      else ((uint16_t*)m.Y)[(size_t)t * m.ldy + row] = to_act16<ACT>(y);
     }
   }
 }
@@ -468,7 +707,7 @@ hipError_t launch_mx_prepare(const uint32_t* codes, const uint8_t* scales, int d
 
 hipError_t launch_mx_quantize_x(const void* X, int T, int d_in, int act, uint8_t* codes, uint8_t* scales,
                                 bool fragment_order, hipStream_t st) {
-  const long long n = (long long)T * (d_in / 32) * 8;
+  const long long n = (long long)T * (d_in / 16);
   dim3 grid((unsigned)((n + 255) / 256)), block(256);
   const uint16_t* x = (const uint16_t*)X;
   if (act == GLOWQ_F16) {
@@ -500,7 +739,10 @@ MxWorkspace plan_mx_workspace(const glowq_unit& u) {
   w.kslice = ((u.d_in + 3) / 4 + 511) / 512 * 512;
   w.ks = (u.d_in + w.kslice - 1) / w.kslice;
   w.off_rpart = 0;
-  w.off_xcodes = up256((size_t)w.ks * 16 * (u.r > 0 ? u.r : 0) * 4);
+  // (partial sums [ks][16][r] of the two-launch path, or the one-launch path's slots
+  // [T <= 4][parts <= 4][r] of 8 bytes)
+  const size_t rr = u.r > 0 ? u.r : 0;
+  w.off_xcodes = up256(std::max((size_t)w.ks * 16 * rr * 4, (size_t)MXS_MAX_TOKENS * MXS_MAX_PARTS * rr * 8));
   w.off_xscales = w.off_xcodes + up256((size_t)MX_MAX_TOKENS * u.d_in);
   w.bytes = w.off_xscales + up256((size_t)MX_MAX_TOKENS * (u.d_in / 32));
   return w;
@@ -544,8 +786,64 @@ static hipError_t launch_mx_gemm(const glowq_unit& u, bool restore, char* worksp
   return hipGetLastError();
 }
 
+static int fill_mx_modules(const glowq_unit& u, int rb_per_wg, MxArgs& a) {
+  a.n_modules = u.n_modules;
+  int blocks = 0;
+  for (int i = 0; i < u.n_modules; ++i) {
+    const glowq_module& m = u.modules[i];
+    const long long tiles = (long long)((m.d_out + 15) / 16) * (u.d_in / 128);
+    a.mod[i].codes = (const uint32_t*)m.w_prepared;
+    a.mod[i].scales = (const uint8_t*)m.w_prepared + tiles * 1024;
+    a.mod[i].A = (const uint16_t*)m.A;
+    a.mod[i].Y = m.Y;
+    a.mod[i].d_out = m.d_out;
+    a.mod[i].ldy = m.ldy;
+    a.mod[i].first_block = blocks;
+    blocks += ((m.d_out + 15) / 16 + rb_per_wg - 1) / rb_per_wg;
+  }
+  a.X = (const uint16_t*)u.X;
+  a.T = u.T;
+  a.d_in = u.d_in;
+  a.r = u.r;
+  a.out_f32 = u.out_dtype == GLOWQ_F32;
+  return blocks;
+}
+
+// what the one-launch kernel holds: X of a workgroup in MXS_ITEMS pieces per thread, its
+// codes in LDS
+static bool mx_one_launch(const glowq_unit& u) {
+  return u.T <= MXS_MAX_TOKENS && (long long)u.T * (u.d_in / 16) <= 256 * MXS_ITEMS && u.d_in <= 12288;
+}
+
+static hipError_t launch_mx_small(const glowq_unit& u, bool restore, char* workspace, hipStream_t st) {
+  const MxWorkspace w = plan_mx_workspace(u);
+  const bool corrected = restore && u.r > 0;
+  MxArgs a;
+  const int blocks = fill_mx_modules(u, 1, a);
+  a.xcodes = a.xscales = nullptr;
+  a.Rpart = nullptr;
+  a.ks = 0;
+  ProjArgs p;
+  p.X = (const uint16_t*)u.X;
+  p.B = corrected ? (const uint16_t*)u.B : nullptr;
+  p.T = u.T; p.K = u.d_in; p.r = u.r;
+  // K parts of at least 2048 channels, at most MXS_MAX_PARTS, whole 32-channel steps
+  const int want = std::min(MXS_MAX_PARTS, (u.d_in + 2047) / 2048);
+  p.kslice = ((u.d_in / 32 + want - 1) / want) * 32;
+  p.ksplit = (u.d_in + p.kslice - 1) / p.kslice;
+  p.Rpart = (float*)(workspace + w.off_rpart);
+  p.R32 = nullptr; p.R16 = nullptr; p.ctl = nullptr; p.groups = 1;
+  const int n_prod = corrected ? (u.r * p.ksplit + 3) / 4 : 0;        // one wave per (rank, part)
+  const size_t lds = 4096 + (size_t)(u.d_in / 128) * (512 + 16) + 4 * MXS_MAX_PARTS * 1024;
+  dim3 grid((unsigned)(n_prod + blocks)), block(256);
+  if (u.act_dtype == GLOWQ_F16) k_mx_decode_small<ACT_F16><<<grid, block, lds, st>>>(a, p, n_prod);
+  else k_mx_decode_small<ACT_BF16><<<grid, block, lds, st>>>(a, p, n_prod);
+  return hipGetLastError();
+}
+
 hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace, hipStream_t st) {
   if (u.T > MX_MAX_TOKENS) return launch_mx_gemm(u, restore, workspace, st);
+  if (mx_one_launch(u)) return launch_mx_small(u, restore, workspace, st);
   const MxWorkspace w = plan_mx_workspace(u);
   uint8_t* xcodes = (uint8_t*)(workspace + w.off_xcodes);
   uint8_t* xscales = (uint8_t*)(workspace + w.off_xscales);
@@ -559,34 +857,17 @@ hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace,
   fa.xcodes = xcodes;
   fa.xscales = xscales;
   fa.T = u.T; fa.d_in = u.d_in; fa.r = u.r; fa.ks = w.ks; fa.kslice = w.kslice;
-  const int qblocks = (u.T * (u.d_in / 32) * 8 + MX_FRONT_THREADS - 1) / MX_FRONT_THREADS;
+  const int qblocks = (u.T * (u.d_in / 16) + MX_FRONT_THREADS - 1) / MX_FRONT_THREADS;
   dim3 fgrid((unsigned)(qblocks + (corrected ? w.ks * ((u.r + 15) / 16) : 0)));
   if (f16) k_mx_front<ACT_F16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
   else k_mx_front<ACT_BF16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
   MxArgs a;
-  a.n_modules = u.n_modules;
   const int RB = u.T <= 4 ? 1 : 3;
-  int blocks = 0;
-  for (int i = 0; i < u.n_modules; ++i) {
-    const glowq_module& m = u.modules[i];
-    const long long tiles = (long long)((m.d_out + 15) / 16) * (u.d_in / 128);
-    a.mod[i].codes = (const uint32_t*)m.w_prepared;
-    a.mod[i].scales = (const uint8_t*)m.w_prepared + tiles * 1024;
-    a.mod[i].A = (const uint16_t*)m.A;
-    a.mod[i].Y = m.Y;
-    a.mod[i].d_out = m.d_out;
-    a.mod[i].ldy = m.ldy;
-    a.mod[i].first_block = blocks;
-    blocks += ((m.d_out + 15) / 16 + RB - 1) / RB;
-  }
+  const int blocks = fill_mx_modules(u, RB, a);
   a.xcodes = xcodes;
   a.xscales = xscales;
   a.Rpart = corrected ? rpart : nullptr;
   a.ks = w.ks;
-  a.T = u.T;
-  a.d_in = u.d_in;
-  a.r = u.r;
-  a.out_f32 = u.out_dtype == GLOWQ_F32;
   dim3 grid((unsigned)blocks), block(256);
   if (f16 && RB == 1) k_mx_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a);
   else if (f16) k_mx_decode<ACT_F16, 3><<<grid, block, 0, st>>>(a);

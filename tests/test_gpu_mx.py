@@ -45,6 +45,12 @@ def test_activation_quantiser_bit_exact(act):
     X[4, 31] = 256.0
     X[5, 0:32] = 1.0
     X[5, 7] = 1.99                                                # the block maximum just under a power of two
+    X[6, 0:32] = np.linspace(440, 511, 32) / 256.0                # scaled magnitudes between 448 and 512: clamped
+    X[6, 0] = 1.99
+    if act == "bf16":
+        X[0, 32:96] = rng.standard_normal(64) * 1e-40             # below 2^-126: the scale code clamps at 0
+        X[1, 64:96] = rng.standard_normal(32) * 1e-38
+        X[3, 96:128] = rng.standard_normal(32) * 1e38             # the top of the bfloat16 range
     Xb = O.f64_to_bits(X, act)
     want_c, want_s = MX.mx_quantize(O.bits_to_f64(Xb, act), "e4m3")
     got_c, got_s = gpu_quantize_x(Xb, act)
@@ -87,6 +93,7 @@ class MxDeviceUnit:
 
 
 def make_unit(shape, T, r, act, seed=11):
+    assert r <= min(sum(shape.d_outs), shape.d_in), "the stacked error has fewer singular values than r"
     W = [gen_module_weight(seed, 0, i, o, shape.d_in) for i, o in enumerate(shape.d_outs)]
     X = gen_activations(seed, 0, T, shape.d_in, act, True)
     return MX.build_unit_mx(W, X, r, act)
@@ -143,6 +150,63 @@ def test_full_size_group():
         ref = MX.mx_group_forward(u, True)
         for g, y in zip(got, ref):
             assert rel_err(g, y) <= TOL
+
+
+@pytest.mark.parametrize("act,T,d_in,r", [("f16", 4, 4096, 64), ("bf16", 2, 8192, 128), ("f16", 1, 11008, 40),
+                                          ("bf16", 3, 5376, 8), ("f16", 1, 12288, 16), ("bf16", 1, 128, 8)])
+def test_one_launch_shapes(act, T, d_in, r):
+    # up to four tokens in one launch: the most X a workgroup quantises (four pieces per
+    # thread), two to four K parts of the in-launch projection, several rounds of register
+    # buffers with a ragged last one (86, 42, 96 tiles on four waves), one tile for four waves;
+    # and the two-launch path right beside its limit (3 x 5504 and 4 x 4224 values are too many)
+    shape = UnitShape("g", d_in, (40, 136))                       # (more rows than the largest rank)
+    u = make_unit(shape, T, r, act, seed=21)
+    assert u["B"].shape == (r, d_in)
+    du = MxDeviceUnit(u)
+    for restore in (True, False):
+        got = du.forward(restore)
+        ref = MX.mx_group_forward(u, restore)
+        for g, y in zip(got, ref):
+            assert rel_err(g, y) <= TOL
+
+
+@pytest.mark.parametrize("T,d_in", [(3, 5504), (4, 4224), (2, 12416)])
+def test_few_tokens_beyond_the_one_launch_limits(T, d_in):
+    shape = UnitShape("g", d_in, (40,))
+    u = make_unit(shape, T, 24, "f16", seed=22)
+    du = MxDeviceUnit(u)
+    got = du.forward(True)[0]
+    assert rel_err(got, MX.mx_group_forward(u, True)[0]) <= TOL
+
+
+def test_one_launch_calls_in_a_row_and_graph_replays():
+    # the in-launch hand-off carries a tag of the launch: 300 calls in a row through one
+    # workspace, then a captured graph of three calls replayed five times with eager calls in
+    # between, every result equal to the first one's bits
+    shape = UnitShape("g", 4096, (136, 72))
+    u = make_unit(shape, 2, 64, "f16", seed=23)
+    du = MxDeviceUnit(u)
+    first = du.forward(True)
+    for g, y in zip(first, MX.mx_group_forward(u, True)):
+        assert rel_err(g, y) <= TOL
+    for it in range(300):
+        G.glowq_mx_group_forward(du.desc, 1, du.ws.data_ptr(), du.ws_bytes, stream())
+    assert all(np.array_equal(a, b) for a, b in zip(first, du.forward(True)))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for it in range(3):
+                G.glowq_mx_group_forward(du.desc, 1, du.ws.data_ptr(), du.ws_bytes, side.cuda_stream)
+    for rep in range(5):
+        for y, m in zip(du.Y, du.desc.modules[:len(du.Y)]):
+            y[:du.T, :m.d_out].fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        outs = [y[:du.T, :m.d_out].to(torch.float64).cpu().numpy() for y, m in zip(du.Y, du.desc.modules[:len(du.Y)])]
+        assert all(np.array_equal(a, b) for a, b in zip(first, outs))
+        assert all(np.array_equal(a, b) for a, b in zip(first, du.forward(True)))
 
 
 def test_calls_in_a_row_through_one_workspace():
