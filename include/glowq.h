@@ -306,10 +306,15 @@ glowq_status glowq_factorize_unit(const glowq_unit* u, const float* const* W_mod
  *   [T][d_in]; codes DEVICE uint8 [T][d_in] (E4M3), scales DEVICE uint8 [T][d_in/32].
  * glowq_mx_group_forward: `u` as for glowq_group_forward with modules[i].w_prepared from
  *   glowq_mx_prepare_weights (group_size is ignored); workspace DEVICE, 256-byte aligned,
- *   glowq_mx_workspace_bytes(u) bytes (it depends on T), any contents.  Up to 16 tokens: two
- *   launches on `stream` (activation quantiser and projection; the weight stream).  More
- *   tokens: the activation quantiser, the stand-alone projection when restored, and a tiled
- *   product (128 tokens x 128 rows per workgroup). */
+ *   glowq_mx_workspace_bytes(u) bytes (it depends on T), any contents.  Up to 4 tokens (and
+ *   T d_in <= 16384, d_in <= 12288): ONE launch on `stream`; the projection's workgroups lead
+ *   the grid and hand R over inside the launch, every hand-off validated by a tag of the
+ *   launch (nothing to reset, graph replays included), every wait bounded; should a wait ever
+ *   expire, the rows concerned are stored as NaN rather than without their correction.  Up to
+ *   16 tokens otherwise: two launches (activation quantiser and projection; the weight
+ *   stream).  More tokens: the activation quantiser, the stand-alone projection when restored,
+ *   and a tiled product (128 tokens x 128 rows per workgroup).  Calls that share a workspace
+ *   must not overlap. */
 glowq_status glowq_mx_prepared_bytes(int32_t d_out, int32_t d_in, size_t* bytes);
 glowq_status glowq_mx_prepare_weights(const uint32_t* codes, const uint8_t* scales, int32_t d_out,
                                       int32_t d_in, void* w_prepared, void* stream);

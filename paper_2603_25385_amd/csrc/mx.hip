@@ -204,13 +204,17 @@ __global__ void __launch_bounds__(MX_FRONT_THREADS) k_mx_front(MxFrontArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// the forward.  One workgroup (4 waves) per RB consecutive 16-row blocks of one module (one
-// for up to four tokens; three beyond, so that an activation tile in registers serves three
-// weight tiles); wave w takes the 128-channel tiles w, w + 4, ... and the correction step of
+// the forward in two launches (5 to 16 tokens, and fewer tokens of shapes the one-launch
+// kernel below does not hold).  One workgroup (4 waves) per RB consecutive 16-row blocks of
+// one module; wave w takes the 128-channel tiles w, w + 4, ... and the correction step of
 // ranks 32 w ..; the four partial tiles of a row block meet in LDS and wave q stores block q.
+// Launched with RB = 1: with the activations in fragment order (a wave's fetch of a tile is
+// two contiguous KiB) three times the waves in flight are worth more than an activation tile
+// in registers that serves three weight tiles (RB = 3: 16.3 instead of 15.7 us at sixteen
+// tokens on a 3 x 4096 x 4096 unit).
 // Measured no faster: sixteen waves per workgroup; a walk over the tiles that starts at
 // another place in every workgroup.  Measured slower: sixteen slices of the projection instead
-// of four (15.0 instead of 13.4 us at one token).  Measured much slower (24 us):
+// of four.  Measured much slower (24 instead of 13 us at one token):
 // letting the projection workgroup that finishes last add the slices into R behind a
 // device-scope fence, so that the correction step reads R instead of sixteen partial sums.
 // ---------------------------------------------------------------------------------------
@@ -862,17 +866,14 @@ hipError_t launch_mx_forward(const glowq_unit& u, bool restore, char* workspace,
   if (f16) k_mx_front<ACT_F16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
   else k_mx_front<ACT_BF16><<<fgrid, dim3(MX_FRONT_THREADS), 0, st>>>(fa);
   MxArgs a;
-  const int RB = u.T <= 4 ? 1 : 3;
-  const int blocks = fill_mx_modules(u, RB, a);
+  const int blocks = fill_mx_modules(u, 1, a);
   a.xcodes = xcodes;
   a.xscales = xscales;
   a.Rpart = corrected ? rpart : nullptr;
   a.ks = w.ks;
   dim3 grid((unsigned)blocks), block(256);
-  if (f16 && RB == 1) k_mx_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a);
-  else if (f16) k_mx_decode<ACT_F16, 3><<<grid, block, 0, st>>>(a);
-  else if (RB == 1) k_mx_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a);
-  else k_mx_decode<ACT_BF16, 3><<<grid, block, 0, st>>>(a);
+  if (f16) k_mx_decode<ACT_F16, 1><<<grid, block, 0, st>>>(a);
+  else k_mx_decode<ACT_BF16, 1><<<grid, block, 0, st>>>(a);
   return hipGetLastError();
 }
 
