@@ -140,6 +140,17 @@ glowq_status glowq_prepare_weights(const uint32_t* wq, const uint16_t* scales,
  * unique per kernel launch, so nothing in the buffer ever has to be reset.  Calls
  * that may overlap in time need separate workspaces.
  *
+ * A unit of more than 64 tokens whose contraction is long (d_in >= 8192) on few tiles
+ * (at most 128 tiles of 128 tokens x 256 rows, 192 rows for bfloat16) is multiplied in two
+ * to four slices of K, so that its few workgroups do not each run the whole contraction
+ * while the chip idles: every slice leaves an fp32 partial result in the unit's slice of
+ * the workspace ([slice][T][d_out rounded up to 4] per module, counted by
+ * glowq_workspace_bytes), and a second kernel adds them in slice order and writes Y.  The
+ * rule reads T, d_in and the modules' d_out only: size the workspace from descriptors that
+ * carry them (pointers may be NULL); a call whose workspace is smaller than what the unit's
+ * shapes ask for is refused with GLOWQ_ERR_WORKSPACE.  Calls without a workspace
+ * (no unit restored) and glowq_group_forward_static multiply such a unit in one piece.
+ *
  * Unit i's slice starts at the sum of glowq_workspace_bytes of the units before it
  * (in the order of the forward call).  Word 3 of a slice (byte offset 12) is the
  * unit's status word: nonzero means that a bounded in-kernel wait for the projection
@@ -177,8 +188,9 @@ glowq_status glowq_group_forward(const glowq_unit* u, int32_t restore, void* wor
  * workspace: the scratch is a file-scope device array of GLOWQ_STATIC_SCRATCH_BYTES
  * inside the library, one per GPU, held until the process ends.  The call allocates
  * nothing (no hipMalloc / hipFree, no allocating library routine) and never
- * synchronises; a unit whose scratch need (glowq_workspace_bytes) exceeds the array is
- * refused with GLOWQ_ERR_WORKSPACE.  Every call on a GPU shares that GPU's array:
+ * synchronises; a unit whose scratch need (glowq_workspace_bytes, less the partial
+ * results of K slices, which this call does not use) exceeds the array is refused with
+ * GLOWQ_ERR_WORKSPACE.  Every call on a GPU shares that GPU's array:
  * calls that may overlap in time on one GPU race (use glowq_group_forward with
  * separate workspaces for those), and the unit's status word is not observable.
  * Results are those of glowq_group_forward. */

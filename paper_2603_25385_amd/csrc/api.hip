@@ -77,7 +77,9 @@ UnitWorkspace plan_unit_workspace(const glowq_unit& u, char* base) {
   size_t rpart = (u.r > 0) ? (size_t)slabs * u.T * u.r * (is_decode(u.T) ? 8 : 4) : 0;
   w.off_r16 = align_up(w.off_rpart + rpart, 256);
   size_t r16 = (u.r > 0) ? (size_t)u.T * u.r * 2 : 0;
-  w.bytes = align_up(w.off_r16 + r16, 256);
+  w.off_splitk = align_up(w.off_r16 + r16, 256);
+  w.splitk_bytes = is_decode(u.T) ? 0 : prefill_splitk_bytes(u);
+  w.bytes = align_up(w.off_splitk + w.splitk_bytes, 256);
   return w;
 }
 
@@ -143,7 +145,7 @@ static inline glowq_status hip_status(hipError_t e) {
 // Enqueue all units: decode-sized units one launch each (projection inside); prefill-sized
 // units in batches of compatible neighbours, projections first, then one GEMM launch.
 static glowq_status forward_all(const glowq_unit* units, int n_units, const uint8_t* mask,
-                                char* workspace, hipStream_t st) {
+                                char* workspace, hipStream_t st, bool allow_split = true) {
   size_t off = 0;
   int i = 0;
   while (i < n_units) {
@@ -183,7 +185,7 @@ static glowq_status forward_all(const glowq_unit* units, int n_units, const uint
       ++i;
     }
     // (the projections of the batch run as the first tiles of the same launch)
-    hipError_t e = launch_prefill_multi(batch, bws, corr, nb, st);
+    hipError_t e = launch_prefill_multi(batch, bws, corr, nb, allow_split && workspace != nullptr, st);
     if (e != hipSuccess) return hip_status(e);
   }
   return GLOWQ_OK;
@@ -310,8 +312,9 @@ glowq_status glowq_group_forward_static(const glowq_unit* u, int32_t restore, vo
   if (s != GLOWQ_OK) return s;
   uint8_t mask = restore ? 1 : 0;
   if (!corrected) return forward_all(u, 1, &mask, nullptr, (hipStream_t)stream);
+  // (the static array holds the projection's words; a long contraction is not cut here)
   const UnitWorkspace plan = plan_unit_workspace(*u, nullptr);
-  if (plan.bytes > (size_t)GLOWQ_STATIC_SCRATCH_BYTES) return GLOWQ_ERR_WORKSPACE;
+  if (plan.off_splitk > (size_t)GLOWQ_STATIC_SCRATCH_BYTES) return GLOWQ_ERR_WORKSPACE;
   void* scratch = nullptr;
   hipError_t e = static_scratch(&scratch);
   if (e != hipSuccess) return hip_status(e);
@@ -320,7 +323,7 @@ glowq_status glowq_group_forward_static(const glowq_unit* u, int32_t restore, vo
   // node, so that the call can be captured into a graph)
   e = launch_fill_zero(scratch, plan.ctl_bytes, (hipStream_t)stream);
   if (e != hipSuccess) return hip_status(e);
-  return forward_all(u, 1, &mask, (char*)scratch, (hipStream_t)stream);
+  return forward_all(u, 1, &mask, (char*)scratch, (hipStream_t)stream, false);
 }
 
 glowq_status glowq_block_forward(const glowq_unit* units, int32_t n_units,

@@ -14,6 +14,8 @@ struct UnitWorkspace {
   size_t off_rpart;   // partial sums of the projection (T <= 32: 8-byte slots {fp32, launch tag},
                       // [T][ksplit][r]; T > 32 and glowq_shared_proj: fp32 [part][T][r])
   size_t off_r16;     // T > 32: R in the activation type, [T][r]
+  size_t off_splitk;  // T > 64: fp32 slabs of a long contraction cut into K slices (0 bytes if not cut)
+  size_t splitk_bytes;
   size_t ctl_bytes;   // leading bytes that must be zero between calls
   int ksplit;         // K slices of the projection
   int kslice;         // channels per slice (multiple of 32)
@@ -96,6 +98,8 @@ bool prefill_compatible(const glowq_unit& a, const glowq_unit& b);
 int prefill_max_units();
 int prefill_max_modules();
 hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorkspace* ws,
-                                const bool* restore, int n_units, hipStream_t st);
+                                const bool* restore, int n_units, bool allow_split, hipStream_t st);
+int prefill_k_slices(const glowq_unit& u);
+size_t prefill_splitk_bytes(const glowq_unit& u);
 
 }  // namespace glowq

@@ -15,6 +15,7 @@
 // stage are placed by hand (see the kernel).  D is [row][token], so a lane ends up with
 // four consecutive rows of one token and stores them with one 8- or 16-byte write.
 #include <type_traits>
+#include <algorithm>
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -64,6 +65,13 @@ struct PfModule {
   int unit;              // index into PrefillArgs::unit
   int wg_start;          // first workgroup of this module in the grid
   int n_ntiles;          // row tiles of the module; its workgroups: n_ntiles * unit.n_mtiles
+  // A module of a long contraction may stand here several times, once per slice of K: each
+  // entry multiplies the K tiles [kt0, kt0 + nkt) and leaves an fp32 partial result (Y, ldy:
+  // its slab of the workspace); the first entry carries the correction; k_splitk_sum adds
+  // the slabs and writes the module's output.
+  int kt0, nkt;
+  int corr;              // this entry applies the correction (if the unit is restored)
+  int out_f32;           // what Y holds: fp32, or the activation type
 };
 
 struct PrefillArgs {
@@ -359,7 +367,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, kq = lane >> 4;
-  const int ktiles = U.K >> 7;
+  const int ktiles = M.nkt;            // K tiles of this entry (all of them unless K is split)
 
   // this wave's four 16-row blocks; blocks past the module's last one are computed from
   // a clamped (valid) block and never stored, so that the hot loop carries no branch
@@ -367,7 +375,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   const uint32_t* wt[RB];
 #pragma unroll
   for (int b = 0; b < RB; ++b)
-    wt[b] = uniform_ptr(M.rec + (size_t)min(nb0 + b, M.rows16 - 1) * ktiles * RW);
+    wt[b] = uniform_ptr(M.rec + ((size_t)min(nb0 + b, M.rows16 - 1) * (U.K >> 7) + M.kt0) * RW);
 
   // X staging, global memory straight into LDS (no registers in between): the wave's
   // load i covers rows XR i + 8 wave + (lane >> 3), one 16-byte chunk per lane, 1 KiB
@@ -377,7 +385,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   const int tok0 = mt * MT;
   // byte offsets of this thread's rows from the tile's first row (below 2^31: MT rows of
   // at most 2^16 channels)
-  const uint16_t* xtile = uniform_ptr(U.X + (size_t)tok0 * U.K);
+  const uint16_t* xtile = uniform_ptr(U.X + (size_t)tok0 * U.K + (size_t)M.kt0 * 128);
   uint32_t xoff[XI];
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
@@ -599,7 +607,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
   // R tile then takes the X path (straight into the idle ring, swizzled the same way,
   // with device-coherent loads: other compute units wrote it during this launch), so
   // that nothing in here waits for memory more than twice.
-  if (U.restore) {
+  if (U.restore && M.corr) {
     const int rstages = (U.r + 63) >> 6;                       // 1 or 2
     u32x4_t af[2][2][RB];
 #pragma unroll
@@ -684,7 +692,7 @@ __global__ void __launch_bounds__(PfShape<ACT>::WAVES * 64, PfShape<ACT>::OCC) k
       if (tok >= U.T) continue;
       const size_t off = (size_t)tok * M.ldy + row;
       const float4_t v = acc[b][mb];
-      if (a.out_f32) {
+      if (M.out_f32) {
         *(float4_t*)((float*)M.Y + off) = v;
       } else {
         uint2 pk;
@@ -707,6 +715,58 @@ static hipError_t launch_prefill_t(const PrefillArgs& a, int n_wgs, int G, hipSt
 
 static inline int prefill_mb(int T) { return T <= 64 ? 4 : 8; }
 
+// Slices of K for a unit whose tiles would each run a long contraction while most of the chip
+// idles: at least 8192 channels on at most 128 tiles (a quarter of the workgroups the chip
+// holds), cut into slices of about 4096 channels, at most 4.  A unit's own shapes decide, so
+// that its workspace can be planned without knowing what else shares the launch.  Measured
+// on a block of 512 tokens (4096 / 14336 / 1024): the 64 tiles of the down projection, 3.5
+// times the others' contraction each, set the launch's duration.
+int prefill_k_slices(const glowq_unit& u) {
+  if (u.T <= 64) return 1;
+  const int ktiles = u.d_in / 128;
+  if (ktiles < 64) return 1;
+  const int tile_blocks = u.act_dtype == GLOWQ_F16 ? PfShape<ACT_F16>::TILE_BLOCKS : PfShape<ACT_BF16>::TILE_BLOCKS;
+  const long long n_mtiles = (u.T + 127) / 128;
+  long long tiles = 0;
+  if (!u.modules) return 1;
+  for (int i = 0; i < u.n_modules; ++i)
+    tiles += (((u.modules[i].d_out + 15) / 16 + tile_blocks - 1) / tile_blocks) * n_mtiles;
+  if (tiles > 128) return 1;
+  return std::min(4, ktiles / 32);
+}
+// fp32 slab of one slice: [T][ldp], ldp = d_out rounded up to 4 (16-byte stores)
+static inline size_t splitk_ldp(int d_out) { return (size_t)(d_out + 3) / 4 * 4; }
+size_t prefill_splitk_bytes(const glowq_unit& u) {
+  const int S = prefill_k_slices(u);
+  if (S <= 1) return 0;
+  size_t b = 0;
+  for (int i = 0; i < u.n_modules; ++i) b += (size_t)S * u.T * splitk_ldp(u.modules[i].d_out) * 4;
+  return b;
+}
+
+// Y[t][row] = sum over the slices' slabs, in slice order, rounded once to the output type
+template <int ACT>
+__global__ void k_splitk_sum(const float* __restrict__ P, int S, int T, int d_out, int ldp, void* Y, int ldy,
+                             int out_f32) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;   // (token, 4 rows)
+  const int per = ldp >> 2;
+  if (idx >= (long long)T * per) return;
+  const int t = (int)(idx / per), row = 4 * (int)(idx - (long long)t * per);
+  float4_t v = *(const float4_t*)(P + (size_t)t * ldp + row);
+  for (int sl = 1; sl < S; ++sl) {
+    const float4_t q = *(const float4_t*)(P + ((size_t)sl * T + t) * ldp + row);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += q[e];
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    if (row + e < d_out) {
+      if (out_f32) ((float*)Y)[(size_t)t * ldy + row + e] = v[e];
+      else ((uint16_t*)Y)[(size_t)t * ldy + row + e] = to_act16<ACT>(v[e]);
+    }
+  }
+}
+
 bool prefill_compatible(const glowq_unit& a, const glowq_unit& b) {
   return a.act_dtype == b.act_dtype && a.out_dtype == b.out_dtype &&
          a.group_size == b.group_size && prefill_mb(a.T) == prefill_mb(b.T);
@@ -717,7 +777,7 @@ int prefill_max_modules() { return PF_MAX_MODS; }
 
 // units[i] uses workspace slice ws[i]; restore[i] says whether its R16 is valid.
 hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorkspace* ws,
-                                const bool* restore, int n_units, hipStream_t st) {
+                                const bool* restore, int n_units, bool allow_split, hipStream_t st) {
   PrefillArgs a;
   const glowq_unit& u0 = *units[0];
   const int MB = prefill_mb(u0.T);
@@ -747,6 +807,20 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
   }
   a.n_proj_wgs = n_proj;
   a.n_units = n_units;
+  // K slices per unit: where the unit's shapes ask for them, its workspace has the slabs and
+  // the module table has room
+  int slices[PF_MAX_UNITS];
+  {
+    int total = 0;
+    for (int ui = 0; ui < n_units; ++ui) total += units[ui]->n_modules;
+    for (int ui = 0; ui < n_units; ++ui) {
+      const glowq_unit& u = *units[ui];
+      int S = (allow_split && ws[ui].base && ws[ui].splitk_bytes > 0) ? prefill_k_slices(u) : 1;
+      if (total + (S - 1) * u.n_modules > PF_MAX_MODS) S = 1;
+      total += (S - 1) * u.n_modules;
+      slices[ui] = S;
+    }
+  }
   int n_mods = 0, wg = n_proj;
   for (int oi = 0; oi < n_units; ++oi) {
     const int ui = order[oi];
@@ -765,20 +839,36 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
     pu.r = u.r;
     pu.restore = (restore[ui] && u.r > 0) ? 1 : 0;
     pu.n_mtiles = (u.T + 16 * MB - 1) / (16 * MB);
+    const int S = slices[ui], ktiles = u.d_in / 128;
+    float* slab = (S > 1) ? (float*)(wsb + ws[ui].off_splitk) : nullptr;
     for (int i = 0; i < u.n_modules; ++i) {
       const glowq_module& m = u.modules[i];
       PreparedView v = prepared_view(m.w_prepared, m.d_out, u.d_in, u.group_size);
-      PfModule& pm = a.mod[n_mods++];
-      pm.rec = v.base;
-      pm.A = (const uint16_t*)m.A;
-      pm.Y = m.Y;
-      pm.d_out = m.d_out;
-      pm.ldy = m.ldy;
-      pm.rows16 = v.rows16;
-      pm.unit = oi;
-      pm.wg_start = wg;
-      pm.n_ntiles = (v.rows16 + tile_blocks - 1) / tile_blocks;
-      wg += pu.n_mtiles * pm.n_ntiles;
+      for (int sl = 0; sl < S; ++sl) {
+        PfModule& pm = a.mod[n_mods++];
+        pm.rec = v.base;
+        pm.A = (const uint16_t*)m.A;
+        pm.d_out = m.d_out;
+        pm.rows16 = v.rows16;
+        pm.unit = oi;
+        pm.wg_start = wg;
+        pm.n_ntiles = (v.rows16 + tile_blocks - 1) / tile_blocks;
+        pm.kt0 = (int)((long long)ktiles * sl / S);
+        pm.nkt = (int)((long long)ktiles * (sl + 1) / S) - pm.kt0;
+        pm.corr = sl == 0;
+        if (S > 1) {
+          const size_t ldp = splitk_ldp(m.d_out);
+          pm.Y = slab + (size_t)sl * u.T * ldp;
+          pm.ldy = (int)ldp;
+          pm.out_f32 = 1;
+        } else {
+          pm.Y = m.Y;
+          pm.ldy = m.ldy;
+          pm.out_f32 = (u.out_dtype == GLOWQ_F32) ? 1 : 0;
+        }
+        wg += pu.n_mtiles * pm.n_ntiles;
+      }
+      if (S > 1) slab += (size_t)S * u.T * splitk_ldp(m.d_out);
     }
   }
   for (int i = n_units; i < PF_MAX_UNITS; ++i) a.unit[i] = a.unit[0];
@@ -786,11 +876,32 @@ hipError_t launch_prefill_multi(const glowq_unit* const* units, const UnitWorksp
   a.n_mods = n_mods;
   a.out_f32 = (u0.out_dtype == GLOWQ_F32) ? 1 : 0;
   const bool f16 = (u0.act_dtype == GLOWQ_F16);
+  hipError_t err;
   if (MB == 4)
-    return f16 ? launch_prefill_t<ACT_F16, 4>(a, wg, u0.group_size, st)
-               : launch_prefill_t<ACT_BF16, 4>(a, wg, u0.group_size, st);
-  return f16 ? launch_prefill_t<ACT_F16, 8>(a, wg, u0.group_size, st)
-             : launch_prefill_t<ACT_BF16, 8>(a, wg, u0.group_size, st);
+    err = f16 ? launch_prefill_t<ACT_F16, 4>(a, wg, u0.group_size, st)
+              : launch_prefill_t<ACT_BF16, 4>(a, wg, u0.group_size, st);
+  else
+    err = f16 ? launch_prefill_t<ACT_F16, 8>(a, wg, u0.group_size, st)
+              : launch_prefill_t<ACT_BF16, 8>(a, wg, u0.group_size, st);
+  if (err != hipSuccess) return err;
+  // the sliced units' outputs
+  for (int ui = 0; ui < n_units; ++ui) {
+    const int S = slices[ui];
+    if (S <= 1) continue;
+    const glowq_unit& u = *units[ui];
+    const float* slab = (const float*)(ws[ui].base + ws[ui].off_splitk);
+    for (int i = 0; i < u.n_modules; ++i) {
+      const glowq_module& m = u.modules[i];
+      const int ldp = (int)splitk_ldp(m.d_out);
+      const long long n = (long long)u.T * (ldp / 4);
+      dim3 grid((unsigned)((n + 255) / 256)), block(256);
+      const int of32 = u.out_dtype == GLOWQ_F32 ? 1 : 0;
+      if (f16) k_splitk_sum<ACT_F16><<<grid, block, 0, st>>>(slab, S, u.T, m.d_out, ldp, m.Y, m.ldy, of32);
+      else k_splitk_sum<ACT_BF16><<<grid, block, 0, st>>>(slab, S, u.T, m.d_out, ldp, m.Y, m.ldy, of32);
+      slab += (size_t)S * u.T * ldp;
+    }
+  }
+  return hipGetLastError();
 }
 
 }  // namespace glowq

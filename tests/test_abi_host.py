@@ -112,6 +112,24 @@ def test_workspace_status_argument_checks():
         assert e.value.status == status
 
 
+def test_workspace_holds_the_partial_results_of_k_slices():
+    """A long contraction on few tiles is multiplied in slices of K (glowq.h, workspace): the
+    unit's workspace then holds an fp32 slab [T][d_out] per slice and module; the rule reads
+    the shapes only, and a forward call with less than that is refused before any launch."""
+    plain = G.glowq_workspace_bytes([_unit(T=512, d_in=4096, d_out=4096, ldy=4096, group_size=128)])
+    for d_in, slices in [(8192, 2), (11008, 2), (14336, 3), (16384, 4), (32768, 4)]:
+        cut = G.glowq_workspace_bytes([_unit(T=512, d_in=d_in, d_out=4096, ldy=4096, group_size=128)])
+        assert cut - plain >= slices * 512 * 4096 * 4 and cut - plain < (slices + 1) * 512 * 4096 * 4
+    # not cut: few tokens, a short contraction, more than 128 tiles
+    for kw in [dict(T=64, d_in=14336, d_out=4096, ldy=4096), dict(T=512, d_in=8064, d_out=4096, ldy=4096),
+               dict(T=1024, d_in=14336, d_out=5120, ldy=5120)]:
+        assert G.glowq_workspace_bytes([_unit(group_size=128, **kw)]) < plain * 3
+    u = _unit(T=512, d_in=14336, d_out=4096, ldy=4096, group_size=128)
+    with pytest.raises(G.GlowqError) as e:
+        G.glowq_group_forward(u, True, 0x10000, plain, 0)
+    assert e.value.status == G.GLOWQ_ERR_WORKSPACE
+
+
 def test_layerwise_argument_checks():
     """The layer-wise mode forwards the unit's modules as one-module units: its workspace
     is the sum of theirs, and every module needs a right factor of its own."""

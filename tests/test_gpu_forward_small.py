@@ -85,6 +85,29 @@ def test_long_contraction(act, T):
         ws.assert_idle()
 
 
+@pytest.mark.parametrize("act,d_in,T,out", [("f16", 8192, 70, "f32"), ("bf16", 8320, 130, "act"),
+                                           ("f16", 12288, 200, "act"), ("bf16", 16384, 65, "f32")])
+def test_long_contraction_in_k_slices(act, d_in, T, out):
+    # 8192 channels and more on a handful of tiles: the launch cuts K into two to four slices
+    # (65 tiles into 32 + 33, 96 into three, 128 into four), each slice leaves an fp32 slab in
+    # the workspace, the first carries the correction, a second kernel adds them in slice
+    # order; ragged rows (40: a slab row of 40 floats), padded output rows, restored and not,
+    # twice through one workspace, and against a call that cannot cut (no workspace)
+    shape = UnitShape("s", d_in, (40, 264))
+    u = recipe_unit(O, 1, 0, T, r=24, shape=shape, act=act, G=128)
+    du = DeviceUnit(u, out, 8)
+    ws = Workspace([du.desc])
+    tol = TOL + (ULP[act] if out == "act" else 0.0)
+    for restore in (True, False, True):
+        du.clear()
+        G.glowq_group_forward(du.desc, restore, ws.ptr, ws.bytes, stream())
+        _check(du.outputs(), O.group_forward(u, restore), tol)
+        ws.assert_idle()
+    du.clear()
+    G.glowq_group_forward(du.desc, False, 0, 0, stream())
+    _check(du.outputs(), O.group_forward(u, False), tol)
+
+
 @pytest.mark.parametrize("T", [4, 96])
 def test_masked_unit_equals_rank_zero_bitwise(T):
     u = recipe_unit(O, 1, 0, T)
