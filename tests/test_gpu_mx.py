@@ -124,11 +124,13 @@ def test_ranks_and_16_bit_output(r):
     assert rel_err(got, ref) <= TOL + ULP["bf16"]
 
 
-def test_main_product_is_exact_on_small_integers():
+@pytest.mark.parametrize("T", [4, 9, 16])
+def test_main_product_is_exact_on_small_integers(T):
     # weights and activations that sit on the grids with small magnitudes: every partial sum
-    # is an integer multiple of 2^-10 below 2^14, so fp32 accumulation is exact
+    # is an integer multiple of 2^-10 below 2^14, so fp32 accumulation is exact (one launch at
+    # four tokens, two launches with the activations in fragment order beyond)
     rng = np.random.default_rng(13)
-    d, T = 256, 4
+    d = 256
     Wg = rng.choice([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], size=(16, d)) * rng.choice([-1, 1], size=(16, d))
     Xg = rng.integers(-8, 9, size=(T, d)).astype(np.float64)
     Xg[:, ::32] = 8.0                                              # every block's maximum: one scale, no clamping
