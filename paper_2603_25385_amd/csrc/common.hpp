@@ -364,6 +364,13 @@ __device__ inline void lds_dma4(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
                : : "v"(gptr), "s"(m) : "memory", "m0");
 }
+// lds_dma4 at device scope: not served from an L2 line that may hold what another compute
+// unit's workgroup wrote before its latest store (the XCDs' L2s are not coherent with each other)
+__device__ inline void lds_dma4_coherent(const void* gptr, uint32_t lds_base) {
+  const uint32_t m = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off sc1"
+               : : "v"(gptr), "s"(m) : "memory", "m0");
+}
 __device__ inline uint32_t lds_address(const void* p) {
   return __builtin_amdgcn_readfirstlane(
       (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p);

@@ -360,12 +360,15 @@ __device__ inline void decode_stream_small(const DecodeArgs& a, const ModuleArgs
 // every one carries THIS launch's tag, adds the parts in part order and rounds to the
 // activation type: no LDS, no workgroup barrier.
 //
-// The first attempt uses ordinary (L2-cached) loads and is issued during the weight
-// stream, so its latency is hidden: the projection waves publish within the first couple
-// of microseconds.  A slot read too early shows an older tag; then, and only then, the
-// retries use device-scope loads, which cannot be served from a stale cached line.  The
-// wait is bounded (the projection waves wait for nothing, so it cannot expire); if it
-// did, ctl->status is set and the correction is left out rather than hang.
+// The first attempt is issued during the weight stream, so its latency is hidden: the
+// projection waves publish within the first couple of microseconds.  It is a device-scope
+// load like the retries: an ordinary load can be served from a line that this XCD's L2
+// still holds from an earlier launch through the same workspace (always, when the same
+// operands are used launch after launch), which then costs a second fetch at the end of the
+// stream (one token on a 3 x 4096 x 4096 unit: 9.4 -> 8.9 us).  A slot read too early shows
+// an older tag and is read again.  The wait is bounded (the projection waves wait for
+// nothing, so it cannot expire); if it did, ctl->status is set and the correction is left
+// out rather than hang.
 constexpr int DEC_MAX_PARTS = 4;   // K parts of the direct projection (see plan_unit_workspace)
 struct RFetch {
   u32x4_t v[DEC_MAX_PARTS][4];     // per part: 8 slots = 64 bytes
@@ -391,7 +394,7 @@ __device__ inline void r_fetch_issue(const DecodeArgs& a, const ProjArgs& p, int
   const uint32_t dst = lds_address(lds_rf_wave);
   for (int t = 0; t < a.T; ++t)
     for (int part = 0; part < p.ksplit; ++part)
-      if (in) lds_dma4(src + (size_t)(t * p.ksplit + part) * a.r * 2, dst + (t * DEC_MAX_PARTS + part) * 256);
+      if (in) lds_dma4_coherent(src + (size_t)(t * p.ksplit + part) * a.r * 2, dst + (t * DEC_MAX_PARTS + part) * 256);
 }
 __device__ inline void r_fetch_take(const DecodeArgs& a, const ProjArgs& p, int lane,
                                     const uint32_t* lds_rf_wave, RFetch& f) {
@@ -434,7 +437,7 @@ __device__ inline bool r_fetch_finish(const ProjArgs& p, RFetch& f, u32x4_t& rf)
       done = true;
       break;
     }
-    __builtin_amdgcn_s_sleep(32);
+    __builtin_amdgcn_s_sleep(2);
     // again, past every cache that may hold a stale copy
 #pragma unroll
     for (int part = 0; part < DEC_MAX_PARTS; ++part) {
