@@ -173,6 +173,29 @@ def test_block_forward_with_mask():
         ws.assert_idle()
 
 
+def test_block_forward_with_k_slices_and_a_full_module_table():
+    """Seven units of 70 tokens in one call, five of them with a contraction long enough to be
+    cut into K slices (four slices at 16384 channels, two at 8192): the launch's table of 16
+    module entries has room for some of the slices only, so units cut four ways, units cut two
+    ways or not at all and ordinary units share a launch (longest contraction first, which is
+    not the order of the call); masked and restored units, twice through one workspace."""
+    shapes = [UnitShape("a", 256, (64, 40)), UnitShape("d1", 16384, (40,)), UnitShape("d2", 8192, (40, 24)),
+              UnitShape("d3", 16384, (24,)), UnitShape("b", 384, (136,)), UnitShape("d4", 16384, (40,)),
+              UnitShape("d5", 8192, (72,))]
+    mask = [1, 1, 0, 1, 1, 0, 1]
+    units = [recipe_unit(O, 1, 0, 70, seed=30 + i, shape=sh, r=16, G=128) for i, sh in enumerate(shapes)]
+    dus = [DeviceUnit(u) for u in units]
+    ws = Workspace([d.desc for d in dus])
+    refs = [O.group_forward(u, bool(f)) for u, f in zip(units, mask)]
+    for _ in range(2):
+        for d in dus:
+            d.clear()
+        G.glowq_block_forward([d.desc for d in dus], bytes(mask), ws.ptr, ws.bytes, stream())
+        for d, ref in zip(dus, refs):
+            _check(d.outputs(), ref, TOL)
+        ws.assert_idle()
+
+
 def test_block_forward_mixed_token_counts():
     """Thirteen few-token units of different token classes and gating in one call: the
     decode launches batch up to eight compatible units and must split at every change
