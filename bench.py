@@ -157,6 +157,8 @@ def run_workload(name, args, torch, want_cpu_baseline):
                                 cfg["restore_fraction"])[:n_units]
     else:
         mask = np.ones(n_units, np.uint8)
+    if args.unit is not None:          # one unit of the block by itself
+        shapes, mask, n_units = [shapes[args.unit]], mask[args.unit:args.unit + 1], 1
     if args.restore != "workload":
         mask = np.full(n_units, 1 if args.restore == "all" else 0, np.uint8)
     decode = bound == "hbm"
@@ -272,7 +274,7 @@ def run_workload(name, args, torch, want_cpu_baseline):
                     frac=tfs / MFMA_PEAK_TFLOPS)
     roof["traffic"] = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{name}.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and args.unit is None and args.restore == "workload":
         with open(tpath) as f:
             roof["traffic"] = json.load(f).get("hbm_bytes_per_step")
     roof["traffic_source"] = f"profiles/{name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)"
@@ -281,7 +283,8 @@ def run_workload(name, args, torch, want_cpu_baseline):
         "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": act, "data": "synthetic",
-        "config": {"workload": f"{cfg['name']} T={T} r={r} G={Gs} ({name})",
+        "config": {"workload": f"{cfg['name']} T={T} r={r} G={Gs} ({name})" +
+                               (f", unit {args.unit} alone" if args.unit is not None else ""),
                    "units": n_units, "restored_units": int(mask.sum()), "rotating_copies": n_rot,
                    "launch": args.mode},
         "us_per_step": ms_per_step * 1e3,
@@ -459,6 +462,9 @@ def main() -> int:
                     help="graph: the K timed steps are captured once into a HIP graph")
     ap.add_argument("--rot", type=int, default=None, help="distinct operand copies to rotate over")
     ap.add_argument("--layers", type=int, default=None, help="cfg5 only: layers to instantiate")
+    ap.add_argument("--unit", type=int, default=None,
+                    help="time one unit of the workload's block by itself (0 q/k/v, 1 o, 2 gate/up, "
+                         "3 down), e.g. --workload cfg4 --unit 3: a long contraction on few tiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-checks", action="store_true",
                     help="report the status / parity checks but do not fail on them (tuning runs "
