@@ -338,8 +338,9 @@ __global__ void __launch_bounds__(256) k_mx_decode(MxArgs a) {
 // rank and K part, proj_wave_direct: every partial sum is published as one 8-byte slot
 // {fp32 bits, low word of the launch tag} that validates itself); the others take one 16-row
 // block each and do everything else themselves: every workgroup quantises the whole X into
-// LDS (T d_in values, two to eight hundred instructions per thread, under the latency of its
-// own weight loads, which are issued first but behind the loads of X: loads return in order),
+// LDS (T d_in values, one to four 16-value pieces of some eighty instructions per thread,
+// under the latency of its own weight loads, which go out right behind the loads of X: loads
+// return in order, so X is there first),
 // its four waves take the 128-channel tiles round robin, eight tiles per register buffer and
 // two buffers in flight, and each wave asks for the slots of its own correction step in the
 // middle of its first round (global -> LDS, device scope) and checks them after its stream.
